@@ -1,0 +1,291 @@
+"""Pins for the oracle's replay memory: tree invariants after every operation, the tree descent
+against brute force in Python integers, exact sampling frequencies, importance weights, FIFO
+eviction, duplicate and stale updates.  Expected values never come from the function under test."""
+import bisect
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from conftest import read_golden
+
+F32 = np.float32
+U64 = 1 << 64
+
+
+def check_tree(r):
+    nodes = r.nodes()
+    half = len(nodes) // 2
+    assert np.array_equal(nodes[1:half], nodes[2:2 * half:2] + nodes[3:2 * half:2])
+    leaves = r.leaves()
+    assert int(nodes[1]) == sum(int(v) for v in leaves) == r.root
+    return leaves
+
+
+def brute_slots(leaves, k, rnd):
+    """Stratified inverse CDF over integer masses in slot order, in Python integers."""
+    cum, run = [], 0
+    for m in leaves:
+        run += int(m)
+        cum.append(run)
+    w = run // k
+    out = []
+    for j, u in enumerate(rnd):
+        x = j * w + (int(u) * w >> 64)
+        out.append(bisect.bisect_right(cum, x))
+    return out
+
+
+def test_hand_worked_tree():
+    g = read_golden("sumtree_hand.txt")
+    F, k = int(g["frac_bits"][0]), int(g["k"][0])
+    r = oracle.Replay(4, 4, 8, 4, alpha=float(g["alpha"][0]), eps=float(g["eps"][0]), frac_bits=F)
+    rc, first = r.add(np.array(g["prio"], F32))
+    assert (rc, first) == (0, 0)
+    assert r.leaves().tolist() == [int(p) << F for p in g["prio"]]
+    assert r.root == 15 << F
+    beta = float(g["beta"][0])
+    for tag in "abc":
+        rnd = np.array([int(v) for v in g["rnd_" + tag]], np.uint64)
+        rc, out = r.sample(1, k, beta, rnd)
+        assert rc == 0
+        assert out["slot"].tolist() == [int(v) for v in g["slots_" + tag]]
+        assert out["key"].tolist() == out["slot"].tolist()
+        if "weights_" + tag in g:
+            np.testing.assert_allclose(out["weight"], [float(v) for v in g["weights_" + tag]], rtol=1e-6)
+    k5 = int(g["k5"][0])
+    rc, out = r.sample(1, k5, beta, np.array([int(v) for v in g["rnd_k5"]], np.uint64))
+    assert out["slot"].tolist() == [int(v) for v in g["slots_k5"]]
+
+
+@pytest.mark.parametrize("P,k", [(5, 3), (64, 7), (1000, 32), (4096, 512)])
+def test_descent_equals_brute_force(P, k):
+    rng = np.random.default_rng(P)
+    r = oracle.Replay(P, P, 4, 4)
+    prio = rng.pareto(1.1, P).astype(F32)
+    prio[rng.random(P) < 0.2] = 0
+    assert r.add(prio)[0] == 0
+    leaves = check_tree(r)
+    for trial in range(4):
+        rnd = rng.integers(0, U64, k, dtype=np.uint64)
+        if trial == 0:
+            rnd[:] = 0
+        if trial == 1:
+            rnd[:] = U64 - 1
+        rc, out = r.sample(1, k, 0.4, rnd)
+        exp = brute_slots(leaves, k, rnd)
+        assert out["slot"].tolist() == exp
+        assert r.sample_linear(k, rnd)[1].tolist() == exp
+        assert out["mass"].tolist() == [int(leaves[s]) for s in exp]
+
+
+def test_holes_are_never_sampled():
+    # evicted slots have zero mass; they sit in the middle of the slot order after wrap-around
+    r = oracle.Replay(6, 8, 4, 4)
+    r.add(np.ones(8, F32))
+    assert r.evict() == (0, 2)
+    r.add(np.ones(1, F32) * 3)                # key 8 -> slot 0
+    leaves = check_tree(r)
+    assert leaves[1] == 0 and leaves[0] > 0
+    rnd = np.random.default_rng(0).integers(0, U64, 7 * 300, dtype=np.uint64)
+    rc, out = r.sample(300, 7, 0.4, rnd)
+    assert 1 not in out["slot"]
+    assert set(out["key"].tolist()) <= set(range(2, 9))
+    # key of slot 0 is 8, the keys of slots 2..7 are themselves
+    assert all(int(kk) % 8 == int(s) for kk, s in zip(out["key"], out["slot"]))
+
+
+def test_sampling_frequencies_are_proportional_to_p_alpha():
+    # Appendix "Implementation": P(k) = p_k^alpha / sum p^alpha.  A regular grid of uniforms makes the
+    # count of every slot equal to its share of the grid up to one point per stratum edge.
+    alpha, F, P, k, G = 0.6, 24, 16, 4, 4096
+    rng = np.random.default_rng(7)
+    prio = rng.lognormal(0, 1, P).astype(F32)
+    r = oracle.Replay(P, P, 4, 4, alpha=alpha, eps=0.0, frac_bits=F)
+    r.add(prio)
+    u = ((np.arange(G, dtype=np.uint64) << np.uint64(52)) + np.uint64(1 << 51))       # mid-points of G cells
+    rnd = np.repeat(u[:, None], k, 1).reshape(-1)
+    rc, out = r.sample(G, k, 0.4, rnd)
+    counts = np.bincount(out["slot"], minlength=P)
+    share = prio.astype(np.float64) ** float(F32(alpha))
+    share /= share.sum()
+    expected = share * G * k
+    assert np.all(np.abs(counts - expected) <= 2 + 2e-5 * expected)
+
+
+def test_chi_square_on_random_uniforms():
+    alpha, P, k, NB = 0.6, 48, 8, 40000
+    rng = np.random.default_rng(11)
+    prio = np.abs(rng.standard_normal(P)).astype(F32) + F32(0.05)
+    r = oracle.Replay(P, P, 4, 4, alpha=alpha)
+    r.add(prio)
+    rc, out = r.sample(NB, k, 0.4, rng.integers(0, U64, NB * k, dtype=np.uint64))
+    counts = np.bincount(out["slot"], minlength=P).astype(np.float64)
+    share = (prio.astype(np.float64) + 1e-6) ** float(F32(alpha))
+    expected = share / share.sum() * NB * k
+    chi2 = ((counts - expected) ** 2 / expected).sum()
+    # stratification only lowers the variance, so the statistic must stay below a loose upper quantile
+    assert chi2 < 47 + 6 * math.sqrt(2 * 47)
+
+
+def test_alpha_zero_is_uniform():
+    P, k = 100, 10
+    r = oracle.Replay(P, P, 4, 4, alpha=0.0)
+    r.add(np.random.default_rng(0).lognormal(0, 3, P).astype(F32))
+    assert set(r.leaves().tolist()) == {1 << 24}
+    rnd = np.random.default_rng(1).integers(0, U64, k, dtype=np.uint64)
+    rc, out = r.sample(1, k, 0.4, rnd)
+    w = (P << 24) // k
+    assert out["slot"].tolist() == [(j * w + (int(u) * w >> 64)) >> 24 for j, u in enumerate(rnd)]
+    assert np.all(out["weight"] == 1.0)
+
+
+def test_importance_weights():
+    P, k = 512, 64
+    rng = np.random.default_rng(2)
+    r = oracle.Replay(P, P, 4, 4)
+    r.add(rng.lognormal(0, 1, P).astype(F32))
+    rnd = rng.integers(0, U64, 3 * k, dtype=np.uint64)
+    for beta in (0.0, 0.4, 1.0):
+        rc, out = r.sample(3, k, beta, rnd)
+        wt, mass = out["weight"].reshape(3, k), out["mass"].reshape(3, k).astype(np.float64)
+        assert np.all(wt > 0) and np.all(wt <= 1)
+        for b in range(3):
+            assert wt[b, np.argmin(mass[b])] == 1.0              # the least likely sample has weight 1
+            np.testing.assert_allclose(wt[b], (mass[b].min() / mass[b]) ** float(F32(beta)), rtol=1e-6)
+            # the definition: (N * P(i))^-beta over its maximum in the batch
+            raw = (P * mass[b] / r.root) ** -float(F32(beta))
+            np.testing.assert_allclose(wt[b], raw / raw.max(), rtol=1e-6)
+        if beta == 0.0:
+            assert np.all(wt == 1.0)
+        if beta == 1.0:
+            prod = wt * mass
+            np.testing.assert_allclose(prod, prod[:, :1] * np.ones_like(prod), rtol=1e-5)
+    r2 = oracle.Replay(P, P, 4, 4)
+    r2.add(np.full(P, 0.7, F32))
+    assert np.all(r2.sample(1, k, 0.4, rnd[:k])[1]["weight"] == 1.0)
+
+
+def test_fifo_eviction_and_keys():
+    C, P = 100, 128
+    r = oracle.Replay(C, P, 4, 4)
+    rng = np.random.default_rng(3)
+    total = 0
+    for rnd_i in range(40):
+        cnt = int(rng.integers(1, 28))
+        rc, first = r.add(rng.lognormal(0, 1, cnt).astype(F32))
+        assert rc == 0 and first == total
+        total += cnt
+        head_before, size_before = r.head, r.size
+        root_before = r.root
+        old = r.leaves()
+        rc, e = r.evict()
+        assert e == max(0, size_before - C) and r.head == head_before + e and r.size == min(size_before, C)
+        leaves = check_tree(r)
+        gone = [(head_before + i) % P for i in range(e)]
+        assert all(leaves[s] == 0 for s in gone)
+        assert r.root == root_before - sum(int(old[s]) for s in gone)
+        live = {(r.head + i) % P for i in range(r.size)}
+        assert {int(s) for s in np.nonzero(leaves)[0]} == live      # exactly the valid keys carry mass
+        rc, out = r.sample(2, 16, 0.4, rng.integers(0, U64, 32, dtype=np.uint64))
+        assert np.all(out["key"] >= r.head) and np.all(out["key"] < r.tail)
+        assert np.all(out["key"] % np.uint64(P) == out["slot"])
+
+
+def test_ring_full_refuses_without_writing():
+    r = oracle.Replay(4, 8, 4, 4)
+    assert r.add(np.ones(6, F32))[0] == 0
+    root = r.root
+    assert r.add(np.ones(3, F32))[0] == oracle.ERR_FULL
+    assert (r.tail, r.root) == (6, root)
+    assert r.add(np.ones(2, F32))[0] == 0                            # soft capacity never refuses
+
+
+def test_update_sets_the_mass_and_duplicates_apply_in_order():
+    P = 64
+    rng = np.random.default_rng(4)
+    prio0 = rng.lognormal(0, 1, P).astype(F32)
+    a, b = oracle.Replay(P, P, 4, 4), oracle.Replay(P, P, 4, 4)
+    a.add(prio0), b.add(prio0)
+    keys = rng.integers(0, P, 200).astype(np.uint64)                 # many repeats
+    newp = rng.lognormal(0, 1, 200).astype(F32)
+    assert a.update_priorities(keys, newp) == 0
+    for kk, pp in zip(keys, newp):                                   # one pair at a time
+        b.update_priorities(np.array([kk], np.uint64), np.array([pp], F32))
+    assert np.array_equal(a.leaves(), b.leaves())
+    leaves = check_tree(a)
+    last = {int(kk): pp for kk, pp in zip(keys, newp)}
+    qm = oracle.qmax(P)
+    for s in range(P):
+        p = last.get(s, prio0[s])
+        x = float(F32(p) + F32(1e-6))
+        assert abs(int(leaves[s]) / 2 ** 24 - math.pow(x, float(F32(0.6)))) <= 1e-5 * x ** 0.6 + 2 ** -24
+        assert int(leaves[s]) <= qm
+
+
+def test_stale_updates_are_dropped():
+    r = oracle.Replay(8, 16, 4, 4)
+    r.add(np.ones(12, F32))
+    r.evict()                                                        # keys 0..3 gone
+    r.add(np.ones(4, F32) * 2)                                       # keys 12..15
+    before = r.leaves()
+    assert r.update_priorities(np.array([0, 3, 16, 1 << 40], np.uint64), np.full(4, 9.0, F32)) == 0
+    assert np.array_equal(before, r.leaves()) and r.n_stale == 4
+    r.update_priorities(np.array([4], np.uint64), np.array([9.0], F32))
+    assert r.leaves()[4] != before[4] and r.n_stale == 4
+    check_tree(r)
+
+
+def test_not_ready_and_empty():
+    r = oracle.Replay(100, 100, 4, 4, min_size_to_sample=50)
+    rnd = np.zeros(4, np.uint64)
+    assert r.sample(1, 4, 0.4, rnd)[0] == oracle.ERR_NOT_READY
+    r.add(np.ones(49, F32))
+    assert r.sample(1, 4, 0.4, rnd)[0] == oracle.ERR_NOT_READY
+    r.add(np.ones(1, F32))
+    assert r.sample(1, 4, 0.4, rnd)[0] == 0
+    assert oracle.Replay(10, 10, 4, 4).sample(1, 4, 0.4, rnd)[0] == oracle.ERR_EMPTY
+
+
+def test_payload_round_trip():
+    P, ob, ab = 32, 24, 8
+    rng = np.random.default_rng(5)
+    r = oracle.Replay(20, P, ob, ab)
+    store = {}
+    key = 0
+    for _ in range(6):
+        cnt = 9
+        obs = rng.integers(0, 256, (cnt, ob), dtype=np.uint8)
+        act = rng.integers(0, 256, (cnt, ab), dtype=np.uint8)
+        ret, gacc = rng.standard_normal(cnt).astype(F32), rng.random(cnt).astype(F32)
+        assert r.add(rng.lognormal(0, 1, cnt).astype(F32), obs, act, ret, gacc)[0] == 0
+        for i in range(cnt):
+            store[key + i] = (obs[i], act[i], ret[i], gacc[i])
+        key += cnt
+        r.evict()
+        rc, out = r.sample(1, 8, 0.4, rng.integers(0, U64, 8, dtype=np.uint64))
+        for j, kk in enumerate(out["key"]):
+            o, a, rt, g = store[int(kk)]
+            assert np.array_equal(out["obs"][j], o) and np.array_equal(out["act"][j], a)
+            assert out["ret"][j] == rt and out["gacc"][j] == g
+
+
+def test_soft_capacity_sawtooth_matches_the_reported_median_size():
+    # Atari experiments: ~12.5K transitions/s in, 19 learner steps/s, excess above 2M removed every 100
+    # steps, reported median size 2,035,050.  Same schedule at 1/100 of the scale, driven through add/evict.
+    C = 20_000
+    r = oracle.Replay(C, 32768, 4, 4)
+    r.add(np.ones(C, F32))
+    sizes, carry = [], 0.0
+    for step in range(100 * 60):
+        carry += 125.0 / 19.0
+        cnt = int(carry)
+        carry -= cnt
+        assert r.add(np.ones(cnt, F32))[0] == 0
+        if (step + 1) % 100 == 0:
+            r.evict()
+            assert r.size == C
+        sizes.append(r.size)
+    assert abs(np.median(sizes) * 100 - 2_035_050) / 2_035_050 < 2e-3
+    assert r.root == C * r.leaves()[r.head % 32768]
