@@ -1,0 +1,199 @@
+/*
+ * apex_replay.h -- C ABI of an MI355X-resident replay memory for Ape-X
+ * ("Distributed Prioritized Experience Replay").
+ *
+ * The library keeps the whole replay memory of the paper (Section 3, Figure 1: one shared,
+ * centralized, prioritized memory that many actors fill and one learner samples) in the HBM
+ * of one GPU and serves the paper's replay verbs as stream-ordered batches of HIP kernels:
+ *
+ *   apex_nstep_priorities          ComputePriorities of Algorithm 1 (actor side)
+ *   apex_replay_add                replay.Add            (Algorithm 1)
+ *   apex_replay_sample             replay.Sample         (Algorithm 2)
+ *   apex_replay_update_priorities  replay.SetPriority    (Algorithm 2)
+ *   apex_replay_evict              replay.RemoveToFit    (Algorithm 2)
+ *
+ * Conventions for every call
+ *   - "device" pointers are HIP device memory that the caller allocated and still owns; the
+ *     library never frees them and does not use them after the work it enqueued has finished.
+ *     "host" pointers are ordinary host memory written before the call returns.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Every call only
+ *     enqueues kernels on that stream and returns; device outputs are valid once the stream has
+ *     reached that point.  No call allocates or frees device memory, none synchronises except
+ *     apex_replay_create and apex_replay_stats.  Calls on one memory must be issued in order
+ *     on one stream (or be ordered by events): the memory holds no locks.
+ *   - Return value: APEX_OK or a negative apex_status; on error nothing has been enqueued and
+ *     no state has changed.
+ *   - Transitions are identified by a key: the running count of insertions (the first
+ *     transition ever added has key 0).  The transition with key K lives in ring slot
+ *     K mod max_slots.  Keys in [head, tail) are valid; eviction advances head.
+ *   - Sampling mass.  A priority p is turned into the integer mass
+ *         Q(p) = clamp( floor( (|p| + eps)^alpha * 2^frac_bits ), 1, QMAX ),
+ *         QMAX = 2^(62 - ceil(log2(max_slots))),
+ *     where the power is evaluated by a fixed sequence of IEEE fp32 operations, so that the
+ *     same priorities give the same masses, tree sums and sampled indices on any machine.
+ *     The probability of drawing a transition is mass / (sum of all masses), the paper's
+ *     p^alpha / sum_k p_k^alpha (Appendix "Implementation", paragraph "Sampling Data").
+ */
+#ifndef APEX_REPLAY_H
+#define APEX_REPLAY_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum apex_status {
+  APEX_OK = 0,
+  APEX_ERR_INVALID_ARG = -1, /* null pointer, zero size, value out of its documented range          */
+  APEX_ERR_FULL = -2,        /* add: size + count would exceed max_slots                             */
+  APEX_ERR_NOT_READY = -3,   /* sample: fewer than min_size_to_sample transitions stored             */
+  APEX_ERR_EMPTY = -4,       /* sample: nothing stored                                               */
+  APEX_ERR_HIP = -5,         /* a HIP call failed; see apex_last_hip_error()                         */
+  APEX_ERR_TOO_LARGE = -6    /* sample: more than APEX_MAX_SAMPLES_PER_CALL samples or
+                                APEX_MAX_BATCHES_PER_CALL batches; update: m >= 2^32                 */
+} apex_status;
+
+#define APEX_MAX_SAMPLES_PER_CALL 65536u
+#define APEX_MAX_BATCHES_PER_CALL 1024u
+#define APEX_TREE_MAX_LEVELS 8u
+
+typedef struct apex_replay apex_replay_t; /* opaque host object; created and destroyed by the library */
+
+typedef struct apex_replay_config {
+  uint64_t capacity;           /* soft limit on stored transitions; apex_replay_evict trims to it
+                                  (Section 4.1: 2,000,000)                                           */
+  uint64_t max_slots;          /* physical ring size P >= capacity; slot = key mod P                 */
+  uint32_t obs_bytes;          /* opaque observation payload per transition (e.g. 84*84*4 = 28224)   */
+  uint32_t act_bytes;          /* opaque action payload per transition (e.g. 4)                      */
+  float alpha;                 /* priority exponent, in [-1, 1] (Section 4.1: 0.6)                   */
+  float eps;                   /* added to |p| before the power, >= 0                                */
+  uint32_t frac_bits;          /* F: fraction bits of the integer mass, <= 32 (24 recommended)       */
+  uint32_t reserved;           /* must be 0                                                          */
+  uint64_t min_size_to_sample; /* sample refuses below this size (Appendix "Atari: Additional
+                                  Details": the learner waits for 50,000 transitions); 0 disables    */
+} apex_replay_config_t;
+
+typedef struct apex_replay_stats {
+  uint64_t size, head, tail; /* stored transitions and the valid key range [head, tail)            */
+  uint64_t root;             /* sum of all masses                                                   */
+  uint64_t n_stale_dropped;  /* priority updates skipped because their key was no longer valid      */
+  uint64_t n_clamped;        /* priorities whose mass had to be clamped to 1 or QMAX                */
+} apex_replay_stats_t;
+
+/* Where things live inside the caller's device regions (for inspection and tests). */
+typedef struct apex_replay_layout {
+  uint64_t obs_offset, act_offset, ret_offset, gacc_offset; /* byte offsets in d_storage; row strides
+                                                               are obs_bytes, act_bytes, 4, 4       */
+  uint32_t tree_levels;                                     /* level 0 = one uint64 mass per slot   */
+  uint32_t tree_fanout;                                     /* node i of level l+1 = sum of nodes
+                                                               [64 i, 64 i + 64) of level l         */
+  uint64_t level_offset[APEX_TREE_MAX_LEVELS];              /* in uint64 units inside d_tree        */
+  uint64_t level_size[APEX_TREE_MAX_LEVELS];                /* nodes in use (arrays are zero padded
+                                                               to a multiple of 64)                 */
+} apex_replay_layout_t;
+
+/*
+ * Sizes of the three device regions apex_replay_create adopts: the payload ring, the sum
+ * tree, and scratch (device-side counters, per-call temporaries).  Any out pointer may be NULL.
+ */
+int apex_replay_workspace_bytes(const apex_replay_config_t *cfg, size_t *storage_bytes, size_t *tree_bytes,
+                                size_t *scratch_bytes);
+
+/*
+ * Builds an empty replay memory inside three caller-allocated device regions of at least the
+ * sizes reported above, each 256-byte aligned.  Zero-fills the tree and the scratch region and
+ * synchronises the device once.  The regions must stay allocated until apex_replay_destroy,
+ * which frees only the host object.
+ */
+int apex_replay_create(const apex_replay_config_t *cfg, void *d_storage, void *d_tree, void *d_scratch,
+                       apex_replay_t **out);
+int apex_replay_destroy(apex_replay_t *r);
+int apex_replay_layout(const apex_replay_t *r, apex_replay_layout_t *out /*host*/);
+
+/*
+ * Actor-side priorities (Algorithm 1, ComputePriorities; Appendix "Implementation", "Adding
+ * Data"): absolute n-step TD errors of S streams x T transitions, from Q-values the actors
+ * already hold.  Stateless.
+ *
+ * All arrays are device, row-major.  Each stream carries T+n rows; row u holds what was known
+ * when acting in state S_u: q_online[s,u,0..A), q_target[s,u,0..A), action[s,u] in [0,A),
+ * reward[s,u] = the reward that followed (R_{u+1}), discount[s,u] = the discount that followed
+ * (gamma, or 0 if the episode ended on that step).  For t in [0,T):
+ *     ret   = sum_{j<n} (prod_{i<j} discount[t+i]) * reward[t+j]
+ *     gacc  = prod_{j<n} discount[t+j]
+ *     boot  = q_target[t+n, argmax_a q_online[t+n, a]]              (ties: lowest a)
+ *     prio  = | ret + gacc * boot - q_online[t, action[t]] |
+ * which is the multi-step double-Q target of Section 3.1; a zero discount truncates the return
+ * at the end of an episode.  With A = 1 (q_* holding critic values) it is the target of
+ * Section 3.2.  An actor with a single network passes the same pointer for q_online and
+ * q_target.  Outputs prio, ret, gacc are [S,T] fp32; prio_fx (may be NULL) receives the integer
+ * mass Q(prio) for a memory of max_slots slots (max_slots = 0: QMAX = 2^62).
+ * fp32 arithmetic in a fixed order: ret by Horner's rule with one fused multiply-add per step,
+ * gacc left to right, the target as one fused multiply-add.
+ */
+int apex_nstep_priorities(uint32_t S, uint32_t T, uint32_t n, uint32_t A, const float *q_online,
+                          const float *q_target, const int32_t *action, const float *reward,
+                          const float *discount, float alpha, float eps, uint32_t frac_bits,
+                          uint64_t max_slots, float *prio, float *ret, float *gacc, uint64_t *prio_fx,
+                          void *hip_stream);
+
+/*
+ * replay.Add (Algorithm 1; Appendix "Implementation", "Adding Data"): stores count transitions
+ * under the next count keys and enters them into the sampling distribution with the priorities
+ * the actors computed.  obs [count,obs_bytes], act [count,act_bytes], ret, gacc, prio [count]
+ * are device arrays; obs, act, ret, gacc may each be NULL (that part of the payload is then
+ * left as it is).  *first_key_out (host, may be NULL) receives the key of the first one.
+ * Data beyond the soft capacity is accepted (Section 4.1: adding is always permitted); only a
+ * full ring refuses, with APEX_ERR_FULL.
+ */
+int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                    const float *gacc, const float *prio, uint64_t *first_key_out, void *hip_stream);
+
+/*
+ * replay.Sample (Algorithm 2; Appendix "Implementation", "Sampling Data"): num_batches
+ * independent batches of k transitions, all drawn from the state of the memory at this point
+ * of the stream (Section 4.1: the learner prefetches up to 16 batches of 512).
+ *
+ * Batch b, sample j: with total = sum of all masses and w = floor(total / k), the point
+ *     x = j*w + floor(rnd[b,j] * w / 2^64)
+ * lies in the j-th of k equal strata of [0,total); the transition drawn is the one whose
+ * interval of the cumulative mass, taken in slot order, contains x.  rnd is a device array
+ * [num_batches,k] of uniform 64-bit integers supplied by the caller.
+ * weight_out[b,j] = (N * P(i))^-beta / max over the batch, N = size, P(i) = mass_i / total:
+ * importance-sampling weights normalised by the largest weight of the same batch of k.
+ * Device outputs, each may be NULL except slot_out: key_out [nb,k] u64, slot_out [nb,k] u32,
+ * weight_out [nb,k] f32, obs_out [nb,k,obs_bytes], act_out [nb,k,act_bytes], ret_out, gacc_out
+ * [nb,k] f32 (copies of what apex_replay_add stored).
+ */
+int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                       uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
+                       float *ret_out, float *gacc_out, void *hip_stream);
+
+/*
+ * replay.SetPriority (Algorithm 2): mass of key[i] becomes Q(prio[i]) for i in [0,m); key and
+ * prio are device arrays.  The result is that of applying the pairs one after the other: of
+ * several pairs naming one key the last stands; a pair whose key is not valid any more is
+ * skipped and counted.
+ */
+int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *key, const float *prio,
+                                  void *hip_stream);
+
+/*
+ * replay.RemoveToFit (Algorithm 2; Section 4.1: excess above the soft capacity is removed en
+ * masse, oldest first): removes the size - capacity oldest keys, if any.  *evicted_out (host,
+ * may be NULL) receives their number.
+ */
+int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream);
+
+/* Synchronises hip_stream and reads the counters back. */
+int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out /*host*/, void *hip_stream);
+
+/* hipError_t of the last failed HIP call of the calling thread (0 if none). */
+int apex_last_hip_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* APEX_REPLAY_H */

@@ -1,0 +1,196 @@
+"""Thin ctypes binding of ``libapex_replay.so`` (declared in ``include/apex_replay.h``).
+
+Argument marshalling only: every step of the replay path runs in the library's HIP kernels.
+PyTorch supplies device memory (``tensor.data_ptr()``) and the current stream, nothing else.
+There is no fallback: if the library has not been built, importing this module raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libapex_replay.so")
+
+OK, ERR_INVALID_ARG, ERR_FULL, ERR_NOT_READY, ERR_EMPTY, ERR_HIP, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
+STATUS_NAMES = {0: "APEX_OK", -1: "APEX_ERR_INVALID_ARG", -2: "APEX_ERR_FULL", -3: "APEX_ERR_NOT_READY",
+                -4: "APEX_ERR_EMPTY", -5: "APEX_ERR_HIP", -6: "APEX_ERR_TOO_LARGE"}
+MAX_SAMPLES_PER_CALL = 65536
+MAX_BATCHES_PER_CALL = 1024
+TREE_MAX_LEVELS = 8
+
+EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_destroy", "apex_replay_layout",
+           "apex_nstep_priorities", "apex_replay_add", "apex_replay_sample", "apex_replay_update_priorities",
+           "apex_replay_evict", "apex_replay_stats", "apex_last_hip_error"]
+
+
+class Config(C.Structure):
+    _fields_ = [("capacity", C.c_uint64), ("max_slots", C.c_uint64), ("obs_bytes", C.c_uint32),
+                ("act_bytes", C.c_uint32), ("alpha", C.c_float), ("eps", C.c_float), ("frac_bits", C.c_uint32),
+                ("reserved", C.c_uint32), ("min_size_to_sample", C.c_uint64)]
+
+
+class Stats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("size", "head", "tail", "root", "n_stale_dropped", "n_clamped")]
+
+
+class Layout(C.Structure):
+    _fields_ = [("obs_offset", C.c_uint64), ("act_offset", C.c_uint64), ("ret_offset", C.c_uint64),
+                ("gacc_offset", C.c_uint64), ("tree_levels", C.c_uint32), ("tree_fanout", C.c_uint32),
+                ("level_offset", C.c_uint64 * TREE_MAX_LEVELS), ("level_size", C.c_uint64 * TREE_MAX_LEVELS)]
+
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError("%s is missing: build it first (python paper_1803_00933_amd/build.py or "
+                      "__graft_entry__.build()); there is no fallback path" % LIB_PATH)
+
+lib = C.CDLL(LIB_PATH)
+_vp, _u32, _u64, _f32 = C.c_void_p, C.c_uint32, C.c_uint64, C.c_float
+lib.apex_replay_workspace_bytes.argtypes = [C.POINTER(Config)] + [C.POINTER(C.c_size_t)] * 3
+lib.apex_replay_create.argtypes = [C.POINTER(Config), _vp, _vp, _vp, C.POINTER(_vp)]
+lib.apex_replay_destroy.argtypes = [_vp]
+lib.apex_replay_layout.argtypes = [_vp, C.POINTER(Layout)]
+lib.apex_nstep_priorities.argtypes = [_u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _f32, _f32, _u32, _u64,
+                                      _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_add.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, C.POINTER(_u64), _vp]
+lib.apex_replay_sample.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
+lib.apex_replay_evict.argtypes = [_vp, C.POINTER(_u64), _vp]
+lib.apex_replay_stats.argtypes = [_vp, C.POINTER(Stats), _vp]
+lib.apex_last_hip_error.argtypes = []
+for _name in EXPORTS:
+    getattr(lib, _name).restype = C.c_int
+
+
+def _ptr(t):
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device, contiguous tensors only"
+    return t.data_ptr()
+
+
+def _stream(stream=None):
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def workspace_bytes(cfg: Config):
+    a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+    rc = lib.apex_replay_workspace_bytes(C.byref(cfg), C.byref(a), C.byref(b), C.byref(c))
+    return rc, a.value, b.value, c.value
+
+
+def nstep_priorities(q_online, q_target, action, reward, discount, n, alpha, eps, frac_bits, max_slots=0,
+                     want_fx=True, out=None, stream=None):
+    """Device tensors: q_* [S,T+n,A] fp32, action int32 / reward / discount fp32 [S,T+n].
+    Returns (rc, prio, ret, gacc, prio_fx) with outputs of shape [S,T]."""
+    S, L, A = q_online.shape
+    T = L - n
+    dev = q_online.device
+    if out is None:
+        prio = torch.empty((S, T), dtype=torch.float32, device=dev)
+        ret = torch.empty_like(prio)
+        gacc = torch.empty_like(prio)
+        fx = torch.empty((S, T), dtype=torch.int64, device=dev) if want_fx else None
+    else:
+        prio, ret, gacc, fx = out
+    rc = lib.apex_nstep_priorities(S, T, n, A, _ptr(q_online), _ptr(q_target), _ptr(action), _ptr(reward),
+                                   _ptr(discount), alpha, eps, frac_bits, max_slots, _ptr(prio), _ptr(ret),
+                                   _ptr(gacc), _ptr(fx), _stream(stream))
+    return rc, prio, ret, gacc, fx
+
+
+class Replay:
+    """Owns the three device regions (as torch tensors) and the library handle."""
+
+    def __init__(self, capacity, max_slots, obs_bytes, act_bytes, alpha=0.6, eps=1e-6, frac_bits=24,
+                 min_size_to_sample=0, device="cuda:0"):
+        self.cfg = Config(capacity, max_slots, obs_bytes, act_bytes, alpha, eps, frac_bits, 0, min_size_to_sample)
+        rc, sb, tb, cb = workspace_bytes(self.cfg)
+        if rc != OK:
+            raise ValueError("configuration rejected: %s" % STATUS_NAMES.get(rc, rc))
+        self.device = torch.device(device)
+        self.storage = torch.empty(sb, dtype=torch.uint8, device=self.device)
+        self.tree = torch.empty(tb // 8, dtype=torch.int64, device=self.device)
+        self.scratch = torch.empty(cb, dtype=torch.uint8, device=self.device)
+        torch.cuda.synchronize(self.device)
+        h = _vp(None)
+        rc = lib.apex_replay_create(C.byref(self.cfg), self.storage.data_ptr(), self.tree.data_ptr(),
+                                    self.scratch.data_ptr(), C.byref(h))
+        if rc != OK:
+            raise RuntimeError("apex_replay_create: %s (hip %d)" % (STATUS_NAMES.get(rc, rc), lib.apex_last_hip_error()))
+        self.h = h
+        self.capacity, self.max_slots, self.obs_bytes, self.act_bytes = capacity, max_slots, obs_bytes, act_bytes
+        lay = Layout()
+        lib.apex_replay_layout(self.h, C.byref(lay))
+        self.layout = lay
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.apex_replay_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    # -- views of the caller-owned regions (for tests) ------------------------------------------
+    def obs_view(self):
+        o = self.layout.obs_offset
+        return self.storage[o:o + self.max_slots * self.obs_bytes].view(self.max_slots, self.obs_bytes)
+
+    def act_view(self):
+        o = self.layout.act_offset
+        return self.storage[o:o + self.max_slots * self.act_bytes].view(self.max_slots, self.act_bytes)
+
+    def ret_view(self):
+        o = self.layout.ret_offset
+        return self.storage[o:o + self.max_slots * 4].view(torch.float32)
+
+    def gacc_view(self):
+        o = self.layout.gacc_offset
+        return self.storage[o:o + self.max_slots * 4].view(torch.float32)
+
+    def level_view(self, l):
+        o, n = self.layout.level_offset[l], self.layout.level_size[l]
+        return self.tree[o:o + n]
+
+    # -- the replay verbs -----------------------------------------------------------------------
+    def add(self, prio, obs=None, act=None, ret=None, gacc=None, stream=None):
+        first = _u64(0)
+        rc = lib.apex_replay_add(self.h, prio.shape[0], _ptr(obs), _ptr(act), _ptr(ret), _ptr(gacc), _ptr(prio),
+                                 C.byref(first), _stream(stream))
+        return rc, int(first.value)
+
+    def alloc_sample_outputs(self, num_batches, k, payload=True):
+        n, dev = num_batches * k, self.device
+        out = dict(key=torch.empty(n, dtype=torch.int64, device=dev),
+                   slot=torch.empty(n, dtype=torch.int32, device=dev),
+                   weight=torch.empty(n, dtype=torch.float32, device=dev))
+        if payload:
+            out.update(obs=torch.empty((n, self.obs_bytes), dtype=torch.uint8, device=dev),
+                       act=torch.empty((n, self.act_bytes), dtype=torch.uint8, device=dev),
+                       ret=torch.empty(n, dtype=torch.float32, device=dev),
+                       gacc=torch.empty(n, dtype=torch.float32, device=dev))
+        return out
+
+    def sample(self, num_batches, k, beta, rnd, out=None, payload=True, stream=None):
+        if out is None:
+            out = self.alloc_sample_outputs(num_batches, k, payload)
+        rc = lib.apex_replay_sample(self.h, num_batches, k, beta, _ptr(rnd), _ptr(out.get("key")), _ptr(out["slot"]),
+                                    _ptr(out.get("weight")), _ptr(out.get("obs")), _ptr(out.get("act")),
+                                    _ptr(out.get("ret")), _ptr(out.get("gacc")), _stream(stream))
+        return rc, out
+
+    def update_priorities(self, key, prio, stream=None):
+        return lib.apex_replay_update_priorities(self.h, key.shape[0], _ptr(key), _ptr(prio), _stream(stream))
+
+    def evict(self, stream=None):
+        e = _u64(0)
+        rc = lib.apex_replay_evict(self.h, C.byref(e), _stream(stream))
+        return rc, int(e.value)
+
+    def stats(self, stream=None):
+        st = Stats()
+        rc = lib.apex_replay_stats(self.h, C.byref(st), _stream(stream))
+        if rc != OK:
+            raise RuntimeError("apex_replay_stats: %s" % STATUS_NAMES.get(rc, rc))
+        return {n: int(getattr(st, n)) for n, _ in Stats._fields_}

@@ -1,0 +1,366 @@
+// Host side of the C ABI declared in include/apex_replay.h: argument checks, host mirror of
+// head/tail, and the kernel launches.  Every entry point only enqueues work on the caller's
+// stream; nothing here allocates device memory.
+#include "apex_replay.h"
+
+#include <hip/hip_runtime.h>
+
+#include <new>
+
+#include "kernels.hpp"
+
+using namespace apex;
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+inline bool hip_failed(hipError_t e)
+{
+  if (e == hipSuccess) return false;
+  g_last_hip_error = (int)e;
+  return true;
+}
+
+#define APEX_HIP(call)                         \
+  do {                                         \
+    if (hip_failed((call))) return APEX_ERR_HIP; \
+  } while (0)
+
+inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+
+uint32_t ceil_log2(uint64_t v)
+{
+  uint32_t l = 0;
+  while ((1ull << l) < v) ++l;
+  return l;
+}
+
+uint64_t qmax_for(uint64_t max_slots) { return max_slots ? 1ull << (62 - ceil_log2(max_slots)) : 1ull << 62; }
+
+struct Geometry {
+  uint64_t obs_off, act_off, ret_off, gacc_off, storage_bytes;
+  uint32_t nlev;
+  uint64_t level_off[kMaxLevels], level_size[kMaxLevels], tree_words;
+  // scratch: DeviceState | tickets | mass | slot | claim
+  uint64_t state_off, ticket_off, mass_off, slot_off, claim_off, scratch_bytes;
+};
+
+int validate(const apex_replay_config_t *c)
+{
+  if (!c) return APEX_ERR_INVALID_ARG;
+  if (c->capacity == 0 || c->max_slots < c->capacity || c->max_slots > (1ull << 32)) return APEX_ERR_INVALID_ARG;
+  if (c->obs_bytes == 0 || c->act_bytes == 0 || c->frac_bits > 32 || c->reserved != 0) return APEX_ERR_INVALID_ARG;
+  if (!(c->alpha >= -1.0f && c->alpha <= 1.0f) || !(c->eps >= 0.0f) || !(c->eps < 1e30f)) return APEX_ERR_INVALID_ARG;
+  return APEX_OK;
+}
+
+int geometry(const apex_replay_config_t *c, Geometry *g)
+{
+  const uint64_t P = c->max_slots;
+  g->obs_off = 0;
+  g->act_off = g->obs_off + round_up(P * c->obs_bytes, 256);
+  g->ret_off = g->act_off + round_up(P * c->act_bytes, 256);
+  g->gacc_off = g->ret_off + round_up(P * 4, 256);
+  g->storage_bytes = g->gacc_off + round_up(P * 4, 256);
+
+  uint64_t n = P, off = 0;
+  uint32_t l = 0;
+  for (;;) {
+    if (l >= kMaxLevels) return APEX_ERR_INVALID_ARG;
+    g->level_off[l] = off;
+    g->level_size[l] = n;
+    off += round_up(n, kFanout);
+    ++l;
+    if (n <= kTopMax) break;
+    n = (n + kFanout - 1) / kFanout;
+  }
+  g->nlev = l;
+  g->tree_words = off;
+
+  g->state_off = 0;
+  g->ticket_off = 256;
+  g->mass_off = g->ticket_off + round_up(APEX_MAX_BATCHES_PER_CALL * 4, 256);
+  g->slot_off = g->mass_off + (uint64_t)APEX_MAX_SAMPLES_PER_CALL * 8;
+  g->claim_off = g->slot_off + (uint64_t)APEX_MAX_SAMPLES_PER_CALL * 4;
+  g->scratch_bytes = g->claim_off + round_up(P * 4, 256);
+  return APEX_OK;
+}
+
+}  // namespace
+
+struct apex_replay {
+  apex_replay_config_t cfg;
+  Geometry geo;
+  uint8_t *storage;
+  uint64_t *tree;
+  uint8_t *scratch;
+  uint64_t head, tail;  // host mirror of the device state
+  QuantParams qp;
+  TreeView tv;
+
+  DeviceState *state() const { return reinterpret_cast<DeviceState *>(scratch + geo.state_off); }
+  uint32_t *ticket() const { return reinterpret_cast<uint32_t *>(scratch + geo.ticket_off); }
+  uint64_t *mass() const { return reinterpret_cast<uint64_t *>(scratch + geo.mass_off); }
+  uint32_t *claim() const { return reinterpret_cast<uint32_t *>(scratch + geo.claim_off); }
+  uint8_t *obs() const { return storage + geo.obs_off; }
+  uint8_t *act() const { return storage + geo.act_off; }
+  float *ret() const { return reinterpret_cast<float *>(storage + geo.ret_off); }
+  float *gacc() const { return reinterpret_cast<float *>(storage + geo.gacc_off); }
+};
+
+namespace {
+
+// Copies nrows rows of row_bytes bytes; picks the widest vector the row size and the base
+// addresses allow and the long- or short-row kernel.
+template <typename Vec>
+int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const RowMap &dmap, uint64_t nrows,
+                  uint64_t row_bytes, hipStream_t stream)
+{
+  constexpr int kUnroll = 7;  // 7 * 256 lanes * 16 B = 28,672 B >= one 84x84x4 frame stack
+  const uint32_t vpr = (uint32_t)(row_bytes / sizeof(Vec));
+  if (vpr > 256) {
+    const uint32_t cpr = (vpr + 256 * kUnroll - 1) / (256 * kUnroll);
+    if (nrows * cpr > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+    copy_rows_long_kernel<Vec, kUnroll>
+        <<<dim3((uint32_t)(nrows * cpr)), dim3(256), 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes);
+  } else {
+    uint32_t lanes_log2 = 0;
+    while ((1u << lanes_log2) < vpr) ++lanes_log2;
+    const uint64_t rows_per_block = 256u >> lanes_log2;
+    const uint64_t blocks = (nrows + rows_per_block - 1) / rows_per_block;
+    if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+    copy_rows_short_kernel<Vec>
+        <<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(src, smap, dst, dmap, nrows, vpr, lanes_log2, row_bytes);
+  }
+  return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+}
+
+int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dmap, uint64_t nrows, uint64_t row_bytes,
+                hipStream_t stream)
+{
+  if (nrows == 0) return APEX_OK;
+  const uintptr_t mis = (uintptr_t)src | (uintptr_t)dst | (uintptr_t)row_bytes;
+  const uint8_t *s = static_cast<const uint8_t *>(src);
+  uint8_t *d = static_cast<uint8_t *>(dst);
+  if ((mis & 15) == 0) return launch_copy_t<u32x4>(s, smap, d, dmap, nrows, row_bytes, stream);
+  if ((mis & 3) == 0) return launch_copy_t<uint32_t>(s, smap, d, dmap, nrows, row_bytes, stream);
+  return launch_copy_t<uint8_t>(s, smap, d, dmap, nrows, row_bytes, stream);
+}
+
+inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
+
+}  // namespace
+
+extern "C" {
+
+int apex_last_hip_error(void) { return g_last_hip_error; }
+
+int apex_replay_workspace_bytes(const apex_replay_config_t *cfg, size_t *storage_bytes, size_t *tree_bytes,
+                                size_t *scratch_bytes)
+{
+  int rc = validate(cfg);
+  if (rc != APEX_OK) return rc;
+  Geometry g;
+  rc = geometry(cfg, &g);
+  if (rc != APEX_OK) return rc;
+  if (storage_bytes) *storage_bytes = g.storage_bytes;
+  if (tree_bytes) *tree_bytes = g.tree_words * 8;
+  if (scratch_bytes) *scratch_bytes = g.scratch_bytes;
+  return APEX_OK;
+}
+
+int apex_replay_create(const apex_replay_config_t *cfg, void *d_storage, void *d_tree, void *d_scratch,
+                       apex_replay_t **out)
+{
+  int rc = validate(cfg);
+  if (rc != APEX_OK) return rc;
+  if (!d_storage || !d_tree || !d_scratch || !out) return APEX_ERR_INVALID_ARG;
+  if (((uintptr_t)d_storage | (uintptr_t)d_tree | (uintptr_t)d_scratch) & 255) return APEX_ERR_INVALID_ARG;
+  apex_replay *r = new (std::nothrow) apex_replay();
+  if (!r) return APEX_ERR_INVALID_ARG;
+  r->cfg = *cfg;
+  rc = geometry(cfg, &r->geo);
+  if (rc != APEX_OK) {
+    delete r;
+    return rc;
+  }
+  r->storage = static_cast<uint8_t *>(d_storage);
+  r->tree = static_cast<uint64_t *>(d_tree);
+  r->scratch = static_cast<uint8_t *>(d_scratch);
+  r->head = r->tail = 0;
+  r->qp = QuantParams{cfg->alpha, cfg->eps, cfg->frac_bits, qmax_for(cfg->max_slots)};
+  r->tv.nlev = r->geo.nlev;
+  r->tv.n_top = (uint32_t)r->geo.level_size[r->geo.nlev - 1];
+  r->tv.P = cfg->max_slots;
+  for (uint32_t l = 0; l < kMaxLevels; ++l) r->tv.level[l] = l < r->geo.nlev ? r->tree + r->geo.level_off[l] : nullptr;
+
+  fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(r->tree, r->geo.tree_words);
+  fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(reinterpret_cast<uint64_t *>(r->scratch),
+                                                          r->geo.scratch_bytes / 8);
+  if (hip_failed(hipGetLastError()) || hip_failed(hipDeviceSynchronize())) {
+    delete r;
+    return APEX_ERR_HIP;
+  }
+  *out = r;
+  return APEX_OK;
+}
+
+int apex_replay_destroy(apex_replay_t *r)
+{
+  if (!r) return APEX_ERR_INVALID_ARG;
+  delete r;
+  return APEX_OK;
+}
+
+int apex_replay_layout(const apex_replay_t *r, apex_replay_layout_t *out)
+{
+  if (!r || !out) return APEX_ERR_INVALID_ARG;
+  out->obs_offset = r->geo.obs_off;
+  out->act_offset = r->geo.act_off;
+  out->ret_offset = r->geo.ret_off;
+  out->gacc_offset = r->geo.gacc_off;
+  out->tree_levels = r->geo.nlev;
+  out->tree_fanout = kFanout;
+  for (uint32_t l = 0; l < APEX_TREE_MAX_LEVELS; ++l) {
+    out->level_offset[l] = l < r->geo.nlev ? r->geo.level_off[l] : 0;
+    out->level_size[l] = l < r->geo.nlev ? r->geo.level_size[l] : 0;
+  }
+  return APEX_OK;
+}
+
+int apex_nstep_priorities(uint32_t S, uint32_t T, uint32_t n, uint32_t A, const float *q_online,
+                          const float *q_target, const int32_t *action, const float *reward,
+                          const float *discount, float alpha, float eps, uint32_t frac_bits,
+                          uint64_t max_slots, float *prio, float *ret, float *gacc, uint64_t *prio_fx,
+                          void *hip_stream)
+{
+  if (!S || !T || !n || !A) return APEX_ERR_INVALID_ARG;
+  if (!q_online || !q_target || !action || !reward || !discount || !prio || !ret || !gacc) return APEX_ERR_INVALID_ARG;
+  if (frac_bits > 32 || !(alpha >= -1.0f && alpha <= 1.0f) || !(eps >= 0.0f) || max_slots > (1ull << 32))
+    return APEX_ERR_INVALID_ARG;
+  const uint64_t total = (uint64_t)S * T;
+  if (total > 0x7fffffffull * 256 || (uint64_t)T + n > 0xffffffffull) return APEX_ERR_TOO_LARGE;
+  const QuantParams qp{alpha, eps, frac_bits, qmax_for(max_slots)};
+  nstep_kernel<<<dim3(blocks_for(total, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
+      S, T, n, A, q_online, q_target, action, reward, discount, qp, prio, ret, gacc, prio_fx);
+  APEX_HIP(hipGetLastError());
+  return APEX_OK;
+}
+
+int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                    const float *gacc, const float *prio, uint64_t *first_key_out, void *hip_stream)
+{
+  if (!r || (count && !prio)) return APEX_ERR_INVALID_ARG;
+  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  if (first_key_out) *first_key_out = r->tail;
+  if (count == 0) return APEX_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const RowMap ident{nullptr, nullptr, 0};
+  const RowMap ring{nullptr, &r->state()->tail, r->cfg.max_slots};
+  int rc;
+  if (obs && (rc = launch_copy(obs, ident, r->obs(), ring, count, r->cfg.obs_bytes, stream)) != APEX_OK) return rc;
+  if (act && (rc = launch_copy(act, ident, r->act(), ring, count, r->cfg.act_bytes, stream)) != APEX_OK) return rc;
+  if (ret && (rc = launch_copy(ret, ident, r->ret(), ring, count, 4, stream)) != APEX_OK) return rc;
+  if (gacc && (rc = launch_copy(gacc, ident, r->gacc(), ring, count, 4, stream)) != APEX_OK) return rc;
+  add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), count, prio, r->qp);
+  advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), 0, count);
+  APEX_HIP(hipGetLastError());
+  r->tail += count;
+  return APEX_OK;
+}
+
+int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                       uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
+                       float *ret_out, float *gacc_out, void *hip_stream)
+{
+  if (!r || !num_batches || !k || !rnd || !slot_out || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
+    return APEX_ERR_TOO_LARGE;
+  const uint64_t size = r->tail - r->head;
+  if (size < r->cfg.min_size_to_sample) return APEX_ERR_NOT_READY;
+  if (size == 0) return APEX_ERR_EMPTY;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+
+  SampleArgs a;
+  a.tv = r->tv;
+  a.st = r->state();
+  a.k = k;
+  a.beta = beta;
+  a.rnd = rnd;
+  a.key_out = key_out;
+  a.slot_out = slot_out;
+  a.weight_out = weight_out;
+  a.mass = r->mass();
+  a.ticket = r->ticket();
+  a.act = r->act();
+  a.act_bytes = r->cfg.act_bytes;
+  a.ret = r->ret();
+  a.gacc = r->gacc();
+  a.act_out = static_cast<uint8_t *>(act_out);
+  a.ret_out = ret_out;
+  a.gacc_out = gacc_out;
+  const uint32_t waves = 4;
+  const size_t lds = ((size_t)r->tv.n_top + waves + 1) * sizeof(uint64_t);
+  sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds, stream>>>(a);
+  APEX_HIP(hipGetLastError());
+  if (obs_out) {
+    const RowMap by_slot{slot_out, nullptr, 0};
+    const RowMap ident{nullptr, nullptr, 0};
+    int rc = launch_copy(r->obs(), by_slot, obs_out, ident, (uint64_t)num_batches * k, r->cfg.obs_bytes, stream);
+    if (rc != APEX_OK) return rc;
+  }
+  return APEX_OK;
+}
+
+int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *key, const float *prio,
+                                  void *hip_stream)
+{
+  if (!r || (m && (!key || !prio))) return APEX_ERR_INVALID_ARG;
+  if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
+  if (m == 0) return APEX_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const dim3 grid(blocks_for(m, 256)), block(256);
+  update_claim_kernel<<<grid, block, 0, stream>>>(r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim());
+  update_apply_kernel<<<grid, block, 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim());
+  APEX_HIP(hipGetLastError());
+  return APEX_OK;
+}
+
+int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream)
+{
+  if (!r) return APEX_ERR_INVALID_ARG;
+  const uint64_t size = r->tail - r->head;
+  const uint64_t e = size > r->cfg.capacity ? size - r->cfg.capacity : 0;
+  if (evicted_out) *evicted_out = e;
+  if (e == 0) return APEX_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  evict_leaves_kernel<<<dim3(blocks_for(e, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), e);
+  advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), e, 0);
+  APEX_HIP(hipGetLastError());
+  r->head += e;
+  return APEX_OK;
+}
+
+int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out, void *hip_stream)
+{
+  if (!r || !out) return APEX_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceState st;
+  APEX_HIP(hipMemcpyAsync(&st, r->state(), sizeof st, hipMemcpyDeviceToHost, stream));
+  // root = sum of the top level (at most kTopMax words)
+  static thread_local uint64_t top[kTopMax];
+  APEX_HIP(hipMemcpyAsync(top, r->tv.level[r->tv.nlev - 1], (size_t)r->tv.n_top * 8, hipMemcpyDeviceToHost, stream));
+  APEX_HIP(hipStreamSynchronize(stream));
+  uint64_t root = 0;
+  for (uint32_t i = 0; i < r->tv.n_top; ++i) root += top[i];
+  out->size = st.tail - st.head;
+  out->head = st.head;
+  out->tail = st.tail;
+  out->root = root;
+  out->n_stale_dropped = st.n_stale;
+  out->n_clamped = st.n_clamped;
+  return APEX_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,419 @@
+// HIP kernels of the replay memory (gfx950).  Host-side entry points are in apex_replay.hip.
+//
+// Data layout in HBM
+//   payload ring   obs[P][obs_bytes], act[P][act_bytes], ret[P], gacc[P]   (structure of arrays)
+//   sum tree       level 0 = one uint64 mass per slot; node i of level l+1 = sum of nodes
+//                  [64 i, 64 i + 64) of level l; levels are added until one has at most kTopMax
+//                  nodes.  A wavefront reads the 64 children of a node as one coalesced 512-byte
+//                  row; the top level is staged and prefix-summed in LDS by every workgroup.
+//   device state   head, tail, counters: read by the kernels, so the same launches can be replayed.
+// The set of transitions and the sampled indices do not depend on this shape: a sample is
+// defined by the cumulative mass in slot order, whatever tree sums it up.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "quantise.hpp"
+#include "wave.hpp"
+
+namespace apex {
+
+constexpr uint32_t kFanoutLog2 = 6;
+constexpr uint32_t kFanout = 1u << kFanoutLog2;
+constexpr uint32_t kTopMax = 4608;  // 36 KB of LDS; covers 2^24 + 2^20 slots with three levels
+constexpr uint32_t kMaxLevels = 8;
+
+struct DeviceState {
+  uint64_t head, tail;      // valid keys: head <= key < tail
+  uint64_t n_stale, n_clamped;
+};
+
+struct TreeView {
+  uint64_t *level[kMaxLevels];
+  uint32_t nlev;   // level nlev-1 is the top
+  uint32_t n_top;  // nodes of the top level
+  uint64_t P;      // ring size
+};
+
+// Adds delta (mod 2^64) to every ancestor of `slot` above level 0.
+__device__ __forceinline__ void add_to_ancestors(const TreeView &tv, uint64_t slot, uint64_t delta)
+{
+  uint64_t idx = slot;
+  for (uint32_t l = 1; l < tv.nlev; ++l) {
+    idx >>= kFanoutLog2;
+    atomic_add_u64(tv.level[l] + idx, delta);
+  }
+}
+
+// Same, for a wave whose active lanes hold neighbouring slots (adds, evictions): lanes under one
+// level-1 node are summed first, so each node receives one atomic per wave instead of up to 64.
+// Must be called by all 64 lanes; `active` marks the lanes that carry a delta.
+__device__ __forceinline__ void add_to_ancestors_grouped(const TreeView &tv, bool active, uint64_t slot, uint64_t delta)
+{
+  const int lane = lane_id();
+  const uint64_t node1 = slot >> kFanoutLog2;
+  uint64_t todo = __ballot(active);
+  while (todo) {
+    const int leader = __ffsll((unsigned long long)todo) - 1;
+    const uint64_t node = __shfl(node1, leader, kWave);
+    const bool mine = active && node1 == node;
+    const uint64_t sum = wave_sum(mine ? delta : 0);
+    if (lane == leader) {
+      uint64_t idx = node;
+      for (uint32_t l = 1; l < tv.nlev; ++l) {
+        atomic_add_u64(tv.level[l] + idx, sum);
+        idx >>= kFanoutLog2;
+      }
+    }
+    todo &= ~__ballot(mine);
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// n-step priorities: one thread per transition (Algorithm 1, ComputePriorities; Sections 3.1, 3.2)
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void nstep_kernel(uint32_t S, uint32_t T, uint32_t n, uint32_t A,
+                                                    const float *__restrict__ q_online,
+                                                    const float *__restrict__ q_target,
+                                                    const int32_t *__restrict__ action,
+                                                    const float *__restrict__ reward,
+                                                    const float *__restrict__ discount, QuantParams qp,
+                                                    float *__restrict__ prio, float *__restrict__ ret,
+                                                    float *__restrict__ gacc, uint64_t *__restrict__ prio_fx)
+{
+  const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (uint64_t)S * T) return;
+  const uint32_t s = (uint32_t)(gid / T), t = (uint32_t)(gid - (uint64_t)s * T);
+  const uint64_t row0 = (uint64_t)s * (T + n);  // first row of this stream
+  const float *rw = reward + row0 + t;
+  const float *dc = discount + row0 + t;
+
+  float R = 0.0f;
+  for (int j = (int)n - 1; j >= 0; --j) R = __builtin_fmaf(dc[j], R, rw[j]);  // Horner, one rounding per step
+  float G = 1.0f;
+  for (uint32_t j = 0; j < n; ++j) G = G * dc[j];
+
+  const float *qrow = q_online + (row0 + t + n) * A;
+  uint32_t best = 0;
+  float vbest = qrow[0];
+  for (uint32_t a = 1; a < A; ++a) {
+    const float v = qrow[a];
+    if (v > vbest) {
+      vbest = v;
+      best = a;
+    }
+  }
+  const float boot = q_target[(row0 + t + n) * A + best];
+  uint32_t at = (uint32_t)action[row0 + t];
+  if (at >= A) at = A - 1;  // keeps a corrupt action index inside the row
+  const float target = __builtin_fmaf(G, boot, R);
+  const float delta = target - q_online[(row0 + t) * A + at];
+  const float p = __builtin_fabsf(delta);
+  ret[gid] = R;
+  gacc[gid] = G;
+  prio[gid] = p;
+  if (prio_fx) {
+    bool c;
+    prio_fx[gid] = quantise_priority(p, qp, &c);
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// row copies: payload into the ring (add) and out of it (gather)
+// --------------------------------------------------------------------------------------------
+// Row i of the source / destination is found through a RowMap: an index array (gather by slot),
+// a ring position read from device memory (keys base+i, slot = key mod ring), or the identity.
+struct RowMap {
+  const uint32_t *index;     // row = index[i]
+  const uint64_t *ring_key;  // row = (*ring_key + i) mod ring
+  uint64_t ring;
+};
+
+__device__ __forceinline__ uint64_t map_row(const RowMap &m, uint64_t i)
+{
+  if (m.index) return m.index[i];
+  if (m.ring_key) return (*m.ring_key + i) % m.ring;
+  return i;
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// Long rows (frame stacks): a workgroup copies kUnroll * blockDim consecutive vectors of one row,
+// all loads issued before the first store so that a whole row can be in flight.
+template <typename Vec, int kUnroll>
+__global__ __launch_bounds__(256) void copy_rows_long_kernel(const uint8_t *__restrict__ src, RowMap smap,
+                                                             uint8_t *__restrict__ dst, RowMap dmap,
+                                                             uint32_t vecs_per_row, uint32_t chunks_per_row,
+                                                             uint64_t row_bytes)
+{
+  const uint32_t row = blockIdx.x / chunks_per_row;
+  const uint32_t chunk = blockIdx.x - row * chunks_per_row;
+  const Vec *s = reinterpret_cast<const Vec *>(src + map_row(smap, row) * row_bytes);
+  Vec *d = reinterpret_cast<Vec *>(dst + map_row(dmap, row) * row_bytes);
+  const uint32_t v0 = chunk * (kUnroll * blockDim.x) + threadIdx.x;
+  Vec tmp[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t v = v0 + u * blockDim.x;
+    if (v < vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+  }
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t v = v0 + u * blockDim.x;
+    if (v < vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+  }
+}
+
+// Short rows: 2^lanes_log2 lanes per row, several rows per workgroup.
+template <typename Vec>
+__global__ __launch_bounds__(256) void copy_rows_short_kernel(const uint8_t *__restrict__ src, RowMap smap,
+                                                              uint8_t *__restrict__ dst, RowMap dmap,
+                                                              uint64_t nrows, uint32_t vecs_per_row,
+                                                              uint32_t lanes_log2, uint64_t row_bytes)
+{
+  const uint32_t rows_per_block = blockDim.x >> lanes_log2;
+  const uint64_t row = (uint64_t)blockIdx.x * rows_per_block + (threadIdx.x >> lanes_log2);
+  const uint32_t v = threadIdx.x & ((1u << lanes_log2) - 1);
+  if (row >= nrows || v >= vecs_per_row) return;
+  const Vec *s = reinterpret_cast<const Vec *>(src + map_row(smap, row) * row_bytes);
+  Vec *d = reinterpret_cast<Vec *>(dst + map_row(dmap, row) * row_bytes);
+  d[v] = s[v];
+}
+
+// --------------------------------------------------------------------------------------------
+// add: masses of the new keys, and their sums into the upper levels
+// --------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, DeviceState *__restrict__ st, uint64_t count,
+                                                         const float *__restrict__ prio, QuantParams qp)
+{
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool active = i < count;
+  uint64_t slot = 0, q = 0;
+  bool clamped = false;
+  if (active) {
+    slot = (st->tail + i) % tv.P;
+    q = quantise_priority(prio[i], qp, &clamped);
+    tv.level[0][slot] = q;  // the slot was empty (mass 0): the ring is never over-filled
+  }
+  add_to_ancestors_grouped(tv, active, slot, q);
+  const uint64_t nc = __popcll(__ballot(clamped));
+  if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
+}
+
+// evict: zero the masses of the e oldest keys and take them out of the upper levels
+__global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, const DeviceState *__restrict__ st, uint64_t e)
+{
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool active = i < e;
+  uint64_t slot = 0, old = 0;
+  if (active) {
+    slot = (st->head + i) % tv.P;
+    old = tv.level[0][slot];
+    tv.level[0][slot] = 0;
+  }
+  add_to_ancestors_grouped(tv, active, slot, 0 - old);
+}
+
+// One thread, after the kernels that needed the old values.
+__global__ void advance_state_kernel(DeviceState *st, uint64_t head_inc, uint64_t tail_inc)
+{
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    st->head += head_inc;
+    st->tail += tail_inc;
+  }
+}
+
+// --------------------------------------------------------------------------------------------
+// update: two passes so that, of several pairs naming one key, the last one wins
+// --------------------------------------------------------------------------------------------
+// pass 1: every valid pair bids its position for the slot (highest position wins)
+__global__ __launch_bounds__(256) void update_claim_kernel(uint64_t P, DeviceState *__restrict__ st, uint32_t m,
+                                                           const uint64_t *__restrict__ key,
+                                                           uint32_t *__restrict__ claim)
+{
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  bool stale = false;
+  if (i < m) {
+    const uint64_t k = key[i];
+    if (k >= st->head && k < st->tail)
+      __hip_atomic_fetch_max(claim + (k % P), i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      stale = true;
+  }
+  const uint64_t ns = __popcll(__ballot(stale));
+  if (ns && lane_id() == 0) atomic_add_u64(&st->n_stale, ns);
+}
+
+// pass 2: the winner of a slot writes the new mass, moves the difference up, and clears the bid
+__global__ __launch_bounds__(256) void update_apply_kernel(TreeView tv, DeviceState *__restrict__ st, uint32_t m,
+                                                           const uint64_t *__restrict__ key,
+                                                           const float *__restrict__ prio, QuantParams qp,
+                                                           uint32_t *__restrict__ claim)
+{
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  bool clamped = false;
+  if (i < m) {
+    const uint64_t k = key[i];
+    if (k >= st->head && k < st->tail) {
+      const uint64_t slot = k % tv.P;
+      const uint64_t q = quantise_priority(prio[i], qp, &clamped);
+      if (claim[slot] == i + 1) {
+        const uint64_t old = tv.level[0][slot];
+        tv.level[0][slot] = q;
+        add_to_ancestors(tv, slot, q - old);
+        claim[slot] = 0;
+      }
+    }
+  }
+  const uint64_t nc = __popcll(__ballot(clamped));
+  if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
+}
+
+// --------------------------------------------------------------------------------------------
+// sample: stratified descent, one wavefront per sample; importance weights by the last
+// workgroup of each batch
+// --------------------------------------------------------------------------------------------
+struct SampleArgs {
+  TreeView tv;
+  const DeviceState *st;
+  uint32_t k;                // samples per batch
+  float beta;
+  const uint64_t *rnd;       // [nb,k]
+  uint64_t *key_out;         // [nb,k] or null
+  uint32_t *slot_out;        // [nb,k]
+  float *weight_out;         // [nb,k] or null
+  uint64_t *mass;            // scratch [nb,k]
+  uint32_t *ticket;          // scratch [nb], zero between calls
+  // small payload columns, gathered here; the observation rows are copied by copy_rows_*
+  const uint8_t *act;
+  uint32_t act_bytes;
+  const float *ret, *gacc;
+  uint8_t *act_out;
+  float *ret_out, *gacc_out;
+};
+
+// Dynamic LDS: n_top uint64 (exclusive prefix sums of the top level) + blockDim/64 + 1 words.
+__global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
+{
+  extern __shared__ uint64_t lds[];
+  const TreeView &tv = a.tv;
+  const uint32_t n_top = tv.n_top;
+  uint64_t *pre = lds;
+  uint64_t *wave_total = lds + n_top;
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x, nwave = nthr / kWave;
+  const uint32_t wave = tid / kWave;
+  const int lane = lane_id();
+
+  // ---- top level -> LDS, exclusive prefix sums in place
+  const uint64_t *top = tv.level[tv.nlev - 1];
+  for (uint32_t i = tid; i < n_top; i += nthr) pre[i] = top[i];
+  __syncthreads();
+  const uint32_t per = (n_top + nthr - 1) / nthr;
+  const uint32_t lo = min(tid * per, n_top), hi = min(lo + per, n_top);
+  uint64_t mine = 0;
+  for (uint32_t i = lo; i < hi; ++i) mine += pre[i];
+  const uint64_t incl = wave_inclusive_scan(mine);
+  if (lane == kWave - 1) wave_total[wave] = incl;
+  __syncthreads();
+  uint64_t before = 0, total = 0;
+  for (uint32_t w = 0; w < nwave; ++w) {
+    const uint64_t t = wave_total[w];
+    if (w < wave) before += t;
+    total += t;
+  }
+  uint64_t run = before + incl - mine;
+  for (uint32_t i = lo; i < hi; ++i) {
+    const uint64_t v = pre[i];
+    pre[i] = run;
+    run += v;
+  }
+  __syncthreads();
+
+  // ---- one sample per wavefront
+  const uint32_t b = blockIdx.y;
+  const uint32_t j = blockIdx.x * nwave + wave;
+  if (j < a.k) {
+    const uint64_t o = (uint64_t)b * a.k + j;
+    const uint64_t w = total / a.k;                       // stratum width
+    uint64_t x = (uint64_t)j * w + __umul64hi(a.rnd[o], w);  // point inside stratum j
+
+    // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
+    const uint32_t stride = (n_top + kWave - 1) / kWave;
+    uint32_t p0 = lane * stride;
+    uint32_t cnt = __popcll(__ballot(p0 < n_top && pre[p0] <= x));
+    const uint32_t base = (cnt - 1) * stride;  // pre[0] = 0 <= x, so cnt >= 1
+    cnt = 0;
+    for (uint32_t off = 0; off < stride; off += kWave) {
+      const uint32_t p1 = base + off + lane;
+      cnt += __popcll(__ballot(off + lane < stride && p1 < n_top && pre[p1] <= x));
+    }
+    uint64_t idx = base + cnt - 1;
+    uint64_t mass = ((idx + 1 < n_top) ? pre[idx + 1] : total) - pre[idx];
+    x -= pre[idx];
+
+    // lower levels: 64 children per step, prefix sum across the wave, first child whose
+    // running sum exceeds the remainder
+    for (int l = (int)tv.nlev - 2; l >= 0; --l) {
+      const uint64_t c = tv.level[l][idx * kFanout + lane];
+      const uint64_t sc = wave_inclusive_scan(c);
+      const uint64_t hit = __ballot(sc > x);
+      const int sel = hit ? __ffsll((unsigned long long)hit) - 1 : kWave - 1;
+      const uint64_t c_sel = __shfl(c, sel, kWave);
+      const uint64_t s_sel = __shfl(sc, sel, kWave);
+      x -= s_sel - c_sel;
+      idx = idx * kFanout + sel;
+      mass = c_sel;
+    }
+    const uint64_t slot = idx;
+    if (lane == 0) {
+      const uint64_t head = a.st->head;
+      a.slot_out[o] = (uint32_t)slot;
+      if (a.key_out) a.key_out[o] = head + ((slot + tv.P - head % tv.P) % tv.P);
+      __hip_atomic_store(a.mass + o, mass, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (a.ret_out) a.ret_out[o] = a.ret[slot];
+      if (a.gacc_out) a.gacc_out[o] = a.gacc[slot];
+    }
+    if (a.act_out)
+      for (uint32_t by = lane; by < a.act_bytes; by += kWave)
+        a.act_out[o * a.act_bytes + by] = a.act[slot * a.act_bytes + by];
+  }
+
+  // ---- importance weights: the workgroup that finishes a batch last normalises it
+  if (!a.weight_out) return;
+  __shared__ uint32_t s_last;
+  __threadfence();
+  __syncthreads();
+  if (tid == 0) {
+    const uint32_t done = __hip_atomic_fetch_add(a.ticket + b, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (done == gridDim.x - 1);
+    if (s_last) __hip_atomic_store(a.ticket + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!s_last) return;
+  __threadfence();
+  const uint64_t *bm = a.mass + (uint64_t)b * a.k;
+  uint64_t mn = ~0ull;
+  for (uint32_t i = tid; i < a.k; i += nthr) {
+    const uint64_t v = __hip_atomic_load(bm + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    mn = v < mn ? v : mn;
+  }
+  mn = wave_min(mn);
+  __syncthreads();  // everyone is done with wave_total's first use
+  if (lane == 0) wave_total[wave] = mn;
+  __syncthreads();
+  for (uint32_t w = 0; w < nwave; ++w) mn = wave_total[w] < mn ? wave_total[w] : mn;
+  // (N P_i)^-beta / max_j (N P_j)^-beta  ==  (min_j mass_j / mass_i)^beta
+  for (uint32_t i = tid; i < a.k; i += nthr) {
+    const uint64_t v = __hip_atomic_load(bm + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    a.weight_out[(uint64_t)b * a.k + i] = (float)pow((double)mn / (double)v, (double)a.beta);
+  }
+}
+
+// zero fill (hipMemset is avoided so that the library's launches stay replayable)
+__global__ __launch_bounds__(256) void fill_zero_kernel(uint64_t *p, uint64_t n)
+{
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+    p[i] = 0;
+}
+
+}  // namespace apex

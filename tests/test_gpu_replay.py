@@ -1,0 +1,169 @@
+"""GPU parity: the replay verbs against the oracle, element by element, on small and ragged shapes."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_close, assert_sample_equal, check_gpu_tree, dev, host
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+U64 = 1 << 64
+
+
+def make_pair(C, P, ob, ab, **kw):
+    from paper_1803_00933_amd import apex
+    return apex.Replay(C, P, ob, ab, **kw), oracle.Replay(C, P, ob, ab, **kw)
+
+
+def add_both(g, o, rng, cnt, dist=lambda rng, n: rng.lognormal(0, 1, n)):
+    from paper_1803_00933_amd import apex
+    obs = rng.integers(0, 256, (cnt, o.obs_bytes), dtype=np.uint8)
+    act = rng.integers(0, 256, (cnt, o.act_bytes), dtype=np.uint8)
+    ret, gacc = rng.standard_normal(cnt).astype(F32), rng.random(cnt).astype(F32)
+    prio = dist(rng, cnt).astype(F32)
+    rco, fo = o.add(prio, obs, act, ret, gacc)
+    rcg, fg = g.add(dev(prio), dev(obs), dev(act), dev(ret), dev(gacc))
+    assert rcg == rco
+    if rco == 0:
+        assert fg == fo
+    return rco
+
+
+def sample_both(g, o, rng, nb, k, beta=0.4, rnd=None):
+    rnd = rng.integers(0, U64, nb * k, dtype=np.uint64) if rnd is None else rnd
+    rco, oo = o.sample(nb, k, beta, rnd)
+    rcg, go = g.sample(nb, k, beta, dev(rnd))
+    assert rcg == rco
+    if rco == 0:
+        torch.cuda.synchronize()
+        assert_sample_equal(go, oo)
+    return oo
+
+
+@pytest.mark.parametrize("P,C,ob,ab", [
+    (100, 80, 32, 4),            # one tree level, everything in LDS
+    (8192, 4096, 32, 4),         # two levels
+    (5000, 4000, 12, 8),         # ragged level sizes, dword copy path
+    (300_000, 250_000, 7, 3),    # three levels with ragged tails, byte copy path
+    (70_000, 65_000, 4112, 32),  # long-row copy path with a partial last chunk
+])
+def test_random_operation_sequences(P, C, ob, ab):
+    rng = np.random.default_rng(P)
+    g, o = make_pair(C, P, ob, ab)
+    pareto = lambda rng, n: np.where(rng.random(n) < 0.2, 0.0, rng.pareto(1.1, n) + 1.0)
+    for it in range(12):
+        cnt = int(rng.integers(1, max(2, P // 4)))
+        if o.size + cnt > P:
+            assert add_both(g, o, rng, cnt) == oracle.ERR_FULL
+            cnt = P - o.size
+        if cnt:
+            assert add_both(g, o, rng, cnt, pareto if it % 2 else (lambda r, n: r.lognormal(0, 2, n))) == 0
+        check_gpu_tree(g, o)
+        for nb, k in ((1, 32), (3, 50), (1, 1), (2, 257)):
+            oo = sample_both(g, o, rng, nb, k, beta=float(rng.uniform(0, 1)))
+        # learner feedback: the sampled keys (with their repeats), some stale and some future keys
+        keys = np.concatenate([oo["key"], rng.integers(0, max(1, o.head), 5).astype(np.uint64),
+                               np.array([o.tail, o.tail + 7, U64 - 1], np.uint64), oo["key"][:40]])
+        newp = pareto(rng, len(keys)).astype(F32)
+        newp[:3] = [np.nan, np.inf, 1e30]
+        assert o.update_priorities(keys, newp) == 0
+        assert g.update_priorities(dev(keys), dev(newp)) == 0
+        check_gpu_tree(g, o)
+        rco, eo = o.evict()
+        rcg, eg = g.evict()
+        assert (rcg, eg) == (rco, eo)
+        check_gpu_tree(g, o)
+        sample_both(g, o, rng, 2, 64)
+
+
+def test_extreme_uniforms_and_edges():
+    rng = np.random.default_rng(1)
+    g, o = make_pair(6000, 6000, 16, 4)
+    add_both(g, o, rng, 6000)
+    for fill in (0, U64 - 1, 1 << 63):
+        sample_both(g, o, rng, 2, 100, rnd=np.full(200, fill, np.uint64))
+    sample_both(g, o, rng, 1, 9000)                      # more samples than transitions
+    sample_both(g, o, rng, 1, 65536 // 2)
+    # all mass on one transition
+    g2, o2 = make_pair(5000, 5000, 16, 4, alpha=1.0, eps=0.0)
+    add_both(g2, o2, rng, 5000, lambda r, n: np.where(np.arange(n) == 4321, 1e6, 0.0))
+    oo = sample_both(g2, o2, rng, 1, 64)
+    assert (oo["slot"] == 4321).sum() >= 63
+
+
+def test_alpha_zero_and_beta_edges():
+    rng = np.random.default_rng(2)
+    g, o = make_pair(10_000, 10_000, 16, 4, alpha=0.0)
+    add_both(g, o, rng, 10_000)
+    oo = sample_both(g, o, rng, 4, 128)
+    assert np.all(oo["weight"] == 1.0)
+    g, o = make_pair(10_000, 10_000, 16, 4)
+    add_both(g, o, rng, 10_000)
+    for beta in (0.0, 1.0, 0.4):
+        sample_both(g, o, rng, 2, 512, beta=beta)
+
+
+def test_status_codes():
+    from paper_1803_00933_amd import apex
+    rng = np.random.default_rng(3)
+    g, o = make_pair(100, 128, 16, 4, min_size_to_sample=50)
+    rnd = dev(np.zeros(8, np.uint64))
+    assert g.sample(1, 8, 0.4, rnd)[0] == apex.ERR_NOT_READY == o.sample(1, 8, 0.4, np.zeros(8, np.uint64))[0]
+    add_both(g, o, rng, 49)
+    assert g.sample(1, 8, 0.4, rnd)[0] == apex.ERR_NOT_READY
+    add_both(g, o, rng, 1)
+    assert g.sample(1, 8, 0.4, rnd)[0] == apex.OK
+    g2, o2 = make_pair(100, 128, 16, 4)
+    assert g2.sample(1, 8, 0.4, rnd)[0] == apex.ERR_EMPTY == o2.sample(1, 8, 0.4, np.zeros(8, np.uint64))[0]
+    assert g.sample(0, 8, 0.4, rnd)[0] == apex.ERR_INVALID_ARG
+    assert g.sample(1, 0, 0.4, rnd)[0] == apex.ERR_INVALID_ARG
+    assert g.sample(1, 8, -1.0, rnd)[0] == apex.ERR_INVALID_ARG
+    big = dev(np.zeros(8, np.uint64))
+    assert apex.lib.apex_replay_sample(g.h, 2, 40000, 0.4, big.data_ptr(), None, big.data_ptr(), *([None] * 6)) \
+        == apex.ERR_TOO_LARGE
+    assert apex.lib.apex_replay_sample(g.h, 1, 8, 0.4, big.data_ptr(), None, None, *([None] * 6)) == apex.ERR_INVALID_ARG
+    assert g.evict() == (0, 0) and g.add(dev(np.zeros(0, F32)))[0] == apex.OK
+    assert g.update_priorities(dev(np.zeros(0, np.uint64)), dev(np.zeros(0, F32))) == apex.OK
+    torch.cuda.synchronize()
+    check_gpu_tree(g, o)
+
+
+def test_tiny_workload_full_trace():
+    """The small configuration end to end: 200 rounds of {n-step priorities, add 400, sample 32,
+    update with fresh |N(0,1)| errors, evict}; every output of every round is compared."""
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["tiny"]
+    g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes, alpha=w.alpha, eps=w.eps, frac_bits=w.frac_bits)
+    key0 = 0
+    for rnd_i in range(200):
+        d = synth.actor_round(w, rnd_i)
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+        rc, prio, ret, gacc, fx = apex.nstep_priorities(dev(d["q_online"]), dev(d["q_target"]), dev(d["action"]),
+                                                        dev(d["reward"]), dev(d["discount"]), w.n, w.alpha, w.eps,
+                                                        w.frac_bits, w.max_slots)
+        assert rc == 0
+        obs = synth.obs_rows(w.seed, key0, w.add_count, w.obs_bytes)
+        rco, fo = o.add(ref[0].reshape(-1), obs, d["act"], ref[1].reshape(-1), ref[2].reshape(-1))
+        rcg, fg = g.add(prio.view(-1), dev(obs), dev(d["act"]), ret.view(-1), gacc.view(-1))   # device to device
+        assert (rcg, fg) == (rco, fo) == (0, key0)
+        key0 += w.add_count
+        torch.cuda.synchronize()
+        assert np.array_equal(host(fx, np.uint64), ref[3])
+        rnd = synth.uniforms(w.seed, rnd_i, 1, w.k).reshape(-1)
+        rco, oo = o.sample(1, w.k, w.beta, rnd)
+        rcg, go = g.sample(1, w.k, w.beta, dev(rnd))
+        assert rcg == rco == 0
+        torch.cuda.synchronize()
+        assert_sample_equal(go, oo)
+        assert np.array_equal(oo["obs"], np.concatenate([synth.obs_rows(w.seed, int(kk), 1, w.obs_bytes)
+                                                         for kk in oo["key"]]))
+        newp = synth.priorities(w.td_dist, w.seed, rnd_i, w.k)
+        assert o.update_priorities(oo["key"], newp) == 0
+        assert g.update_priorities(go["key"], dev(newp)) == 0
+        assert g.evict() == o.evict()
+        if rnd_i % 10 == 9 or rnd_i < 12:
+            st = check_gpu_tree(g, o)
+            assert st["size"] == min(key0, w.capacity)
+    check_gpu_tree(g, o)
