@@ -1,0 +1,248 @@
+#!/usr/bin/env python3
+"""Throughput of the replay hot path on one MI355X, Atari-shaped workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one learner step of the paper's Atari setting (Section 4.1) served from a memory of
+2,000,000 transitions of 84x84x4 uint8 frames: sample a prioritized batch of 512 (stratified
+descent, importance weights, gather of the frame stacks) and write 512 new priorities back.
+The actors' side runs inside the timed region at the paper's ratio: every 25 steps one round of
+360 streams x 50 transitions goes through n-step priorities and add (about 12.5K inserts per
+19 learner steps), and every 100 steps the excess above 2M is evicted, oldest first.
+All inputs are synthetic, seeded, and resident in HBM before the clock starts.
+
+Prints one JSON line (see the keys at the bottom).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+ADD_EVERY, EVICT_EVERY = 25, 100
+
+# HBM bytes per launch of the gather kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
+# scaled by a plain copy of known size; see profiles/.  None until measured.
+MEASURED_GATHER_TRAFFIC_BYTES = None
+
+
+def dev(a):
+    import torch
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.uint64:
+        a = a.view(np.int64)
+    return torch.from_numpy(a).to("cuda:0")
+
+
+class GpuJob:
+    """The device-resident replay memory plus every pre-generated input of the timed loop."""
+
+    def __init__(self, w, steps_total, log):
+        import torch
+        from paper_1803_00933_amd import apex, synth
+        self.torch, self.apex, self.synth, self.w = torch, apex, synth, w
+        self.rep = apex.Replay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes, w.alpha, w.eps, w.frac_bits)
+        self.n_pool = 4
+        self.rounds = []
+        for i in range(self.n_pool):
+            d = synth.actor_round(w, i)
+            t = {k: dev(v) for k, v in d.items()}
+            S, T = w.streams, w.chunk
+            t["out"] = (torch.empty((S, T), dtype=torch.float32, device="cuda:0"),
+                        torch.empty((S, T), dtype=torch.float32, device="cuda:0"),
+                        torch.empty((S, T), dtype=torch.float32, device="cuda:0"), None)
+            self.rounds.append(t)
+        self.obs_stage = torch.empty((w.add_count, w.obs_bytes), dtype=torch.uint8, device="cuda:0")
+        self.step = 0
+        self.key0 = 0
+        # prefill to capacity with hashed frame bytes, then trim
+        t0 = time.time()
+        n_fill = -(-w.capacity // w.add_count)
+        for i in range(n_fill):
+            self.obs_stage.copy_(synth.obs_rows_torch(w.seed, self.key0, w.add_count, w.obs_bytes, "cuda:0"))
+            self.add_round(i)
+        rc, e = self.rep.evict()
+        assert rc == 0
+        torch.cuda.synchronize()
+        st = self.rep.stats()
+        assert st["size"] == w.capacity, st
+        log("prefill: %d rounds, %.1f s, size %d, root %d" % (n_fill, time.time() - t0, st["size"], st["root"]))
+        # learner inputs for every step
+        n = steps_total
+        self.rnd = dev(np.concatenate([synth.uniforms(w.seed, s, 1, w.k) for s in range(n)]))
+        self.td = dev(np.stack([synth.priorities(w.td_dist, w.seed, s, w.k) for s in range(n)]))
+        self.outs = [self.rep.alloc_sample_outputs(1, w.k) for _ in range(4)]
+        # raw argument lists per step: the timed loop only marshals integers into the C ABI
+        self.stream = torch.cuda.current_stream().cuda_stream
+        self.sample_args, self.update_args = [], []
+        for s in range(n):
+            o = self.outs[s % len(self.outs)]
+            self.sample_args.append((self.rep.h, 1, w.k, w.beta, self.rnd[s].data_ptr(), o["key"].data_ptr(),
+                                     o["slot"].data_ptr(), o["weight"].data_ptr(), o["obs"].data_ptr(),
+                                     o["act"].data_ptr(), o["ret"].data_ptr(), o["gacc"].data_ptr(), self.stream))
+            self.update_args.append((self.rep.h, w.k, o["key"].data_ptr(), self.td[s].data_ptr(), self.stream))
+
+    def add_round(self, i):
+        w, apex = self.w, self.apex
+        t = self.rounds[i % self.n_pool]
+        rc, prio, ret, gacc, _ = apex.nstep_priorities(t["q_online"], t["q_target"], t["action"], t["reward"],
+                                                       t["discount"], w.n, w.alpha, w.eps, w.frac_bits, w.max_slots,
+                                                       want_fx=False, out=t["out"])
+        assert rc == 0
+        rc, first = self.rep.add(prio.view(-1), self.obs_stage, t["act"], ret.view(-1), gacc.view(-1))
+        assert rc == 0, rc
+        self.key0 += w.add_count
+
+    def learner_step(self, s):
+        lib = self.apex.lib
+        rc = lib.apex_replay_sample(*self.sample_args[s])
+        assert rc == 0, rc
+        rc = lib.apex_replay_update_priorities(*self.update_args[s])
+        assert rc == 0, rc
+
+    def run(self, first, count, with_actors=True):
+        for s in range(first, first + count):
+            self.learner_step(s)
+            if with_actors:
+                if (s + 1) % ADD_EVERY == 0:
+                    self.add_round(s // ADD_EVERY)
+                if (s + 1) % EVICT_EVERY == 0:
+                    rc, e = self.rep.evict()
+                    assert rc == 0
+
+    def timed(self, first, count, with_actors=True):
+        torch = self.torch
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        self.run(first, count, with_actors)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def gather_kernel_ms(self, launches):
+        """Average duration of the dominant kernel (frame-stack gather), HIP events on the launch stream."""
+        torch = self.torch
+        out = self.outs[0]
+        slot = out["slot"]
+        for _ in range(10):
+            self.rep.gather(slot, out["obs"])
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(launches):
+            self.rep.gather(slot, out["obs"])
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / launches
+
+
+def cpu_baseline(w, budget_steps, log):
+    """The oracle, untouched, on one host core: same schedule, bounded number of steps."""
+    import oracle
+    from paper_1803_00933_amd import synth
+    payload_slots = 1 << 15                      # frame rows aliased modulo 32768 slots (0.9 GB): timing only
+    o = oracle.Replay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes, w.alpha, w.eps, w.frac_bits,
+                      payload_slots=payload_slots)
+    rng = np.random.default_rng(0)
+    n_fill = -(-w.capacity // w.add_count)
+    for i in range(n_fill):
+        o.add(synth.priorities("lognormal1", w.seed, i, w.add_count, tag="bulk"))
+    o.evict()
+    obs = rng.integers(0, 256, (w.add_count, w.obs_bytes), dtype=np.uint8)
+    rounds = [synth.actor_round(w, i) for i in range(2)]
+    rnd = [synth.uniforms(w.seed, s, 1, w.k).reshape(-1) for s in range(budget_steps)]
+    td = [synth.priorities(w.td_dist, w.seed, s, w.k) for s in range(budget_steps)]
+    t0 = time.perf_counter()
+    for s in range(budget_steps):
+        rc, out = o.sample(1, w.k, w.beta, rnd[s])
+        o.update_priorities(out["key"], td[s])
+        if (s + 1) % ADD_EVERY == 0:
+            d = rounds[(s // ADD_EVERY) % 2]
+            prio, ret, gacc, _ = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"],
+                                                         d["discount"], w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+            o.add(prio.reshape(-1), obs, d["act"], ret.reshape(-1), gacc.reshape(-1))
+        if (s + 1) % EVICT_EVERY == 0:
+            o.evict()
+    dt = time.perf_counter() - t0
+    log("cpu oracle: %d steps in %.2f s" % (budget_steps, dt))
+    return {"value": w.k * budget_steps / dt, "unit": "transitions/s", "cores": 1, "kind": "oracle",
+            "sample": "%d learner steps of the same schedule (batch %d, add round every %d steps, evict every %d); "
+                      "tree and keys at full size, frame rows aliased modulo %d slots to fit host memory"
+                      % (budget_steps, w.k, ADD_EVERY, EVICT_EVERY, payload_slots),
+            "seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--cpu-steps", type=int, default=2000, help="learner steps timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--quiet", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU (the replay memory lives in one MI355X's HBM); "
+              "--gpus %d is not supported" % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    def log(msg):
+        if not args.quiet:
+            print("[bench] " + msg, file=sys.stderr, flush=True)
+
+    import torch
+    from paper_1803_00933_amd import synth
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    w = synth.WORKLOADS["atari"]
+    K, W = args.steps, args.warmup
+    job = GpuJob(w, W + 2 * K, log)
+
+    job.run(0, W)
+    dt = job.timed(W, K, with_actors=True)
+    log("full schedule: %d steps in %.3f ms (%.2f us/step)" % (K, dt * 1e3, dt / K * 1e6))
+    # learner steps alone, with the memory in the same state of fill (size stays below max_slots: no adds)
+    dt_learner = job.timed(W + K, K, with_actors=False)
+    log("learner steps only: %.2f us/step" % (dt_learner / K * 1e6))
+    st = job.rep.stats()
+    log("state after run: %s" % st)
+
+    gather_ms = job.gather_kernel_ms(500)
+    gather_bytes = 2 * w.k * w.obs_bytes                       # read + write of one batch of frame stacks
+    achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
+    log("gather kernel: %.2f us/launch, %.0f GB/s" % (gather_ms * 1e3, achieved))
+
+    cpu = cpu_baseline(w, args.cpu_steps, log) if args.cpu_steps > 0 else None
+
+    line = {
+        "metric": "sampled transitions/s (sample+IS+gather+update) at 2M slots, batch 512",
+        "value": w.k * K / dt,
+        "unit": "transitions/s",
+        "n_gpus": 1, "steps": K, "warmup": W,
+        "ms_per_step": dt / K * 1e3,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u64",
+        "data": "synthetic",
+        "config": {"workload": "atari: capacity 2,000,000 (ring 2^21) x uint8[84*84*4], 18 actions, n=3, alpha 0.6, "
+                               "beta 0.4, batch 512; add round of 360x50 every 25 steps, FIFO evict every 100",
+                   "capacity": w.capacity, "max_slots": w.max_slots, "obs_bytes": w.obs_bytes, "batch": w.k,
+                   "add_round": w.add_count, "add_every": ADD_EVERY, "evict_every": EVICT_EVERY},
+        "learner_steps_only": {"value": w.k * K / dt_learner, "unit": "transitions/s",
+                               "ms_per_step": dt_learner / K * 1e3,
+                               "priority_updates_per_s": w.k * K / dt_learner},
+        "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel (frame-stack gather)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_GATHER_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,
+                     "us_per_launch": gather_ms * 1e3},
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -172,6 +172,16 @@ int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float
                        float *ret_out, float *gacc_out, void *hip_stream);
 
 /*
+ * The read half of replay.Sample on its own (Appendix "Implementation", "Data Storage": reading
+ * batches of stored tensors): copies the payload of count ring slots, slot[i] < max_slots (device,
+ * u32, e.g. the slot_out of an earlier apex_replay_sample), into obs_out [count,obs_bytes],
+ * act_out [count,act_bytes], ret_out, gacc_out [count]; each output may be NULL.  Lets a caller put
+ * the large copy on another stream than the tree work.  count <= APEX_MAX_SAMPLES_PER_CALL.
+ */
+int apex_replay_gather(apex_replay_t *r, uint64_t count, const uint32_t *slot, void *obs_out, void *act_out,
+                       float *ret_out, float *gacc_out, void *hip_stream);
+
+/*
  * replay.SetPriority (Algorithm 2): mass of key[i] becomes Q(prio[i]) for i in [0,m); key and
  * prio are device arrays.  The result is that of applying the pairs one after the other: of
  * several pairs naming one key the last stands; a pair whose key is not valid any more is

@@ -20,7 +20,8 @@ MAX_BATCHES_PER_CALL = 1024
 TREE_MAX_LEVELS = 8
 
 EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_destroy", "apex_replay_layout",
-           "apex_nstep_priorities", "apex_replay_add", "apex_replay_sample", "apex_replay_update_priorities",
+           "apex_nstep_priorities", "apex_replay_add", "apex_replay_sample", "apex_replay_gather",
+           "apex_replay_update_priorities",
            "apex_replay_evict", "apex_replay_stats", "apex_last_hip_error"]
 
 
@@ -54,6 +55,7 @@ lib.apex_nstep_priorities.argtypes = [_u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp
                                       _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_add.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, C.POINTER(_u64), _vp]
 lib.apex_replay_sample.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_gather.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
 lib.apex_replay_evict.argtypes = [_vp, C.POINTER(_u64), _vp]
 lib.apex_replay_stats.argtypes = [_vp, C.POINTER(Stats), _vp]
@@ -179,6 +181,10 @@ class Replay:
                                     _ptr(out.get("weight")), _ptr(out.get("obs")), _ptr(out.get("act")),
                                     _ptr(out.get("ret")), _ptr(out.get("gacc")), _stream(stream))
         return rc, out
+
+    def gather(self, slot, obs=None, act=None, ret=None, gacc=None, stream=None):
+        return lib.apex_replay_gather(self.h, slot.shape[0], _ptr(slot), _ptr(obs), _ptr(act), _ptr(ret), _ptr(gacc),
+                                      _stream(stream))
 
     def update_priorities(self, key, prio, stream=None):
         return lib.apex_replay_update_priorities(self.h, key.shape[0], _ptr(key), _ptr(prio), _stream(stream))

@@ -42,8 +42,8 @@ struct Geometry {
   uint64_t obs_off, act_off, ret_off, gacc_off, storage_bytes;
   uint32_t nlev;
   uint64_t level_off[kMaxLevels], level_size[kMaxLevels], tree_words;
-  // scratch: DeviceState | tickets | mass | slot | claim
-  uint64_t state_off, ticket_off, mass_off, slot_off, claim_off, scratch_bytes;
+  // scratch: DeviceState | mass | claim
+  uint64_t state_off, mass_off, claim_off, scratch_bytes;
 };
 
 int validate(const apex_replay_config_t *c)
@@ -79,10 +79,8 @@ int geometry(const apex_replay_config_t *c, Geometry *g)
   g->tree_words = off;
 
   g->state_off = 0;
-  g->ticket_off = 256;
-  g->mass_off = g->ticket_off + round_up(APEX_MAX_BATCHES_PER_CALL * 4, 256);
-  g->slot_off = g->mass_off + (uint64_t)APEX_MAX_SAMPLES_PER_CALL * 8;
-  g->claim_off = g->slot_off + (uint64_t)APEX_MAX_SAMPLES_PER_CALL * 4;
+  g->mass_off = 256;
+  g->claim_off = g->mass_off + (uint64_t)APEX_MAX_SAMPLES_PER_CALL * 8;
   g->scratch_bytes = g->claim_off + round_up(P * 4, 256);
   return APEX_OK;
 }
@@ -100,7 +98,6 @@ struct apex_replay {
   TreeView tv;
 
   DeviceState *state() const { return reinterpret_cast<DeviceState *>(scratch + geo.state_off); }
-  uint32_t *ticket() const { return reinterpret_cast<uint32_t *>(scratch + geo.ticket_off); }
   uint64_t *mass() const { return reinterpret_cast<uint64_t *>(scratch + geo.mass_off); }
   uint32_t *claim() const { return reinterpret_cast<uint32_t *>(scratch + geo.claim_off); }
   uint8_t *obs() const { return storage + geo.obs_off; }
@@ -113,17 +110,24 @@ namespace {
 
 // Copies nrows rows of row_bytes bytes; picks the widest vector the row size and the base
 // addresses allow and the long- or short-row kernel.
+// *wa (may be null): importance weights to be written along the way; cleared once a kernel took them on.
 template <typename Vec>
 int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const RowMap &dmap, uint64_t nrows,
-                  uint64_t row_bytes, hipStream_t stream)
+                  uint64_t row_bytes, hipStream_t stream, WeightArgs *wa)
 {
   constexpr int kUnroll = 7;  // 7 * 256 lanes * 16 B = 28,672 B >= one 84x84x4 frame stack
   const uint32_t vpr = (uint32_t)(row_bytes / sizeof(Vec));
   if (vpr > 256) {
     const uint32_t cpr = (vpr + 256 * kUnroll - 1) / (256 * kUnroll);
     if (nrows * cpr > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
-    copy_rows_long_kernel<Vec, kUnroll>
-        <<<dim3((uint32_t)(nrows * cpr)), dim3(256), 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes);
+    const dim3 grid((uint32_t)(nrows * cpr)), block(256);
+    if (wa && wa->weight_out) {
+      copy_rows_long_kernel<Vec, kUnroll, true><<<grid, block, 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, *wa);
+      wa->weight_out = nullptr;
+    } else {
+      copy_rows_long_kernel<Vec, kUnroll, false>
+          <<<grid, block, 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, WeightArgs{nullptr, nullptr, 1, 0.f});
+    }
   } else {
     uint32_t lanes_log2 = 0;
     while ((1u << lanes_log2) < vpr) ++lanes_log2;
@@ -137,15 +141,15 @@ int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const Ro
 }
 
 int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dmap, uint64_t nrows, uint64_t row_bytes,
-                hipStream_t stream)
+                hipStream_t stream, WeightArgs *wa = nullptr)
 {
   if (nrows == 0) return APEX_OK;
   const uintptr_t mis = (uintptr_t)src | (uintptr_t)dst | (uintptr_t)row_bytes;
   const uint8_t *s = static_cast<const uint8_t *>(src);
   uint8_t *d = static_cast<uint8_t *>(dst);
-  if ((mis & 15) == 0) return launch_copy_t<u32x4>(s, smap, d, dmap, nrows, row_bytes, stream);
-  if ((mis & 3) == 0) return launch_copy_t<uint32_t>(s, smap, d, dmap, nrows, row_bytes, stream);
-  return launch_copy_t<uint8_t>(s, smap, d, dmap, nrows, row_bytes, stream);
+  if ((mis & 15) == 0) return launch_copy_t<u32x4>(s, smap, d, dmap, nrows, row_bytes, stream, wa);
+  if ((mis & 3) == 0) return launch_copy_t<uint32_t>(s, smap, d, dmap, nrows, row_bytes, stream, wa);
+  return launch_copy_t<uint8_t>(s, smap, d, dmap, nrows, row_bytes, stream, wa);
 }
 
 inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
@@ -253,8 +257,10 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
 {
   if (!r || (count && !prio)) return APEX_ERR_INVALID_ARG;
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
-  if (first_key_out) *first_key_out = r->tail;
-  if (count == 0) return APEX_OK;
+  if (count == 0) {
+    if (first_key_out) *first_key_out = r->tail;
+    return APEX_OK;
+  }
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const RowMap ident{nullptr, nullptr, 0};
   const RowMap ring{nullptr, &r->state()->tail, r->cfg.max_slots};
@@ -266,6 +272,7 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
   add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), count, prio, r->qp);
   advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), 0, count);
   APEX_HIP(hipGetLastError());
+  if (first_key_out) *first_key_out = r->tail;
   r->tail += count;
   return APEX_OK;
 }
@@ -290,9 +297,7 @@ int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float
   a.rnd = rnd;
   a.key_out = key_out;
   a.slot_out = slot_out;
-  a.weight_out = weight_out;
   a.mass = r->mass();
-  a.ticket = r->ticket();
   a.act = r->act();
   a.act_bytes = r->cfg.act_bytes;
   a.ret = r->ret();
@@ -301,15 +306,36 @@ int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float
   a.ret_out = ret_out;
   a.gacc_out = gacc_out;
   const uint32_t waves = 4;
-  const size_t lds = ((size_t)r->tv.n_top + waves + 1) * sizeof(uint64_t);
+  const size_t lds = ((size_t)r->tv.n_top + waves) * sizeof(uint64_t);
   sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds, stream>>>(a);
   APEX_HIP(hipGetLastError());
+  WeightArgs wa{r->mass(), weight_out, k, beta};
   if (obs_out) {
     const RowMap by_slot{slot_out, nullptr, 0};
     const RowMap ident{nullptr, nullptr, 0};
-    int rc = launch_copy(r->obs(), by_slot, obs_out, ident, (uint64_t)num_batches * k, r->cfg.obs_bytes, stream);
+    int rc = launch_copy(r->obs(), by_slot, obs_out, ident, (uint64_t)num_batches * k, r->cfg.obs_bytes, stream, &wa);
     if (rc != APEX_OK) return rc;
   }
+  if (wa.weight_out) {  // no gather, or short rows: the weights get a small launch of their own
+    batch_weights_kernel<<<dim3(num_batches), dim3(256), 0, stream>>>(wa);
+    APEX_HIP(hipGetLastError());
+  }
+  return APEX_OK;
+}
+
+int apex_replay_gather(apex_replay_t *r, uint64_t count, const uint32_t *slot, void *obs_out, void *act_out,
+                       float *ret_out, float *gacc_out, void *hip_stream)
+{
+  if (!r || (count && !slot)) return APEX_ERR_INVALID_ARG;
+  if (count > APEX_MAX_SAMPLES_PER_CALL) return APEX_ERR_TOO_LARGE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const RowMap by_slot{slot, nullptr, 0};
+  const RowMap ident{nullptr, nullptr, 0};
+  int rc;
+  if (obs_out && (rc = launch_copy(r->obs(), by_slot, obs_out, ident, count, r->cfg.obs_bytes, stream)) != APEX_OK) return rc;
+  if (act_out && (rc = launch_copy(r->act(), by_slot, act_out, ident, count, r->cfg.act_bytes, stream)) != APEX_OK) return rc;
+  if (ret_out && (rc = launch_copy(r->ret(), by_slot, ret_out, ident, count, 4, stream)) != APEX_OK) return rc;
+  if (gacc_out && (rc = launch_copy(r->gacc(), by_slot, gacc_out, ident, count, 4, stream)) != APEX_OK) return rc;
   return APEX_OK;
 }
 
@@ -320,6 +346,12 @@ int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *
   if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
   if (m == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (m <= 1024) {
+    const uint32_t threads = (uint32_t)round_up(m, kWave);
+    update_small_kernel<<<dim3(1), dim3(threads), 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim());
+    APEX_HIP(hipGetLastError());
+    return APEX_OK;
+  }
   const dim3 grid(blocks_for(m, 256)), block(256);
   update_claim_kernel<<<grid, block, 0, stream>>>(r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim());
   update_apply_kernel<<<grid, block, 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim());

@@ -138,13 +138,45 @@ __device__ __forceinline__ uint64_t map_row(const RowMap &m, uint64_t i)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// Importance-sampling weights of one batch of k samples, by one workgroup:
+//   (N P_i)^-beta / max_j (N P_j)^-beta  ==  (min_j mass_j / mass_i)^beta,   P_i = mass_i / total.
+// `red` is LDS scratch of blockDim/64 words.
+struct WeightArgs {
+  const uint64_t *mass;  // [nb,k], written by the descent kernel that ran before
+  float *weight_out;     // [nb,k]; null: no weights wanted
+  uint32_t k;
+  float beta;
+};
+
+__device__ __forceinline__ void batch_weights(const WeightArgs &wa, uint32_t b, uint64_t *red)
+{
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x, nwave = nthr / kWave;
+  const uint64_t *bm = wa.mass + (uint64_t)b * wa.k;
+  uint64_t mn = ~0ull;
+  for (uint32_t i = tid; i < wa.k; i += nthr) mn = bm[i] < mn ? bm[i] : mn;
+  mn = wave_min(mn);
+  if (lane_id() == 0) red[tid / kWave] = mn;
+  __syncthreads();
+  for (uint32_t w = 0; w < nwave; ++w) mn = red[w] < mn ? red[w] : mn;
+  for (uint32_t i = tid; i < wa.k; i += nthr)
+    wa.weight_out[(uint64_t)b * wa.k + i] = (float)pow((double)mn / (double)bm[i], (double)wa.beta);
+}
+
+__global__ __launch_bounds__(256) void batch_weights_kernel(WeightArgs wa)
+{
+  __shared__ uint64_t red[256 / kWave];
+  batch_weights(wa, blockIdx.x, red);
+}
+
 // Long rows (frame stacks): a workgroup copies kUnroll * blockDim consecutive vectors of one row,
-// all loads issued before the first store so that a whole row can be in flight.
-template <typename Vec, int kUnroll>
+// all loads issued before the first store so that a whole row can be in flight.  With kWeights the
+// workgroup that copies the first chunk of a batch's first row also writes that batch's
+// importance weights, so sampling needs no further launch.
+template <typename Vec, int kUnroll, bool kWeights>
 __global__ __launch_bounds__(256) void copy_rows_long_kernel(const uint8_t *__restrict__ src, RowMap smap,
                                                              uint8_t *__restrict__ dst, RowMap dmap,
                                                              uint32_t vecs_per_row, uint32_t chunks_per_row,
-                                                             uint64_t row_bytes)
+                                                             uint64_t row_bytes, WeightArgs wa)
 {
   const uint32_t row = blockIdx.x / chunks_per_row;
   const uint32_t chunk = blockIdx.x - row * chunks_per_row;
@@ -161,6 +193,10 @@ __global__ __launch_bounds__(256) void copy_rows_long_kernel(const uint8_t *__re
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = v0 + u * blockDim.x;
     if (v < vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+  }
+  if (kWeights) {
+    __shared__ uint64_t red[256 / kWave];
+    if (chunk == 0 && row % wa.k == 0) batch_weights(wa, row / wa.k, red);
   }
 }
 
@@ -269,9 +305,44 @@ __global__ __launch_bounds__(256) void update_apply_kernel(TreeView tv, DeviceSt
   if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
 }
 
+// Both passes in one workgroup, for a learner batch (m <= blockDim): bids and reads of the bid go
+// to memory as device-scope atomics, the workgroup barrier separates the passes.
+__global__ __launch_bounds__(1024) void update_small_kernel(TreeView tv, DeviceState *__restrict__ st, uint32_t m,
+                                                            const uint64_t *__restrict__ key,
+                                                            const float *__restrict__ prio, QuantParams qp,
+                                                            uint32_t *__restrict__ claim)
+{
+  const uint32_t i = threadIdx.x;
+  bool valid = false, stale = false, clamped = false;
+  uint64_t slot = 0, q = 0;
+  if (i < m) {
+    const uint64_t k = key[i];
+    valid = k >= st->head && k < st->tail;
+    stale = !valid;
+    if (valid) {
+      slot = k % tv.P;
+      __hip_atomic_fetch_max(claim + slot, i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      q = quantise_priority(prio[i], qp, &clamped);
+    }
+  }
+  __syncthreads();
+  if (valid && __hip_atomic_load(claim + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == i + 1) {
+    const uint64_t old = tv.level[0][slot];
+    tv.level[0][slot] = q;
+    add_to_ancestors(tv, slot, q - old);
+    claim[slot] = 0;
+  }
+  const uint64_t ns = __popcll(__ballot(stale)), nc = __popcll(__ballot(clamped));
+  if (lane_id() == 0) {
+    if (ns) atomic_add_u64(&st->n_stale, ns);
+    if (nc) atomic_add_u64(&st->n_clamped, nc);
+  }
+}
+
 // --------------------------------------------------------------------------------------------
-// sample: stratified descent, one wavefront per sample; importance weights by the last
-// workgroup of each batch
+// sample: stratified descent, one wavefront per sample.  The importance weights need the
+// smallest mass of a whole batch; they are written by the kernel that runs next (the gather,
+// or batch_weights_kernel), so this one needs no fence or counter between workgroups.
 // --------------------------------------------------------------------------------------------
 struct SampleArgs {
   TreeView tv;
@@ -281,9 +352,7 @@ struct SampleArgs {
   const uint64_t *rnd;       // [nb,k]
   uint64_t *key_out;         // [nb,k] or null
   uint32_t *slot_out;        // [nb,k]
-  float *weight_out;         // [nb,k] or null
-  uint64_t *mass;            // scratch [nb,k]
-  uint32_t *ticket;          // scratch [nb], zero between calls
+  uint64_t *mass;            // scratch [nb,k]: mass of each drawn transition, for the weights
   // small payload columns, gathered here; the observation rows are copied by copy_rows_*
   const uint8_t *act;
   uint32_t act_bytes;
@@ -292,7 +361,7 @@ struct SampleArgs {
   float *ret_out, *gacc_out;
 };
 
-// Dynamic LDS: n_top uint64 (exclusive prefix sums of the top level) + blockDim/64 + 1 words.
+// Dynamic LDS: n_top uint64 (exclusive prefix sums of the top level) + blockDim/64 words.
 __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
 {
   extern __shared__ uint64_t lds[];
@@ -369,7 +438,7 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
       const uint64_t head = a.st->head;
       a.slot_out[o] = (uint32_t)slot;
       if (a.key_out) a.key_out[o] = head + ((slot + tv.P - head % tv.P) % tv.P);
-      __hip_atomic_store(a.mass + o, mass, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      a.mass[o] = mass;
       if (a.ret_out) a.ret_out[o] = a.ret[slot];
       if (a.gacc_out) a.gacc_out[o] = a.gacc[slot];
     }
@@ -378,35 +447,6 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
         a.act_out[o * a.act_bytes + by] = a.act[slot * a.act_bytes + by];
   }
 
-  // ---- importance weights: the workgroup that finishes a batch last normalises it
-  if (!a.weight_out) return;
-  __shared__ uint32_t s_last;
-  __threadfence();
-  __syncthreads();
-  if (tid == 0) {
-    const uint32_t done = __hip_atomic_fetch_add(a.ticket + b, 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (done == gridDim.x - 1);
-    if (s_last) __hip_atomic_store(a.ticket + b, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-  __syncthreads();
-  if (!s_last) return;
-  __threadfence();
-  const uint64_t *bm = a.mass + (uint64_t)b * a.k;
-  uint64_t mn = ~0ull;
-  for (uint32_t i = tid; i < a.k; i += nthr) {
-    const uint64_t v = __hip_atomic_load(bm + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    mn = v < mn ? v : mn;
-  }
-  mn = wave_min(mn);
-  __syncthreads();  // everyone is done with wave_total's first use
-  if (lane == 0) wave_total[wave] = mn;
-  __syncthreads();
-  for (uint32_t w = 0; w < nwave; ++w) mn = wave_total[w] < mn ? wave_total[w] : mn;
-  // (N P_i)^-beta / max_j (N P_j)^-beta  ==  (min_j mass_j / mass_i)^beta
-  for (uint32_t i = tid; i < a.k; i += nthr) {
-    const uint64_t v = __hip_atomic_load(bm + i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    a.weight_out[(uint64_t)b * a.k + i] = (float)pow((double)mn / (double)v, (double)a.beta);
-  }
 }
 
 // zero fill (hipMemset is avoided so that the library's launches stay replayable)

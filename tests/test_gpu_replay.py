@@ -77,6 +77,35 @@ def test_random_operation_sequences(P, C, ob, ab):
         sample_both(g, o, rng, 2, 64)
 
 
+def test_large_update_batches_with_heavy_duplication():
+    # more than one workgroup's worth of pairs: the two-pass path; few distinct keys: many repeats
+    rng = np.random.default_rng(10)
+    g, o = make_pair(20_000, 20_000, 16, 4)
+    add_both(g, o, rng, 20_000)
+    for m, distinct in ((1025, 50), (8192, 300), (5000, 20_000), (1024, 3), (64, 1)):
+        keys = rng.integers(0, distinct, m).astype(np.uint64)
+        newp = rng.lognormal(0, 1, m).astype(F32)
+        assert o.update_priorities(keys, newp) == 0
+        assert g.update_priorities(dev(keys), dev(newp)) == 0
+        check_gpu_tree(g, o)
+    sample_both(g, o, rng, 16, 512)
+
+
+def test_gather_by_slot():
+    rng = np.random.default_rng(9)
+    for ob, ab in ((28224, 4), (64, 4), (256, 32), (10, 6)):
+        g, o = make_pair(900, 1000, ob, ab)
+        add_both(g, o, rng, 950)
+        oo = sample_both(g, o, rng, 1, 300)
+        out = g.alloc_sample_outputs(1, 300)
+        slot = dev(oo["slot"])
+        assert g.gather(slot, out["obs"], out["act"], out["ret"], out["gacc"]) == 0
+        torch.cuda.synchronize()
+        for name in ("obs", "act", "ret", "gacc"):
+            assert np.array_equal(host(out[name]), oo[name]), name
+        assert g.gather(slot[:0]) == 0
+
+
 def test_extreme_uniforms_and_edges():
     rng = np.random.default_rng(1)
     g, o = make_pair(6000, 6000, 16, 4)
