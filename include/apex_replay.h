@@ -64,7 +64,7 @@ typedef struct apex_replay apex_replay_t; /* opaque host object; created and des
 typedef struct apex_replay_config {
   uint64_t capacity;           /* soft limit on stored transitions; apex_replay_evict trims to it
                                   (Section 4.1: 2,000,000)                                           */
-  uint64_t max_slots;          /* physical ring size P >= capacity; slot = key mod P                 */
+  uint64_t max_slots;          /* physical ring size P, capacity <= P <= 2^31; slot = key mod P      */
   uint32_t obs_bytes;          /* opaque observation payload per transition (e.g. 84*84*4 = 28224)   */
   uint32_t act_bytes;          /* opaque action payload per transition (e.g. 4)                      */
   float alpha;                 /* priority exponent, in [-1, 1] (Section 4.1: 0.6)                   */
@@ -152,6 +152,20 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
                     const float *gacc, const float *prio, uint64_t *first_key_out, void *hip_stream);
 
 /*
+ * The two halves of apex_replay_add, for callers that overlap the large payload copy with other
+ * work (Appendix "Implementation": the key-value store of transitions and the prioritized
+ * distribution over its keys are separate structures; the distribution is updated once the batch
+ * is in the store).  apex_replay_add_payload writes the rows of the next count keys into the ring
+ * and publishes nothing; apex_replay_add_publish enters the same count keys into the sum tree and
+ * advances tail.  The publish must be ordered after its payload (same stream, or an event), and
+ * one payload/publish pair must complete before the next payload call is issued.
+ */
+int apex_replay_add_payload(apex_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                            const float *gacc, void *hip_stream);
+int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio, uint64_t *first_key_out,
+                            void *hip_stream);
+
+/*
  * replay.Sample (Algorithm 2; Appendix "Implementation", "Sampling Data"): num_batches
  * independent batches of k transitions, all drawn from the state of the memory at this point
  * of the stream (Section 4.1: the learner prefetches up to 16 batches of 512).
@@ -170,6 +184,23 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
 int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
                        uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
                        float *ret_out, float *gacc_out, void *hip_stream);
+
+/*
+ * The two halves of apex_replay_sample, for callers that run the large copy on another stream
+ * than the tree work (Section 4.1: the learner fetches batches asynchronously, ahead of use).
+ * apex_replay_sample_begin does everything that reads the sum tree: it draws the samples and
+ * writes key_out, slot_out, the small payload columns, and mass_out [nb,k] u64 (device,
+ * required): the mass of every drawn transition.  It must be ordered with updates, adds and
+ * evictions like apex_replay_sample.  apex_replay_sample_finish reads only slot and mass (device,
+ * as written by begin) and the payload ring: it writes weight_out (may be NULL; needs mass) and
+ * obs_out (may be NULL).  It may run on any stream once begin has completed, but before an add
+ * re-uses the drawn slots.
+ */
+int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k, const uint64_t *rnd,
+                             uint64_t *key_out, uint32_t *slot_out, uint64_t *mass_out, void *act_out, float *ret_out,
+                             float *gacc_out, void *hip_stream);
+int apex_replay_sample_finish(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
+                              const uint64_t *mass, float *weight_out, void *obs_out, void *hip_stream);
 
 /*
  * The read half of replay.Sample on its own (Appendix "Implementation", "Data Storage": reading
@@ -196,6 +227,14 @@ int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *
  * may be NULL) receives their number.
  */
 int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream);
+
+/*
+ * head and tail live in device memory and the kernels read them there, so launches captured in a
+ * HIP graph stay correct when replayed.  The host keeps a mirror for its own checks (ring full,
+ * eviction count, first_key_out), which replays do not advance: after replaying captured
+ * launches, call this before the next direct call.  Synchronises hip_stream.
+ */
+int apex_replay_resync(apex_replay_t *r, void *hip_stream);
 
 /* Synchronises hip_stream and reads the counters back. */
 int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out /*host*/, void *hip_stream);

@@ -20,9 +20,10 @@ MAX_BATCHES_PER_CALL = 1024
 TREE_MAX_LEVELS = 8
 
 EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_destroy", "apex_replay_layout",
-           "apex_nstep_priorities", "apex_replay_add", "apex_replay_sample", "apex_replay_gather",
-           "apex_replay_update_priorities",
-           "apex_replay_evict", "apex_replay_stats", "apex_last_hip_error"]
+           "apex_nstep_priorities", "apex_replay_add", "apex_replay_add_payload", "apex_replay_add_publish",
+           "apex_replay_sample", "apex_replay_sample_begin", "apex_replay_sample_finish", "apex_replay_gather",
+           "apex_replay_update_priorities", "apex_replay_evict", "apex_replay_resync", "apex_replay_stats",
+           "apex_last_hip_error"]
 
 
 class Config(C.Structure):
@@ -55,6 +56,11 @@ lib.apex_nstep_priorities.argtypes = [_u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp
                                       _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_add.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, C.POINTER(_u64), _vp]
 lib.apex_replay_sample.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_add_payload.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_add_publish.argtypes = [_vp, _u64, _vp, C.POINTER(_u64), _vp]
+lib.apex_replay_sample_begin.argtypes = [_vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_sample_finish.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_resync.argtypes = [_vp, _vp]
 lib.apex_replay_gather.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
 lib.apex_replay_evict.argtypes = [_vp, C.POINTER(_u64), _vp]
@@ -181,6 +187,27 @@ class Replay:
                                     _ptr(out.get("weight")), _ptr(out.get("obs")), _ptr(out.get("act")),
                                     _ptr(out.get("ret")), _ptr(out.get("gacc")), _stream(stream))
         return rc, out
+
+    def add_payload(self, count, obs=None, act=None, ret=None, gacc=None, stream=None):
+        return lib.apex_replay_add_payload(self.h, count, _ptr(obs), _ptr(act), _ptr(ret), _ptr(gacc), _stream(stream))
+
+    def add_publish(self, prio, stream=None):
+        first = _u64(0)
+        rc = lib.apex_replay_add_publish(self.h, prio.shape[0], _ptr(prio), C.byref(first), _stream(stream))
+        return rc, int(first.value)
+
+    def sample_begin(self, num_batches, k, rnd, out, stream=None):
+        """out needs 'slot' and 'mass' (int64 [nb*k]); 'key', 'act', 'ret', 'gacc' are optional."""
+        return lib.apex_replay_sample_begin(self.h, num_batches, k, _ptr(rnd), _ptr(out.get("key")), _ptr(out["slot"]),
+                                            _ptr(out["mass"]), _ptr(out.get("act")), _ptr(out.get("ret")),
+                                            _ptr(out.get("gacc")), _stream(stream))
+
+    def sample_finish(self, num_batches, k, beta, out, stream=None):
+        return lib.apex_replay_sample_finish(self.h, num_batches, k, beta, _ptr(out["slot"]), _ptr(out.get("mass")),
+                                             _ptr(out.get("weight")), _ptr(out.get("obs")), _stream(stream))
+
+    def resync(self, stream=None):
+        return lib.apex_replay_resync(self.h, _stream(stream))
 
     def gather(self, slot, obs=None, act=None, ret=None, gacc=None, stream=None):
         return lib.apex_replay_gather(self.h, slot.shape[0], _ptr(slot), _ptr(obs), _ptr(act), _ptr(ret), _ptr(gacc),

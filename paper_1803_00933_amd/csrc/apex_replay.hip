@@ -49,7 +49,7 @@ struct Geometry {
 int validate(const apex_replay_config_t *c)
 {
   if (!c) return APEX_ERR_INVALID_ARG;
-  if (c->capacity == 0 || c->max_slots < c->capacity || c->max_slots > (1ull << 32)) return APEX_ERR_INVALID_ARG;
+  if (c->capacity == 0 || c->max_slots < c->capacity || c->max_slots > (1ull << 31)) return APEX_ERR_INVALID_ARG;
   if (c->obs_bytes == 0 || c->act_bytes == 0 || c->frac_bits > 32 || c->reserved != 0) return APEX_ERR_INVALID_ARG;
   if (!(c->alpha >= -1.0f && c->alpha <= 1.0f) || !(c->eps >= 0.0f) || !(c->eps < 1e30f)) return APEX_ERR_INVALID_ARG;
   return APEX_OK;
@@ -120,13 +120,15 @@ int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const Ro
   if (vpr > 256) {
     const uint32_t cpr = (vpr + 256 * kUnroll - 1) / (256 * kUnroll);
     if (nrows * cpr > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
-    const dim3 grid((uint32_t)(nrows * cpr)), block(256);
+    const uint32_t blocks = (uint32_t)(nrows * cpr);
     if (wa && wa->weight_out) {
-      copy_rows_long_kernel<Vec, kUnroll, true><<<grid, block, 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, *wa);
+      const uint32_t nb = (uint32_t)(nrows / wa->k);  // one leading workgroup per batch
+      copy_rows_long_kernel<Vec, kUnroll, true>
+          <<<dim3(blocks + nb), dim3(256), 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, *wa, nb);
       wa->weight_out = nullptr;
     } else {
-      copy_rows_long_kernel<Vec, kUnroll, false>
-          <<<grid, block, 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, WeightArgs{nullptr, nullptr, 1, 0.f});
+      copy_rows_long_kernel<Vec, kUnroll, false><<<dim3(blocks), dim3(256), 0, stream>>>(
+          src, smap, dst, dmap, vpr, cpr, row_bytes, WeightArgs{nullptr, nullptr, 1, 0.f}, 0);
     }
   } else {
     uint32_t lanes_log2 = 0;
@@ -241,7 +243,7 @@ int apex_nstep_priorities(uint32_t S, uint32_t T, uint32_t n, uint32_t A, const 
 {
   if (!S || !T || !n || !A) return APEX_ERR_INVALID_ARG;
   if (!q_online || !q_target || !action || !reward || !discount || !prio || !ret || !gacc) return APEX_ERR_INVALID_ARG;
-  if (frac_bits > 32 || !(alpha >= -1.0f && alpha <= 1.0f) || !(eps >= 0.0f) || max_slots > (1ull << 32))
+  if (frac_bits > 32 || !(alpha >= -1.0f && alpha <= 1.0f) || !(eps >= 0.0f) || max_slots > (1ull << 31))
     return APEX_ERR_INVALID_ARG;
   const uint64_t total = (uint64_t)S * T;
   if (total > 0x7fffffffull * 256 || (uint64_t)T + n > 0xffffffffull) return APEX_ERR_TOO_LARGE;
@@ -252,15 +254,12 @@ int apex_nstep_priorities(uint32_t S, uint32_t T, uint32_t n, uint32_t A, const 
   return APEX_OK;
 }
 
-int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
-                    const float *gacc, const float *prio, uint64_t *first_key_out, void *hip_stream)
+int apex_replay_add_payload(apex_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                            const float *gacc, void *hip_stream)
 {
-  if (!r || (count && !prio)) return APEX_ERR_INVALID_ARG;
+  if (!r) return APEX_ERR_INVALID_ARG;
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
-  if (count == 0) {
-    if (first_key_out) *first_key_out = r->tail;
-    return APEX_OK;
-  }
+  if (count == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const RowMap ident{nullptr, nullptr, 0};
   const RowMap ring{nullptr, &r->state()->tail, r->cfg.max_slots};
@@ -269,35 +268,52 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
   if (act && (rc = launch_copy(act, ident, r->act(), ring, count, r->cfg.act_bytes, stream)) != APEX_OK) return rc;
   if (ret && (rc = launch_copy(ret, ident, r->ret(), ring, count, 4, stream)) != APEX_OK) return rc;
   if (gacc && (rc = launch_copy(gacc, ident, r->gacc(), ring, count, 4, stream)) != APEX_OK) return rc;
-  add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), count, prio, r->qp);
-  advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), 0, count);
-  APEX_HIP(hipGetLastError());
+  return APEX_OK;
+}
+
+int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio, uint64_t *first_key_out,
+                            void *hip_stream)
+{
+  if (!r || (count && !prio)) return APEX_ERR_INVALID_ARG;
+  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  if (count) {
+    hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), count, prio, r->qp);
+    advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), 0, count);
+    APEX_HIP(hipGetLastError());
+  }
   if (first_key_out) *first_key_out = r->tail;
   r->tail += count;
   return APEX_OK;
 }
 
-int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
-                       uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
-                       float *ret_out, float *gacc_out, void *hip_stream)
+int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                    const float *gacc, const float *prio, uint64_t *first_key_out, void *hip_stream)
 {
-  if (!r || !num_batches || !k || !rnd || !slot_out || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  if (!r || (count && !prio)) return APEX_ERR_INVALID_ARG;
+  const int rc = apex_replay_add_payload(r, count, obs, act, ret, gacc, hip_stream);
+  if (rc != APEX_OK) return rc;
+  return apex_replay_add_publish(r, count, prio, first_key_out, hip_stream);
+}
+
+int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k, const uint64_t *rnd,
+                             uint64_t *key_out, uint32_t *slot_out, uint64_t *mass_out, void *act_out, float *ret_out,
+                             float *gacc_out, void *hip_stream)
+{
+  if (!r || !num_batches || !k || !rnd || !slot_out || !mass_out) return APEX_ERR_INVALID_ARG;
   if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
     return APEX_ERR_TOO_LARGE;
   const uint64_t size = r->tail - r->head;
   if (size < r->cfg.min_size_to_sample) return APEX_ERR_NOT_READY;
   if (size == 0) return APEX_ERR_EMPTY;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-
   SampleArgs a;
   a.tv = r->tv;
   a.st = r->state();
   a.k = k;
-  a.beta = beta;
   a.rnd = rnd;
   a.key_out = key_out;
   a.slot_out = slot_out;
-  a.mass = r->mass();
+  a.mass = mass_out;
   a.act = r->act();
   a.act_bytes = r->cfg.act_bytes;
   a.ret = r->ret();
@@ -307,11 +323,23 @@ int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float
   a.gacc_out = gacc_out;
   const uint32_t waves = 4;
   const size_t lds = ((size_t)r->tv.n_top + waves) * sizeof(uint64_t);
-  sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds, stream>>>(a);
+  sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds,
+                          static_cast<hipStream_t>(hip_stream)>>>(a);
   APEX_HIP(hipGetLastError());
-  WeightArgs wa{r->mass(), weight_out, k, beta};
+  return APEX_OK;
+}
+
+int apex_replay_sample_finish(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
+                              const uint64_t *mass, float *weight_out, void *obs_out, void *hip_stream)
+{
+  if (!r || !num_batches || !k || !slot || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  if (weight_out && !mass) return APEX_ERR_INVALID_ARG;
+  if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
+    return APEX_ERR_TOO_LARGE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  WeightArgs wa{mass, weight_out, k, beta};
   if (obs_out) {
-    const RowMap by_slot{slot_out, nullptr, 0};
+    const RowMap by_slot{slot, nullptr, 0};
     const RowMap ident{nullptr, nullptr, 0};
     int rc = launch_copy(r->obs(), by_slot, obs_out, ident, (uint64_t)num_batches * k, r->cfg.obs_bytes, stream, &wa);
     if (rc != APEX_OK) return rc;
@@ -321,6 +349,18 @@ int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float
     APEX_HIP(hipGetLastError());
   }
   return APEX_OK;
+}
+
+int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                       uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
+                       float *ret_out, float *gacc_out, void *hip_stream)
+{
+  if (!r || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  const int rc = apex_replay_sample_begin(r, num_batches, k, rnd, key_out, slot_out, r->mass(), act_out, ret_out,
+                                          gacc_out, hip_stream);
+  if (rc != APEX_OK) return rc;
+  if (!weight_out && !obs_out) return APEX_OK;
+  return apex_replay_sample_finish(r, num_batches, k, beta, slot_out, r->mass(), weight_out, obs_out, hip_stream);
 }
 
 int apex_replay_gather(apex_replay_t *r, uint64_t count, const uint32_t *slot, void *obs_out, void *act_out,
@@ -348,7 +388,7 @@ int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (m <= 1024) {
     const uint32_t threads = (uint32_t)round_up(m, kWave);
-    update_small_kernel<<<dim3(1), dim3(threads), 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim());
+    update_small_kernel<<<dim3(1), dim3(threads), 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp);
     APEX_HIP(hipGetLastError());
     return APEX_OK;
   }
@@ -371,6 +411,18 @@ int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream)
   advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), e, 0);
   APEX_HIP(hipGetLastError());
   r->head += e;
+  return APEX_OK;
+}
+
+int apex_replay_resync(apex_replay_t *r, void *hip_stream)
+{
+  if (!r) return APEX_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  DeviceState st;
+  APEX_HIP(hipMemcpyAsync(&st, r->state(), sizeof st, hipMemcpyDeviceToHost, stream));
+  APEX_HIP(hipStreamSynchronize(stream));
+  r->head = st.head;
+  r->tail = st.tail;
   return APEX_OK;
 }
 

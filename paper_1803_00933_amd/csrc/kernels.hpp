@@ -170,16 +170,25 @@ __global__ __launch_bounds__(256) void batch_weights_kernel(WeightArgs wa)
 
 // Long rows (frame stacks): a workgroup copies kUnroll * blockDim consecutive vectors of one row,
 // all loads issued before the first store so that a whole row can be in flight.  With kWeights the
-// workgroup that copies the first chunk of a batch's first row also writes that batch's
-// importance weights, so sampling needs no further launch.
+// grid carries one extra leading workgroup per batch that writes that batch's importance
+// weights, so sampling needs no further launch and the copy is not held up by it.
 template <typename Vec, int kUnroll, bool kWeights>
 __global__ __launch_bounds__(256) void copy_rows_long_kernel(const uint8_t *__restrict__ src, RowMap smap,
                                                              uint8_t *__restrict__ dst, RowMap dmap,
                                                              uint32_t vecs_per_row, uint32_t chunks_per_row,
-                                                             uint64_t row_bytes, WeightArgs wa)
+                                                             uint64_t row_bytes, WeightArgs wa, uint32_t weight_blocks)
 {
-  const uint32_t row = blockIdx.x / chunks_per_row;
-  const uint32_t chunk = blockIdx.x - row * chunks_per_row;
+  uint32_t blk = blockIdx.x;
+  if (kWeights) {
+    __shared__ uint64_t red[256 / kWave];
+    if (blk < weight_blocks) {
+      batch_weights(wa, blk, red);
+      return;
+    }
+    blk -= weight_blocks;
+  }
+  const uint32_t row = blk / chunks_per_row;
+  const uint32_t chunk = blk - row * chunks_per_row;
   const Vec *s = reinterpret_cast<const Vec *>(src + map_row(smap, row) * row_bytes);
   Vec *d = reinterpret_cast<Vec *>(dst + map_row(dmap, row) * row_bytes);
   const uint32_t v0 = chunk * (kUnroll * blockDim.x) + threadIdx.x;
@@ -193,10 +202,6 @@ __global__ __launch_bounds__(256) void copy_rows_long_kernel(const uint8_t *__re
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = v0 + u * blockDim.x;
     if (v < vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
-  }
-  if (kWeights) {
-    __shared__ uint64_t red[256 / kWave];
-    if (chunk == 0 && row % wa.k == 0) batch_weights(wa, row / wa.k, red);
   }
 }
 
@@ -305,32 +310,50 @@ __global__ __launch_bounds__(256) void update_apply_kernel(TreeView tv, DeviceSt
   if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
 }
 
-// Both passes in one workgroup, for a learner batch (m <= blockDim): bids and reads of the bid go
-// to memory as device-scope atomics, the workgroup barrier separates the passes.
+// A learner batch (m <= blockDim) in one workgroup: duplicates are resolved in an LDS hash table
+// keyed by slot (the highest position wins), so no pass over global memory is needed for it, and
+// the old mass is fetched while the table is being filled.
+constexpr uint32_t kDedupeSlots = 2048;  // >= 2 * 1024 pairs: linear probing stays short
 __global__ __launch_bounds__(1024) void update_small_kernel(TreeView tv, DeviceState *__restrict__ st, uint32_t m,
                                                             const uint64_t *__restrict__ key,
-                                                            const float *__restrict__ prio, QuantParams qp,
-                                                            uint32_t *__restrict__ claim)
+                                                            const float *__restrict__ prio, QuantParams qp)
 {
+  __shared__ uint32_t h_slot[kDedupeSlots];
+  __shared__ uint32_t h_pos[kDedupeSlots];
   const uint32_t i = threadIdx.x;
-  bool valid = false, stale = false, clamped = false;
-  uint64_t slot = 0, q = 0;
+  for (uint32_t t = i; t < kDedupeSlots; t += blockDim.x) {
+    h_slot[t] = 0xffffffffu;  // no slot has this number: max_slots <= 2^31
+    h_pos[t] = 0;
+  }
+  uint64_t k = 0;
+  float p = 0.0f;
   if (i < m) {
-    const uint64_t k = key[i];
-    valid = k >= st->head && k < st->tail;
-    stale = !valid;
-    if (valid) {
-      slot = k % tv.P;
-      __hip_atomic_fetch_max(claim + slot, i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      q = quantise_priority(prio[i], qp, &clamped);
+    k = key[i];
+    p = prio[i];
+  }
+  const uint64_t head = st->head, tail = st->tail;
+  __syncthreads();
+  const bool valid = i < m && k >= head && k < tail;
+  const bool stale = i < m && !valid;
+  bool clamped = false;
+  uint32_t slot = 0, h = 0;
+  uint64_t q = 0, old = 0;
+  if (valid) {
+    slot = (uint32_t)(k % tv.P);
+    old = tv.level[0][slot];  // in flight during the dedupe
+    h = (slot * 2654435761u) >> 21;  // top 11 bits
+    for (;;) {
+      const uint32_t prev = atomicCAS(&h_slot[h], 0xffffffffu, slot);
+      if (prev == 0xffffffffu || prev == slot) break;
+      h = (h + 1) & (kDedupeSlots - 1);
     }
+    atomicMax(&h_pos[h], i + 1);
+    q = quantise_priority(p, qp, &clamped);
   }
   __syncthreads();
-  if (valid && __hip_atomic_load(claim + slot, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == i + 1) {
-    const uint64_t old = tv.level[0][slot];
+  if (valid && h_pos[h] == i + 1) {
     tv.level[0][slot] = q;
     add_to_ancestors(tv, slot, q - old);
-    claim[slot] = 0;
   }
   const uint64_t ns = __popcll(__ballot(stale)), nc = __popcll(__ballot(clamped));
   if (lane_id() == 0) {
@@ -352,7 +375,7 @@ struct SampleArgs {
   const uint64_t *rnd;       // [nb,k]
   uint64_t *key_out;         // [nb,k] or null
   uint32_t *slot_out;        // [nb,k]
-  uint64_t *mass;            // scratch [nb,k]: mass of each drawn transition, for the weights
+  uint64_t *mass;            // [nb,k]: mass of each drawn transition, for the weights
   // small payload columns, gathered here; the observation rows are copied by copy_rows_*
   const uint8_t *act;
   uint32_t act_bytes;
@@ -372,6 +395,12 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
   const uint32_t tid = threadIdx.x, nthr = blockDim.x, nwave = nthr / kWave;
   const uint32_t wave = tid / kWave;
   const int lane = lane_id();
+  const uint32_t b = blockIdx.y;
+  const uint32_t j = blockIdx.x * nwave + wave;
+  const uint64_t o = (uint64_t)b * a.k + j;
+  // issued ahead of the LDS work below, which does not depend on them
+  const uint64_t u = j < a.k ? a.rnd[o] : 0;
+  const uint64_t head = a.st->head;
 
   // ---- top level -> LDS, exclusive prefix sums in place
   const uint64_t *top = tv.level[tv.nlev - 1];
@@ -399,12 +428,9 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
   __syncthreads();
 
   // ---- one sample per wavefront
-  const uint32_t b = blockIdx.y;
-  const uint32_t j = blockIdx.x * nwave + wave;
   if (j < a.k) {
-    const uint64_t o = (uint64_t)b * a.k + j;
-    const uint64_t w = total / a.k;                       // stratum width
-    uint64_t x = (uint64_t)j * w + __umul64hi(a.rnd[o], w);  // point inside stratum j
+    const uint64_t w = total / a.k;                 // stratum width
+    uint64_t x = (uint64_t)j * w + __umul64hi(u, w);  // point inside stratum j
 
     // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
     const uint32_t stride = (n_top + kWave - 1) / kWave;
@@ -435,7 +461,6 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
     }
     const uint64_t slot = idx;
     if (lane == 0) {
-      const uint64_t head = a.st->head;
       a.slot_out[o] = (uint32_t)slot;
       if (a.key_out) a.key_out[o] = head + ((slot + tv.P - head % tv.P) % tv.P);
       a.mass[o] = mass;

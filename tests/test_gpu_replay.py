@@ -196,3 +196,105 @@ def test_tiny_workload_full_trace():
             st = check_gpu_tree(g, o)
             assert st["size"] == min(key0, w.capacity)
     check_gpu_tree(g, o)
+
+
+def test_split_calls_on_separate_streams():
+    """sample_begin / sample_finish and add_payload / add_publish, tree work and copies on different
+    streams ordered by events, against the oracle's plain sequence."""
+    rng = np.random.default_rng(12)
+    C, P, ob, ab, k, cnt = 3000, 4096, 28224, 4, 128, 500
+    g, o = make_pair(C, P, ob, ab)
+    add_both(g, o, rng, C)
+    tree_s, copy_s = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    outs, refs = [], []
+    for step in range(8):
+        out = g.alloc_sample_outputs(1, k)
+        out["mass"] = torch.empty(k, dtype=torch.int64, device="cuda:0")
+        rnd = rng.integers(0, U64, k, dtype=np.uint64)
+        newp = rng.lognormal(0, 1, k).astype(F32)
+        obs = rng.integers(0, 256, (cnt, ob), dtype=np.uint8)
+        act = rng.integers(0, 256, (cnt, ab), dtype=np.uint8)
+        ret, gacc, prio = (rng.standard_normal(cnt).astype(F32) for _ in range(3))
+        d = [dev(x) for x in (rnd, newp, obs, act, ret, gacc, prio)]
+        torch.cuda.synchronize()
+        # oracle: sample, update, add, evict
+        rco, oo = o.sample(1, k, 0.4, rnd)
+        o.update_priorities(oo["key"], newp)
+        o.add(prio, obs, act, ret, gacc)
+        o.evict()
+        # device: the payload copy of the add runs beside the learner step
+        assert g.add_payload(cnt, d[2], d[3], d[4], d[5], stream=copy_s) == 0
+        payload_done = torch.cuda.Event()
+        payload_done.record(copy_s)
+        assert g.sample_begin(1, k, d[0], out, stream=tree_s) == 0
+        drawn = torch.cuda.Event()
+        drawn.record(tree_s)
+        copy_s.wait_event(drawn)
+        assert g.sample_finish(1, k, 0.4, out, stream=copy_s) == 0
+        assert g.update_priorities(out["key"], d[1], stream=tree_s) == 0
+        tree_s.wait_event(payload_done)
+        assert g.add_publish(d[6], stream=tree_s)[0] == 0
+        assert g.evict(stream=tree_s)[0] == 0
+        gathered = torch.cuda.Event()
+        gathered.record(copy_s)
+        tree_s.wait_event(gathered)          # the next payload must not overwrite rows still being read
+        copy_s.wait_stream(tree_s)           # and needs the advanced tail
+        outs.append(out), refs.append(oo)
+    torch.cuda.synchronize()
+    for out, oo in zip(outs, refs):
+        assert_sample_equal(out, oo)
+        assert np.array_equal(host(out["mass"], np.uint64), oo["mass"])
+    check_gpu_tree(g, o)
+
+
+def test_captured_launches_replay_correctly():
+    """A captured sequence of add / sample / update / evict is replayed several times, with eager work
+    and synchronisations in between; every replay is checked against the oracle doing the same."""
+    rng = np.random.default_rng(13)
+    C, P, ob, ab, k, cnt = 1000, 2048, 64, 4, 64, 100
+    g, o = make_pair(C, P, ob, ab)
+    add_both(g, o, rng, C)
+    rnd = [rng.integers(0, U64, k, dtype=np.uint64) for _ in range(3)]
+    newp = [rng.lognormal(0, 1, k).astype(F32) for _ in range(3)]
+    obs = rng.integers(0, 256, (cnt, ob), dtype=np.uint8)
+    act = rng.integers(0, 256, (cnt, ab), dtype=np.uint8)
+    ret, gacc, prio = (rng.standard_normal(cnt).astype(F32) for _ in range(3))
+    d_rnd, d_newp = [dev(x) for x in rnd], [dev(x) for x in newp]
+    d_obs, d_act, d_ret, d_gacc, d_prio = (dev(x) for x in (obs, act, ret, gacc, prio))
+    outs = [g.alloc_sample_outputs(1, k) for _ in range(3)]
+
+    def sequence():
+        assert g.add(d_prio, d_obs, d_act, d_ret, d_gacc)[0] == 0
+        for i in range(3):
+            assert g.sample(1, k, 0.4, d_rnd[i], out=outs[i])[0] == 0
+            assert g.update_priorities(outs[i]["key"], d_newp[i]) == 0
+        assert g.evict() == (0, cnt)
+
+    def oracle_sequence():
+        o.add(prio, obs, act, ret, gacc)
+        res = []
+        for i in range(3):
+            res.append(o.sample(1, k, 0.4, rnd[i])[1])
+            o.update_priorities(res[-1]["key"], newp[i])
+        assert o.evict() == (0, cnt)
+        return res
+
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=s):
+        sequence()
+    for replay in range(4):
+        graph.replay()
+        torch.cuda.synchronize()
+        res = oracle_sequence()
+        for i in range(3):
+            assert_sample_equal(outs[i], res[i])
+        assert g.resync() == 0
+        check_gpu_tree(g, o)
+        if replay == 1:                      # eager work between replays, on the same memory
+            add_both(g, o, rng, 50)
+            sample_both(g, o, rng, 1, 32)
+            assert g.evict() == o.evict()
+            assert g.resync() == 0
