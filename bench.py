@@ -107,6 +107,7 @@ class GpuJob:
         assert rc == 0, rc
 
     def run(self, first, count, with_actors=True):
+        """Everything on one stream, one call after the other."""
         for s in range(first, first + count):
             self.learner_step(s)
             if with_actors:
@@ -116,29 +117,72 @@ class GpuJob:
                     rc, e = self.rep.evict()
                     assert rc == 0
 
-    def timed(self, first, count, with_actors=True):
+    # -- the library's prefetch pipeline: learner steps on one stream, add payloads on a second ----
+    def setup_pipeline(self):
+        self.pipe = self.apex.Pipeline(self.rep, 8, 1, self.w.k)
+
+    def issue_windows(self, first, count):
+        """Same order of tree operations as run(): draw s, update s, [publish the add round], [evict]."""
+        w, pipe = self.w, self.pipe
+        assert first % ADD_EVERY == 0 and count % ADD_EVERY == 0
+        for f in range(first, first + count, ADD_EVERY):
+            t = self.rounds[(f // ADD_EVERY) % self.n_pool]
+            prio, ret, gacc, _ = t["out"]
+            rc = pipe.add_begin(t["q_online"], t["q_target"], t["action"], t["reward"], t["discount"], w.n,
+                                self.obs_stage, t["act"], prio, ret, gacc)
+            assert rc == 0, rc
+            rc, _ = pipe.steps(ADD_EVERY, w.beta, self.rnd[f:f + ADD_EVERY], self.td[f:f + ADD_EVERY])
+            assert rc == 0, rc
+            rc, _, _ = pipe.add_end(evict=(f + ADD_EVERY) % EVICT_EVERY == 0)
+            assert rc == 0, rc
+
+    def run_pipelined(self, first, count):
+        assert self.pipe.fork() == 0
+        self.issue_windows(first, count)
+        assert self.pipe.join() == 0
+
+    def capture_cycle(self, first):
+        """One EVICT_EVERY-step cycle recorded as a HIP graph; replays re-use its uniforms and TD errors."""
+        assert self.pipe.capture_begin() == 0
+        self.issue_windows(first, EVICT_EVERY)
+        assert self.pipe.capture_end() == 0
+
+    def run_replays(self, reps):
+        assert self.pipe.fork() == 0
+        assert self.pipe.replay(reps) == 0
+        assert self.pipe.join() == 0
+
+    def timed(self, fn):
         torch = self.torch
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        self.run(first, count, with_actors)
+        fn()
+        t_host = time.perf_counter() - t0
         torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        return time.perf_counter() - t0, t_host
 
-    def gather_kernel_ms(self, launches):
-        """Average duration of the dominant kernel (frame-stack gather), HIP events on the launch stream."""
+    def gather_kernel_ms(self, launches=50, replays=10):
+        """Average duration of the dominant kernel (the frame-stack gather of one batch of 512), between
+        HIP events on the launch stream.  The launches are captured once and replayed, so that the host's
+        launch rate does not enter the figure."""
         torch = self.torch
         out = self.outs[0]
         slot = out["slot"]
-        for _ in range(10):
-            self.rep.gather(slot, out["obs"])
+        s = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):
+            for _ in range(launches):
+                assert self.rep.gather(slot, out["obs"]) == 0
+        graph.replay()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
-        for _ in range(launches):
-            self.rep.gather(slot, out["obs"])
+        for _ in range(replays):
+            graph.replay()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / launches
+        return e0.elapsed_time(e1) / (launches * replays)
 
 
 def cpu_baseline(w, budget_steps, log):
@@ -199,18 +243,36 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     w = synth.WORKLOADS["atari"]
     K, W = args.steps, args.warmup
+    torch.cuda.set_stream(torch.cuda.Stream())      # plain calls go to an ordinary stream, not the null stream
     job = GpuJob(w, W + 2 * K, log)
 
+    assert K % EVICT_EVERY == 0 and W % EVICT_EVERY == 0, "steps and warmup must be multiples of %d" % EVICT_EVERY
+    job.setup_pipeline()
     job.run(0, W)
-    dt = job.timed(W, K, with_actors=True)
-    log("full schedule: %d steps in %.3f ms (%.2f us/step)" % (K, dt * 1e3, dt / K * 1e6))
-    # learner steps alone, with the memory in the same state of fill (size stays below max_slots: no adds)
-    dt_learner = job.timed(W + K, K, with_actors=False)
-    log("learner steps only: %.2f us/step" % (dt_learner / K * 1e6))
+    # (1) every call on one stream, in order
+    dt_serial, host_serial = job.timed(lambda: job.run(W, K, with_actors=True))
+    log("one stream: %.2f us/step (host enqueue %.2f us/step)" % (dt_serial / K * 1e6, host_serial / K * 1e6))
+    dt_learner, _ = job.timed(lambda: job.run(W + K, K, with_actors=False))
+    log("one stream, learner steps only: %.2f us/step" % (dt_learner / K * 1e6))
+    # (2) the library's pipeline (learner steps as two launches each; add payloads on a second stream)
+    dt_pipe, host_pipe = job.timed(lambda: job.run_pipelined(W, K))
+    log("pipeline, two streams: %.2f us/step (host enqueue %.2f us/step)" % (dt_pipe / K * 1e6, host_pipe / K * 1e6))
+    mode, dt = "apex_pipeline: two streams, eager launches", dt_pipe
+    # (3) one cycle of the same pipeline captured as a HIP graph and replayed
+    job.capture_cycle(W)
+    job.run_replays(max(1, W // EVICT_EVERY))
+    dt_graph, host_graph = job.timed(lambda: job.run_replays(K // EVICT_EVERY))
+    assert job.rep.resync() == 0
+    log("pipeline, graph replays: %.2f us/step (host %.2f us/step)" % (dt_graph / K * 1e6, host_graph / K * 1e6))
+    if dt_graph < dt:
+        mode, dt = "apex_pipeline: two streams, one HIP graph per %d-step cycle" % EVICT_EVERY, dt_graph
+    if dt_serial < dt:
+        mode, dt = "plain calls on one stream, eager launches", dt_serial
     st = job.rep.stats()
+    assert st["size"] == w.capacity, st
     log("state after run: %s" % st)
 
-    gather_ms = job.gather_kernel_ms(500)
+    gather_ms = job.gather_kernel_ms()
     gather_bytes = 2 * w.k * w.obs_bytes                       # read + write of one batch of frame stacks
     achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
     log("gather kernel: %.2f us/launch, %.0f GB/s" % (gather_ms * 1e3, achieved))
@@ -231,10 +293,12 @@ def main():
         "config": {"workload": "atari: capacity 2,000,000 (ring 2^21) x uint8[84*84*4], 18 actions, n=3, alpha 0.6, "
                                "beta 0.4, batch 512; add round of 360x50 every 25 steps, FIFO evict every 100",
                    "capacity": w.capacity, "max_slots": w.max_slots, "obs_bytes": w.obs_bytes, "batch": w.k,
-                   "add_round": w.add_count, "add_every": ADD_EVERY, "evict_every": EVICT_EVERY},
-        "learner_steps_only": {"value": w.k * K / dt_learner, "unit": "transitions/s",
-                               "ms_per_step": dt_learner / K * 1e3,
-                               "priority_updates_per_s": w.k * K / dt_learner},
+                   "add_round": w.add_count, "add_every": ADD_EVERY, "evict_every": EVICT_EVERY,
+                   "launch_mode": mode},
+        "priority_updates_per_s": w.k * K / dt,
+        "adds_per_s": w.add_count * (K // ADD_EVERY) / dt,
+        "variants_us_per_step": {"one_stream": dt_serial / K * 1e6, "one_stream_learner_only": dt_learner / K * 1e6,
+                                 "pipeline": dt_pipe / K * 1e6, "pipeline_graph": dt_graph / K * 1e6},
         "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel (frame-stack gather)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_GATHER_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,

@@ -201,6 +201,15 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
                              float *gacc_out, void *hip_stream);
 int apex_replay_sample_finish(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
                               const uint64_t *mass, float *weight_out, void *obs_out, void *hip_stream);
+/*
+ * apex_replay_sample_finish followed by apex_replay_update_priorities(m, key, prio), as one call:
+ * the two touch disjoint data (payload ring and caller buffers; sum tree), and for m <= 1024 and
+ * long observation rows the update rides in one extra workgroup of the gather kernel instead of
+ * a launch of its own.  key may be the key_out of the batch being finished, or an older one.
+ */
+int apex_replay_sample_finish_update(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta,
+                                     const uint32_t *slot, const uint64_t *mass, float *weight_out, void *obs_out,
+                                     uint64_t m, const uint64_t *key, const float *prio, void *hip_stream);
 
 /*
  * The read half of replay.Sample on its own (Appendix "Implementation", "Data Storage": reading
@@ -238,6 +247,85 @@ int apex_replay_resync(apex_replay_t *r, void *hip_stream);
 
 /* Synchronises hip_stream and reads the counters back. */
 int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out /*host*/, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
+ * Prefetch pipeline.  Section 4.1 and Appendix "Implementation" describe a learner that fetches
+ * batches asynchronously, ahead of use, while priorities flow back and actors keep adding.  An
+ * apex_pipeline_t issues the same verbs as above on two streams of its own (default priority),
+ * ordered by events: learner steps (draw; gather + weights + priority write-back as one launch)
+ * and every other tree operation in program order on one, the payload copies of add rounds
+ * (with their n-step priorities) beside them on the other.  Results are those of the plain
+ * calls issued in the order: draw batch, update, [publish add], [evict].
+ * ---------------------------------------------------------------------------------------- */
+typedef struct apex_pipeline apex_pipeline_t;
+
+/* Device output buffers of one sample call of num_batches x k transitions ("a set"). */
+typedef struct apex_batch_buffers {
+  uint64_t *key;  /* [nb*k]            */
+  uint32_t *slot; /* [nb*k]            */
+  uint64_t *mass; /* [nb*k]            */
+  float *weight;  /* [nb*k]            */
+  void *obs;      /* [nb*k, obs_bytes] */
+  void *act;      /* [nb*k, act_bytes] */
+  float *ret;     /* [nb*k]            */
+  float *gacc;    /* [nb*k]            */
+} apex_batch_buffers_t;
+
+/*
+ * sets: host array of `depth` (1..64) buffer sets, all pointers non-NULL device memory owned by
+ * the caller; step i fills set i mod depth.  The caller must have consumed a set before depth
+ * further steps are issued.  Creates two streams and four events.
+ */
+int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buffers_t *sets, uint32_t num_batches,
+                         uint32_t k, apex_pipeline_t **out);
+/* Waits for the pipeline's streams, then destroys them. */
+int apex_pipeline_destroy(apex_pipeline_t *p);
+/* Everything enqueued so far on `after` (hipStream_t; NULL = the default stream) will precede
+ * whatever the pipeline is given next. */
+int apex_pipeline_fork(apex_pipeline_t *p, void *after);
+/* `stream` (NULL = the default stream) waits, on the device, for everything the pipeline was given. */
+int apex_pipeline_join(apex_pipeline_t *p, void *stream);
+
+/*
+ * n learner steps.  Step i draws num_batches x k transitions with the uniforms rnd[i] (device,
+ * [n, nb*k]) into the next buffer set, gathers them, and, if new_prio is not NULL, writes
+ * new_prio[i] (device, [n, nb*k]) back as the priorities of the keys just drawn, before the next
+ * step draws.  *first_set_out (host, may be NULL) receives the index of the set
+ * the first of these steps fills.
+ */
+int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64_t *rnd, const float *new_prio,
+                        uint32_t *first_set_out);
+
+/*
+ * An add round in two halves, so that its payload copy runs beside learner steps:
+ * apex_pipeline_add_begin computes the n-step priorities of S x T transitions (arguments as for
+ * apex_nstep_priorities; prio, ret, gacc are device scratch of S*T floats that must stay
+ * untouched until the matching add_end has run) and copies obs, act, ret, gacc into the ring on
+ * the add stream; apex_pipeline_add_end publishes them on the tree stream (after whatever steps
+ * were issued in between) and, if evict is non-zero, then trims the memory to its capacity.
+ * One round at a time.
+ */
+int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t n, uint32_t A, const float *q_online,
+                            const float *q_target, const int32_t *action, const float *reward,
+                            const float *discount, const void *obs, const void *act, float *prio, float *ret,
+                            float *gacc);
+int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out, uint64_t *evicted_out);
+
+/*
+ * The same sequence as a HIP graph.  Between apex_pipeline_capture_begin and
+ * apex_pipeline_capture_end the steps / add_begin / add_end calls are recorded instead of run
+ * (stream capture across the pipeline's two streams; fork and join are not allowed inside);
+ * apex_pipeline_replay then launches the recorded sequence `times` times on the tree stream.
+ * Because head and tail are read on the device, each replay continues where the last stopped;
+ * the buffers, uniforms and priorities are those named at capture time.  The host mirror is
+ * left as if the sequence had run once: replay at least once and call apex_replay_resync before
+ * the next direct call.  capture_begin waits for the pipeline's streams to drain.  The counts
+ * the recorded calls took from the host (eviction size) are frozen, so the sequence must leave
+ * the memory at the size it found it.
+ */
+int apex_pipeline_capture_begin(apex_pipeline_t *p);
+int apex_pipeline_capture_end(apex_pipeline_t *p);
+int apex_pipeline_replay(apex_pipeline_t *p, uint32_t times);
 
 /* hipError_t of the last failed HIP call of the calling thread (0 if none). */
 int apex_last_hip_error(void);

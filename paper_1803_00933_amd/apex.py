@@ -21,9 +21,12 @@ TREE_MAX_LEVELS = 8
 
 EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_destroy", "apex_replay_layout",
            "apex_nstep_priorities", "apex_replay_add", "apex_replay_add_payload", "apex_replay_add_publish",
-           "apex_replay_sample", "apex_replay_sample_begin", "apex_replay_sample_finish", "apex_replay_gather",
+           "apex_replay_sample", "apex_replay_sample_begin", "apex_replay_sample_finish",
+           "apex_replay_sample_finish_update", "apex_replay_gather",
            "apex_replay_update_priorities", "apex_replay_evict", "apex_replay_resync", "apex_replay_stats",
-           "apex_last_hip_error"]
+           "apex_last_hip_error", "apex_pipeline_create", "apex_pipeline_destroy", "apex_pipeline_fork",
+           "apex_pipeline_join", "apex_pipeline_steps", "apex_pipeline_add_begin", "apex_pipeline_add_end",
+           "apex_pipeline_capture_begin", "apex_pipeline_capture_end", "apex_pipeline_replay"]
 
 
 class Config(C.Structure):
@@ -40,6 +43,10 @@ class Layout(C.Structure):
     _fields_ = [("obs_offset", C.c_uint64), ("act_offset", C.c_uint64), ("ret_offset", C.c_uint64),
                 ("gacc_offset", C.c_uint64), ("tree_levels", C.c_uint32), ("tree_fanout", C.c_uint32),
                 ("level_offset", C.c_uint64 * TREE_MAX_LEVELS), ("level_size", C.c_uint64 * TREE_MAX_LEVELS)]
+
+
+class BatchBuffers(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("key", "slot", "mass", "weight", "obs", "act", "ret", "gacc")]
 
 
 if not os.path.exists(LIB_PATH):
@@ -60,12 +67,23 @@ lib.apex_replay_add_payload.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_add_publish.argtypes = [_vp, _u64, _vp, C.POINTER(_u64), _vp]
 lib.apex_replay_sample_begin.argtypes = [_vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_sample_finish.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_sample_finish_update.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _u64, _vp, _vp, _vp]
 lib.apex_replay_resync.argtypes = [_vp, _vp]
 lib.apex_replay_gather.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
 lib.apex_replay_evict.argtypes = [_vp, C.POINTER(_u64), _vp]
 lib.apex_replay_stats.argtypes = [_vp, C.POINTER(Stats), _vp]
 lib.apex_last_hip_error.argtypes = []
+lib.apex_pipeline_create.argtypes = [_vp, _u32, C.POINTER(BatchBuffers), _u32, _u32, C.POINTER(_vp)]
+lib.apex_pipeline_destroy.argtypes = [_vp]
+lib.apex_pipeline_fork.argtypes = [_vp, _vp]
+lib.apex_pipeline_join.argtypes = [_vp, _vp]
+lib.apex_pipeline_steps.argtypes = [_vp, _u32, _f32, _vp, _vp, C.POINTER(_u32)]
+lib.apex_pipeline_add_begin.argtypes = [_vp, _u32, _u32, _u32, _u32] + [_vp] * 10
+lib.apex_pipeline_add_end.argtypes = [_vp, C.c_int, C.POINTER(_u64), C.POINTER(_u64)]
+lib.apex_pipeline_capture_begin.argtypes = [_vp]
+lib.apex_pipeline_capture_end.argtypes = [_vp]
+lib.apex_pipeline_replay.argtypes = [_vp, _u32]
 for _name in EXPORTS:
     getattr(lib, _name).restype = C.c_int
 
@@ -206,6 +224,12 @@ class Replay:
         return lib.apex_replay_sample_finish(self.h, num_batches, k, beta, _ptr(out["slot"]), _ptr(out.get("mass")),
                                              _ptr(out.get("weight")), _ptr(out.get("obs")), _stream(stream))
 
+    def sample_finish_update(self, num_batches, k, beta, out, key, prio, stream=None):
+        return lib.apex_replay_sample_finish_update(self.h, num_batches, k, beta, _ptr(out["slot"]),
+                                                    _ptr(out.get("mass")), _ptr(out.get("weight")),
+                                                    _ptr(out.get("obs")), key.shape[0], _ptr(key), _ptr(prio),
+                                                    _stream(stream))
+
     def resync(self, stream=None):
         return lib.apex_replay_resync(self.h, _stream(stream))
 
@@ -227,3 +251,61 @@ class Replay:
         if rc != OK:
             raise RuntimeError("apex_replay_stats: %s" % STATUS_NAMES.get(rc, rc))
         return {n: int(getattr(st, n)) for n, _ in Stats._fields_}
+
+
+class Pipeline:
+    """Binding of apex_pipeline_*: the verbs on two internal streams.  Owns `depth` output sets."""
+
+    def __init__(self, rep: Replay, depth, num_batches, k):
+        self.rep, self.depth, self.nb, self.k = rep, depth, num_batches, k
+        self.sets = []
+        arr = (BatchBuffers * depth)()
+        for i in range(depth):
+            o = rep.alloc_sample_outputs(num_batches, k)
+            o["mass"] = torch.empty(num_batches * k, dtype=torch.int64, device=rep.device)
+            self.sets.append(o)
+            for name, _ in BatchBuffers._fields_:
+                setattr(arr[i], name, o[name].data_ptr())
+        h = _vp(None)
+        rc = lib.apex_pipeline_create(rep.h, depth, arr, num_batches, k, C.byref(h))
+        if rc != OK:
+            raise RuntimeError("apex_pipeline_create: %s" % STATUS_NAMES.get(rc, rc))
+        self.h = h
+
+    def close(self):
+        if getattr(self, "h", None):
+            lib.apex_pipeline_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def fork(self, after=None):
+        return lib.apex_pipeline_fork(self.h, _stream(after))
+
+    def join(self, stream=None):
+        return lib.apex_pipeline_join(self.h, _stream(stream))
+
+    def steps(self, n, beta, rnd, new_prio=None):
+        first = _u32(0)
+        rc = lib.apex_pipeline_steps(self.h, n, beta, _ptr(rnd), _ptr(new_prio), C.byref(first))
+        return rc, int(first.value)
+
+    def add_begin(self, q_online, q_target, action, reward, discount, n, obs, act, prio, ret, gacc):
+        S, L, A = q_online.shape
+        return lib.apex_pipeline_add_begin(self.h, S, L - n, n, A, _ptr(q_online), _ptr(q_target), _ptr(action),
+                                           _ptr(reward), _ptr(discount), _ptr(obs), _ptr(act), _ptr(prio), _ptr(ret),
+                                           _ptr(gacc))
+
+    def capture_begin(self):
+        return lib.apex_pipeline_capture_begin(self.h)
+
+    def capture_end(self):
+        return lib.apex_pipeline_capture_end(self.h)
+
+    def replay(self, times=1):
+        return lib.apex_pipeline_replay(self.h, times)
+
+    def add_end(self, evict=False):
+        first, ev = _u64(0), _u64(0)
+        rc = lib.apex_pipeline_add_end(self.h, int(evict), C.byref(first), C.byref(ev))
+        return rc, int(first.value), int(ev.value)

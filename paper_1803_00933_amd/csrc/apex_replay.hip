@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <new>
+#include <vector>
 
 #include "kernels.hpp"
 
@@ -110,25 +111,38 @@ namespace {
 
 // Copies nrows rows of row_bytes bytes; picks the widest vector the row size and the base
 // addresses allow and the long- or short-row kernel.
-// *wa (may be null): importance weights to be written along the way; cleared once a kernel took them on.
+// Side jobs a long-row copy can take along in leading workgroups (see copy_rows_long_kernel).
+// A field is cleared once a kernel has taken the job on; what is left needs launches of its own.
+struct SideJobs {
+  WeightArgs wa{nullptr, nullptr, 1, 0.f};  // wa.weight_out != null: importance weights wanted
+  UpdateArgs ua{};                          // ua.m != 0: a priority update of at most 1024 pairs
+};
+
 template <typename Vec>
 int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const RowMap &dmap, uint64_t nrows,
-                  uint64_t row_bytes, hipStream_t stream, WeightArgs *wa)
+                  uint64_t row_bytes, hipStream_t stream, SideJobs *jobs)
 {
-  constexpr int kUnroll = 7;  // 7 * 256 lanes * 16 B = 28,672 B >= one 84x84x4 frame stack
+  constexpr int kUnroll = kLongCopyUnroll, kThreads = kLongCopyThreads;
   const uint32_t vpr = (uint32_t)(row_bytes / sizeof(Vec));
   if (vpr > 256) {
-    const uint32_t cpr = (vpr + 256 * kUnroll - 1) / (256 * kUnroll);
-    if (nrows * cpr > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+    const uint32_t cpr = (vpr + kThreads * kUnroll - 1) / (kThreads * kUnroll);
+    if (nrows * cpr > 0x7ffffff0ull) return APEX_ERR_TOO_LARGE;
     const uint32_t blocks = (uint32_t)(nrows * cpr);
-    if (wa && wa->weight_out) {
-      const uint32_t nb = (uint32_t)(nrows / wa->k);  // one leading workgroup per batch
-      copy_rows_long_kernel<Vec, kUnroll, true>
-          <<<dim3(blocks + nb), dim3(256), 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, *wa, nb);
-      wa->weight_out = nullptr;
-    } else {
-      copy_rows_long_kernel<Vec, kUnroll, false><<<dim3(blocks), dim3(256), 0, stream>>>(
-          src, smap, dst, dmap, vpr, cpr, row_bytes, WeightArgs{nullptr, nullptr, 1, 0.f}, 0);
+    const bool w = jobs && jobs->wa.weight_out, u = jobs && jobs->ua.m;
+    const WeightArgs wa = w ? jobs->wa : WeightArgs{nullptr, nullptr, 1, 0.f};
+    const UpdateArgs ua = u ? jobs->ua : UpdateArgs{};
+    const uint32_t nb = w ? (uint32_t)(nrows / wa.k) : 0;  // one leading workgroup per batch
+    const dim3 grid(blocks + nb + (u ? 1 : 0)), block(kThreads);
+#define APEX_LAUNCH_COPY(W, U) \
+  copy_rows_long_kernel<Vec, kUnroll, W, U><<<grid, block, 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, wa, nb, ua)
+    if (w && u) APEX_LAUNCH_COPY(true, true);
+    else if (w) APEX_LAUNCH_COPY(true, false);
+    else if (u) APEX_LAUNCH_COPY(false, true);
+    else APEX_LAUNCH_COPY(false, false);
+#undef APEX_LAUNCH_COPY
+    if (jobs) {
+      jobs->wa.weight_out = nullptr;
+      jobs->ua.m = 0;
     }
   } else {
     uint32_t lanes_log2 = 0;
@@ -143,15 +157,15 @@ int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const Ro
 }
 
 int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dmap, uint64_t nrows, uint64_t row_bytes,
-                hipStream_t stream, WeightArgs *wa = nullptr)
+                hipStream_t stream, SideJobs *jobs = nullptr)
 {
   if (nrows == 0) return APEX_OK;
   const uintptr_t mis = (uintptr_t)src | (uintptr_t)dst | (uintptr_t)row_bytes;
   const uint8_t *s = static_cast<const uint8_t *>(src);
   uint8_t *d = static_cast<uint8_t *>(dst);
-  if ((mis & 15) == 0) return launch_copy_t<u32x4>(s, smap, d, dmap, nrows, row_bytes, stream, wa);
-  if ((mis & 3) == 0) return launch_copy_t<uint32_t>(s, smap, d, dmap, nrows, row_bytes, stream, wa);
-  return launch_copy_t<uint8_t>(s, smap, d, dmap, nrows, row_bytes, stream, wa);
+  if ((mis & 15) == 0) return launch_copy_t<u32x4>(s, smap, d, dmap, nrows, row_bytes, stream, jobs);
+  if ((mis & 3) == 0) return launch_copy_t<uint32_t>(s, smap, d, dmap, nrows, row_bytes, stream, jobs);
+  return launch_copy_t<uint8_t>(s, smap, d, dmap, nrows, row_bytes, stream, jobs);
 }
 
 inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
@@ -329,26 +343,74 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
   return APEX_OK;
 }
 
-int apex_replay_sample_finish(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
-                              const uint64_t *mass, float *weight_out, void *obs_out, void *hip_stream)
+namespace {
+
+int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *prio, hipStream_t stream)
+{
+  if (m <= 1024) {
+    const UpdateArgs ua{r->tv, r->state(), (uint32_t)m, key, prio, r->qp};
+    update_small_kernel<<<dim3(1), dim3((uint32_t)round_up(m, kWave)), 0, stream>>>(ua);
+  } else {
+    const dim3 grid(blocks_for(m, 256)), block(256);
+    update_claim_kernel<<<grid, block, 0, stream>>>(r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim());
+    update_apply_kernel<<<grid, block, 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim());
+  }
+  return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+}
+
+// gather + importance weights (+ a priority update riding along when it fits one workgroup)
+int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
+                const uint64_t *mass, float *weight_out, void *obs_out, uint64_t m, const uint64_t *key,
+                const float *prio, hipStream_t stream)
+{
+  SideJobs jobs;
+  jobs.wa = WeightArgs{mass, weight_out, k, beta};
+  if (m && m <= 1024) jobs.ua = UpdateArgs{r->tv, r->state(), (uint32_t)m, key, prio, r->qp};
+  if (obs_out) {
+    const RowMap by_slot{slot, nullptr, 0};
+    const RowMap ident{nullptr, nullptr, 0};
+    const int rc = launch_copy(r->obs(), by_slot, obs_out, ident, (uint64_t)num_batches * k, r->cfg.obs_bytes, stream, &jobs);
+    if (rc != APEX_OK) return rc;
+  }
+  if (jobs.wa.weight_out) {  // no gather, or short rows: the weights get a small launch of their own
+    batch_weights_kernel<<<dim3(num_batches), dim3(256), 0, stream>>>(jobs.wa);
+    APEX_HIP(hipGetLastError());
+  }
+  if (m && (m > 1024 || jobs.ua.m)) return launch_update(r, m, key, prio, stream);
+  return APEX_OK;
+}
+
+int check_finish_args(const apex_replay *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
+                      const uint64_t *mass, const float *weight_out)
 {
   if (!r || !num_batches || !k || !slot || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
   if (weight_out && !mass) return APEX_ERR_INVALID_ARG;
   if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
     return APEX_ERR_TOO_LARGE;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  WeightArgs wa{mass, weight_out, k, beta};
-  if (obs_out) {
-    const RowMap by_slot{slot, nullptr, 0};
-    const RowMap ident{nullptr, nullptr, 0};
-    int rc = launch_copy(r->obs(), by_slot, obs_out, ident, (uint64_t)num_batches * k, r->cfg.obs_bytes, stream, &wa);
-    if (rc != APEX_OK) return rc;
-  }
-  if (wa.weight_out) {  // no gather, or short rows: the weights get a small launch of their own
-    batch_weights_kernel<<<dim3(num_batches), dim3(256), 0, stream>>>(wa);
-    APEX_HIP(hipGetLastError());
-  }
   return APEX_OK;
+}
+
+}  // namespace
+
+int apex_replay_sample_finish(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
+                              const uint64_t *mass, float *weight_out, void *obs_out, void *hip_stream)
+{
+  const int rc = check_finish_args(r, num_batches, k, beta, slot, mass, weight_out);
+  if (rc != APEX_OK) return rc;
+  return finish_impl(r, num_batches, k, beta, slot, mass, weight_out, obs_out, 0, nullptr, nullptr,
+                     static_cast<hipStream_t>(hip_stream));
+}
+
+int apex_replay_sample_finish_update(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta,
+                                     const uint32_t *slot, const uint64_t *mass, float *weight_out, void *obs_out,
+                                     uint64_t m, const uint64_t *key, const float *prio, void *hip_stream)
+{
+  const int rc = check_finish_args(r, num_batches, k, beta, slot, mass, weight_out);
+  if (rc != APEX_OK) return rc;
+  if (m && (!key || !prio)) return APEX_ERR_INVALID_ARG;
+  if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
+  return finish_impl(r, num_batches, k, beta, slot, mass, weight_out, obs_out, m, key, prio,
+                     static_cast<hipStream_t>(hip_stream));
 }
 
 int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
@@ -385,18 +447,7 @@ int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *
   if (!r || (m && (!key || !prio))) return APEX_ERR_INVALID_ARG;
   if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
   if (m == 0) return APEX_OK;
-  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  if (m <= 1024) {
-    const uint32_t threads = (uint32_t)round_up(m, kWave);
-    update_small_kernel<<<dim3(1), dim3(threads), 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp);
-    APEX_HIP(hipGetLastError());
-    return APEX_OK;
-  }
-  const dim3 grid(blocks_for(m, 256)), block(256);
-  update_claim_kernel<<<grid, block, 0, stream>>>(r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim());
-  update_apply_kernel<<<grid, block, 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim());
-  APEX_HIP(hipGetLastError());
-  return APEX_OK;
+  return launch_update(r, m, key, prio, static_cast<hipStream_t>(hip_stream));
 }
 
 int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream)
@@ -448,3 +499,5 @@ int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out, void *hip_stre
 }
 
 }  // extern "C"
+
+#include "pipeline.inc.hpp"

@@ -138,6 +138,72 @@ __device__ __forceinline__ uint64_t map_row(const RowMap &m, uint64_t i)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// A learner batch (m <= blockDim) handled by one workgroup: duplicates are resolved in an LDS hash
+// table keyed by slot (the highest position wins), so no pass over global memory is needed for
+// it, and the old mass is fetched while the table is being filled.
+constexpr uint32_t kDedupeSlots = 2048;  // >= 2 * 1024 pairs: linear probing stays short
+struct UpdateArgs {
+  TreeView tv;
+  DeviceState *st;
+  uint32_t m;
+  const uint64_t *key;
+  const float *prio;
+  QuantParams qp;
+};
+
+// h_slot, h_pos: LDS, kDedupeSlots words each.  Called by every thread of the workgroup.
+__device__ __forceinline__ void update_batch_in_block(const UpdateArgs &ua, uint32_t *h_slot, uint32_t *h_pos)
+{
+  const TreeView &tv = ua.tv;
+  const uint32_t i = threadIdx.x;
+  for (uint32_t t = i; t < kDedupeSlots; t += blockDim.x) {
+    h_slot[t] = 0xffffffffu;  // no slot has this number: max_slots <= 2^31
+    h_pos[t] = 0;
+  }
+  uint64_t k = 0;
+  float p = 0.0f;
+  if (i < ua.m) {
+    k = ua.key[i];
+    p = ua.prio[i];
+  }
+  const uint64_t head = ua.st->head, tail = ua.st->tail;
+  __syncthreads();
+  const bool valid = i < ua.m && k >= head && k < tail;
+  const bool stale = i < ua.m && !valid;
+  bool clamped = false;
+  uint32_t slot = 0, h = 0;
+  uint64_t q = 0, old = 0;
+  if (valid) {
+    slot = (uint32_t)(k % tv.P);
+    old = tv.level[0][slot];  // in flight during the dedupe
+    h = (slot * 2654435761u) >> 21;  // top 11 bits
+    for (;;) {
+      const uint32_t prev = atomicCAS(&h_slot[h], 0xffffffffu, slot);
+      if (prev == 0xffffffffu || prev == slot) break;
+      h = (h + 1) & (kDedupeSlots - 1);
+    }
+    atomicMax(&h_pos[h], i + 1);
+    q = quantise_priority(p, ua.qp, &clamped);
+  }
+  __syncthreads();
+  if (valid && h_pos[h] == i + 1) {
+    tv.level[0][slot] = q;
+    add_to_ancestors(tv, slot, q - old);
+  }
+  const uint64_t ns = __popcll(__ballot(stale)), nc = __popcll(__ballot(clamped));
+  if (lane_id() == 0) {
+    if (ns) atomic_add_u64(&ua.st->n_stale, ns);
+    if (nc) atomic_add_u64(&ua.st->n_clamped, nc);
+  }
+}
+
+__global__ __launch_bounds__(1024) void update_small_kernel(UpdateArgs ua)
+{
+  __shared__ uint32_t h_slot[kDedupeSlots];
+  __shared__ uint32_t h_pos[kDedupeSlots];
+  update_batch_in_block(ua, h_slot, h_pos);
+}
+
 // Importance-sampling weights of one batch of k samples, by one workgroup:
 //   (N P_i)^-beta / max_j (N P_j)^-beta  ==  (min_j mass_j / mass_i)^beta,   P_i = mass_i / total.
 // `red` is LDS scratch of blockDim/64 words.
@@ -162,6 +228,9 @@ __device__ __forceinline__ void batch_weights(const WeightArgs &wa, uint32_t b, 
     wa.weight_out[(uint64_t)b * wa.k + i] = (float)pow((double)mn / (double)bm[i], (double)wa.beta);
 }
 
+constexpr int kLongCopyThreads = 1024;  // one workgroup of 16 waves per 28 KB frame stack
+constexpr int kLongCopyUnroll = 2;      // 1024 lanes * 2 * 16 B = 32 KB per workgroup
+
 __global__ __launch_bounds__(256) void batch_weights_kernel(WeightArgs wa)
 {
   __shared__ uint64_t red[256 / kWave];
@@ -169,18 +238,30 @@ __global__ __launch_bounds__(256) void batch_weights_kernel(WeightArgs wa)
 }
 
 // Long rows (frame stacks): a workgroup copies kUnroll * blockDim consecutive vectors of one row,
-// all loads issued before the first store so that a whole row can be in flight.  With kWeights the
-// grid carries one extra leading workgroup per batch that writes that batch's importance
-// weights, so sampling needs no further launch and the copy is not held up by it.
-template <typename Vec, int kUnroll, bool kWeights>
-__global__ __launch_bounds__(256) void copy_rows_long_kernel(const uint8_t *__restrict__ src, RowMap smap,
-                                                             uint8_t *__restrict__ dst, RowMap dmap,
-                                                             uint32_t vecs_per_row, uint32_t chunks_per_row,
-                                                             uint64_t row_bytes, WeightArgs wa, uint32_t weight_blocks)
+// all loads issued before the first store so that a whole row can be in flight.
+// The grid may carry leading workgroups with side jobs that touch none of the copied bytes, so
+// that a learner step needs no launch of their own for them:
+//   kUpdate   workgroup 0 writes a batch of priorities back into the sum tree;
+//   kWeights  the next weight_blocks workgroups write one batch's importance weights each.
+template <typename Vec, int kUnroll, bool kWeights, bool kUpdate>
+__global__ __launch_bounds__(kLongCopyThreads) void copy_rows_long_kernel(const uint8_t *__restrict__ src, RowMap smap,
+                                                                          uint8_t *__restrict__ dst, RowMap dmap,
+                                                                          uint32_t vecs_per_row, uint32_t chunks_per_row,
+                                                                          uint64_t row_bytes, WeightArgs wa,
+                                                                          uint32_t weight_blocks, UpdateArgs ua)
 {
   uint32_t blk = blockIdx.x;
+  if (kUpdate) {
+    __shared__ uint32_t h_slot[kDedupeSlots];
+    __shared__ uint32_t h_pos[kDedupeSlots];
+    if (blk == 0) {
+      update_batch_in_block(ua, h_slot, h_pos);
+      return;
+    }
+    blk -= 1;
+  }
   if (kWeights) {
-    __shared__ uint64_t red[256 / kWave];
+    __shared__ uint64_t red[kLongCopyThreads / kWave];
     if (blk < weight_blocks) {
       batch_weights(wa, blk, red);
       return;
@@ -308,58 +389,6 @@ __global__ __launch_bounds__(256) void update_apply_kernel(TreeView tv, DeviceSt
   }
   const uint64_t nc = __popcll(__ballot(clamped));
   if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
-}
-
-// A learner batch (m <= blockDim) in one workgroup: duplicates are resolved in an LDS hash table
-// keyed by slot (the highest position wins), so no pass over global memory is needed for it, and
-// the old mass is fetched while the table is being filled.
-constexpr uint32_t kDedupeSlots = 2048;  // >= 2 * 1024 pairs: linear probing stays short
-__global__ __launch_bounds__(1024) void update_small_kernel(TreeView tv, DeviceState *__restrict__ st, uint32_t m,
-                                                            const uint64_t *__restrict__ key,
-                                                            const float *__restrict__ prio, QuantParams qp)
-{
-  __shared__ uint32_t h_slot[kDedupeSlots];
-  __shared__ uint32_t h_pos[kDedupeSlots];
-  const uint32_t i = threadIdx.x;
-  for (uint32_t t = i; t < kDedupeSlots; t += blockDim.x) {
-    h_slot[t] = 0xffffffffu;  // no slot has this number: max_slots <= 2^31
-    h_pos[t] = 0;
-  }
-  uint64_t k = 0;
-  float p = 0.0f;
-  if (i < m) {
-    k = key[i];
-    p = prio[i];
-  }
-  const uint64_t head = st->head, tail = st->tail;
-  __syncthreads();
-  const bool valid = i < m && k >= head && k < tail;
-  const bool stale = i < m && !valid;
-  bool clamped = false;
-  uint32_t slot = 0, h = 0;
-  uint64_t q = 0, old = 0;
-  if (valid) {
-    slot = (uint32_t)(k % tv.P);
-    old = tv.level[0][slot];  // in flight during the dedupe
-    h = (slot * 2654435761u) >> 21;  // top 11 bits
-    for (;;) {
-      const uint32_t prev = atomicCAS(&h_slot[h], 0xffffffffu, slot);
-      if (prev == 0xffffffffu || prev == slot) break;
-      h = (h + 1) & (kDedupeSlots - 1);
-    }
-    atomicMax(&h_pos[h], i + 1);
-    q = quantise_priority(p, qp, &clamped);
-  }
-  __syncthreads();
-  if (valid && h_pos[h] == i + 1) {
-    tv.level[0][slot] = q;
-    add_to_ancestors(tv, slot, q - old);
-  }
-  const uint64_t ns = __popcll(__ballot(stale)), nc = __popcll(__ballot(clamped));
-  if (lane_id() == 0) {
-    if (ns) atomic_add_u64(&st->n_stale, ns);
-    if (nc) atomic_add_u64(&st->n_clamped, nc);
-  }
 }
 
 // --------------------------------------------------------------------------------------------

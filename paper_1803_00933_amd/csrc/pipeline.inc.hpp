@@ -1,0 +1,243 @@
+// apex_pipeline_*: the replay verbs issued on two internal streams ordered by events (learner
+// steps on one, the payload copies of add rounds on the other), and the same sequence captured
+// once as a HIP graph and replayed.
+// Included by apex_replay.hip (one translation unit), after the plain entry points.
+
+struct apex_pipeline {
+  apex_replay *r;
+  uint32_t depth, nb, k;
+  std::vector<apex_batch_buffers_t> sets;
+  hipStream_t tree, add;  // learner steps and every tree operation; add payloads
+
+  // A "mark" is the latest record of one role (payload copied, tail advanced).  Outside a capture each role re-records its own long-lived event; inside a capture
+  // every record gets a fresh event, so that no event is recorded twice in one capture.
+  struct Mark {
+    hipEvent_t own = nullptr;  // long-lived
+    hipEvent_t cur = nullptr;  // what a wait has to wait for; null: nothing to wait for
+  };
+  Mark payload_done, tail_ready;
+  hipEvent_t fork_ev = nullptr, join_ev = nullptr;
+  std::vector<hipEvent_t> capture_events;
+
+  uint64_t step = 0;          // learner steps issued so far
+  uint64_t first_step = 0;    // steps before this one cannot be in flight (pipeline was drained)
+  bool add_open = false;      // add_begin issued, add_end not yet
+  uint64_t add_count = 0;
+  float *add_prio = nullptr;
+
+  bool capturing = false;
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t graph_exec = nullptr;
+
+  hipStream_t streams(int i) const { return i == 0 ? tree : add; }
+};
+
+namespace {
+
+bool new_event(hipEvent_t *e) { return !hip_failed(hipEventCreateWithFlags(e, hipEventDisableTiming)); }
+
+int mark_record(apex_pipeline *p, apex_pipeline::Mark &m, hipStream_t s)
+{
+  hipEvent_t e = m.own;
+  if (p->capturing) {
+    if (!new_event(&e)) return APEX_ERR_HIP;
+    p->capture_events.push_back(e);
+  }
+  APEX_HIP(hipEventRecord(e, s));
+  m.cur = e;
+  return APEX_OK;
+}
+
+int mark_wait(apex_pipeline::Mark &m, hipStream_t s)
+{
+  if (m.cur) APEX_HIP(hipStreamWaitEvent(s, m.cur, 0));
+  return APEX_OK;
+}
+
+void forget_marks(apex_pipeline *p)
+{
+  p->payload_done.cur = p->tail_ready.cur = nullptr;
+  p->first_step = p->step;
+}
+
+void drop_graph(apex_pipeline *p)
+{
+  if (p->graph_exec) (void)hipGraphExecDestroy(p->graph_exec);
+  if (p->graph) (void)hipGraphDestroy(p->graph);
+  p->graph_exec = nullptr;
+  p->graph = nullptr;
+  for (hipEvent_t e : p->capture_events) (void)hipEventDestroy(e);
+  p->capture_events.clear();
+}
+
+void pipeline_free(apex_pipeline *p)
+{
+  drop_graph(p);
+  for (hipEvent_t e : {p->payload_done.own, p->tail_ready.own, p->fork_ev, p->join_ev})
+    if (e) (void)hipEventDestroy(e);
+  for (int i = 0; i < 2; ++i)
+    if (p->streams(i)) (void)hipStreamDestroy(p->streams(i));
+  delete p;
+}
+
+#define APEX_TRY(call)            \
+  do {                            \
+    const int rc_ = (call);       \
+    if (rc_ != APEX_OK) return rc_; \
+  } while (0)
+
+}  // namespace
+
+extern "C" {
+
+int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buffers_t *sets, uint32_t num_batches,
+                         uint32_t k, apex_pipeline_t **out)
+{
+  if (!r || !sets || !out || depth == 0 || depth > 64 || !num_batches || !k) return APEX_ERR_INVALID_ARG;
+  if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
+    return APEX_ERR_TOO_LARGE;
+  for (uint32_t i = 0; i < depth; ++i) {
+    const apex_batch_buffers_t &b = sets[i];
+    if (!b.key || !b.slot || !b.mass || !b.weight || !b.obs || !b.act || !b.ret || !b.gacc) return APEX_ERR_INVALID_ARG;
+  }
+  apex_pipeline *p = new (std::nothrow) apex_pipeline();
+  if (!p) return APEX_ERR_INVALID_ARG;
+  p->r = r;
+  p->depth = depth;
+  p->nb = num_batches;
+  p->k = k;
+  p->sets.assign(sets, sets + depth);
+  p->tree = p->add = nullptr;
+  bool ok = true;
+  for (hipStream_t *s : {&p->tree, &p->add})
+    ok = ok && !hip_failed(hipStreamCreateWithFlags(s, hipStreamNonBlocking));  // default priority
+  ok = ok && new_event(&p->payload_done.own) && new_event(&p->tail_ready.own) && new_event(&p->fork_ev) &&
+       new_event(&p->join_ev);
+  if (!ok) {
+    pipeline_free(p);
+    return APEX_ERR_HIP;
+  }
+  *out = p;
+  return APEX_OK;
+}
+
+int apex_pipeline_destroy(apex_pipeline_t *p)
+{
+  if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
+  for (int i = 0; i < 2; ++i) (void)hipStreamSynchronize(p->streams(i));
+  pipeline_free(p);
+  return APEX_OK;
+}
+
+int apex_pipeline_fork(apex_pipeline_t *p, void *after)
+{
+  if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
+  APEX_HIP(hipEventRecord(p->fork_ev, static_cast<hipStream_t>(after)));
+  for (int i = 0; i < 2; ++i) APEX_HIP(hipStreamWaitEvent(p->streams(i), p->fork_ev, 0));
+  return APEX_OK;
+}
+
+int apex_pipeline_join(apex_pipeline_t *p, void *stream)
+{
+  if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
+  for (int i = 0; i < 2; ++i) {
+    APEX_HIP(hipEventRecord(p->join_ev, p->streams(i)));
+    APEX_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), p->join_ev, 0));
+  }
+  return APEX_OK;
+}
+
+int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64_t *rnd, const float *new_prio,
+                        uint32_t *first_set_out)
+{
+  if (!p || (n && !rnd) || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  if (first_set_out) *first_set_out = (uint32_t)(p->step % p->depth);
+  const uint64_t per = (uint64_t)p->nb * p->k;
+  for (uint32_t i = 0; i < n; ++i) {
+    const apex_batch_buffers_t &b = p->sets[p->step % p->depth];
+    APEX_TRY(apex_replay_sample_begin(p->r, p->nb, p->k, rnd + i * per, b.key, b.slot, b.mass, b.act, b.ret, b.gacc,
+                                      p->tree));
+    // the gather of this batch, its weights, and the write-back of its priorities: one launch
+    APEX_TRY(apex_replay_sample_finish_update(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs,
+                                              new_prio ? per : 0, b.key, new_prio ? new_prio + i * per : nullptr,
+                                              p->tree));
+    ++p->step;
+  }
+  return APEX_OK;
+}
+
+int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t n, uint32_t A, const float *q_online,
+                            const float *q_target, const int32_t *action, const float *reward,
+                            const float *discount, const void *obs, const void *act, float *prio, float *ret,
+                            float *gacc)
+{
+  if (!p || p->add_open) return APEX_ERR_INVALID_ARG;
+  apex_replay *r = p->r;
+  const uint64_t count = (uint64_t)S * T;
+  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  APEX_TRY(mark_wait(p->tail_ready, p->add));  // the add stream reads tail on the device
+  APEX_TRY(apex_nstep_priorities(S, T, n, A, q_online, q_target, action, reward, discount, r->cfg.alpha, r->cfg.eps,
+                                 r->cfg.frac_bits, r->cfg.max_slots, prio, ret, gacc, nullptr, p->add));
+  APEX_TRY(apex_replay_add_payload(r, count, obs, act, ret, gacc, p->add));
+  APEX_TRY(mark_record(p, p->payload_done, p->add));
+  p->add_open = true;
+  p->add_count = count;
+  p->add_prio = prio;
+  return APEX_OK;
+}
+
+int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out, uint64_t *evicted_out)
+{
+  if (!p || !p->add_open) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(mark_wait(p->payload_done, p->tree));
+  APEX_TRY(apex_replay_add_publish(p->r, p->add_count, p->add_prio, first_key_out, p->tree));
+  p->add_open = false;
+  if (evicted_out) *evicted_out = 0;
+  if (evict) APEX_TRY(apex_replay_evict(p->r, evicted_out, p->tree));
+  APEX_TRY(mark_record(p, p->tail_ready, p->tree));
+  return APEX_OK;
+}
+
+int apex_pipeline_capture_begin(apex_pipeline_t *p)
+{
+  if (!p || p->capturing || p->add_open) return APEX_ERR_INVALID_ARG;
+  for (int i = 0; i < 2; ++i) APEX_HIP(hipStreamSynchronize(p->streams(i)));  // drained: nothing older to wait for
+  drop_graph(p);
+  forget_marks(p);
+  APEX_HIP(hipStreamBeginCapture(p->tree, hipStreamCaptureModeRelaxed));
+  p->capturing = true;
+  // fork the add stream into the capture
+  apex_pipeline::Mark origin;
+  int rc = mark_record(p, origin, p->tree);
+  if (rc == APEX_OK) rc = mark_wait(origin, p->add);
+  return rc;
+}
+
+int apex_pipeline_capture_end(apex_pipeline_t *p)
+{
+  if (!p || !p->capturing || p->add_open) return APEX_ERR_INVALID_ARG;
+  // join the add stream back into the origin of the capture
+  apex_pipeline::Mark done;
+  int rc = mark_record(p, done, p->add);
+  if (rc == APEX_OK) rc = mark_wait(done, p->tree);
+  hipGraph_t g = nullptr;
+  const bool failed = hip_failed(hipStreamEndCapture(p->tree, &g));
+  p->capturing = false;
+  forget_marks(p);
+  if (failed || rc != APEX_OK || !g) {
+    if (g) (void)hipGraphDestroy(g);
+    return rc != APEX_OK ? rc : APEX_ERR_HIP;
+  }
+  p->graph = g;
+  APEX_HIP(hipGraphInstantiate(&p->graph_exec, p->graph, nullptr, nullptr, 0));
+  return APEX_OK;
+}
+
+int apex_pipeline_replay(apex_pipeline_t *p, uint32_t times)
+{
+  if (!p || p->capturing || !p->graph_exec) return APEX_ERR_INVALID_ARG;
+  for (uint32_t i = 0; i < times; ++i) APEX_HIP(hipGraphLaunch(p->graph_exec, p->tree));
+  return APEX_OK;
+}
+
+}  // extern "C"

@@ -298,3 +298,167 @@ def test_captured_launches_replay_correctly():
             sample_both(g, o, rng, 1, 32)
             assert g.evict() == o.evict()
             assert g.resync() == 0
+
+
+def test_pipeline_matches_the_plain_call_order():
+    """apex_pipeline_*: learner steps with the gathers on a second stream and add rounds whose payload
+    copy runs beside them, against the oracle doing draw, update, [add], [evict] one after the other."""
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=96)
+    rng = np.random.default_rng(14)
+    g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    add_both(g, o, rng, w.capacity)
+    depth, n_steps, per_round = 3, 24, 6
+    pipe = apex.Pipeline(g, depth, 1, w.k)
+    rnd = rng.integers(0, U64, (n_steps, w.k), dtype=np.uint64)
+    newp = rng.lognormal(0, 1, (n_steps, w.k)).astype(F32)
+    d_rnd, d_newp = dev(rnd), dev(newp)
+    S, T = w.streams, w.chunk
+    scratch = [torch.empty(S * T, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    rounds = []
+    for i in range(n_steps // per_round):
+        d = synth.actor_round(w, i)
+        d["obs"] = rng.integers(0, 256, (S * T, w.obs_bytes), dtype=np.uint8)
+        rounds.append((d, {k2: dev(v) for k2, v in d.items()}))
+    torch.cuda.synchronize()
+    assert pipe.fork() == 0
+    refs, got = [], []
+    for s in range(n_steps):
+        if s % per_round == 0:
+            d, dd = rounds[s // per_round]
+            assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                                  dd["obs"], dd["act"], *scratch) == 0
+        rc, first = pipe.steps(1, 0.4, d_rnd[s], d_newp[s])
+        assert rc == 0 and first == s % depth
+        rco, oo = o.sample(1, w.k, 0.4, rnd[s])
+        o.update_priorities(oo["key"], newp[s])
+        refs.append(oo)
+        if (s + 1) % per_round == 0:
+            evict = (s + 1) % (2 * per_round) == 0
+            rc, first_key, ev = pipe.add_end(evict)
+            ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                          w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+            rco, fo = o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1), ref[2].reshape(-1))
+            assert (rc, first_key) == (rco, fo)
+            if evict:
+                assert o.evict() == (0, ev)
+        # a set must be consumed before `depth` further steps are issued: copy it out now
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        got.append({k2: v.clone() for k2, v in pipe.sets[s % depth].items()})
+        assert pipe.fork() == 0
+    assert pipe.join() == 0
+    torch.cuda.synchronize()
+    for out, oo in zip(got, refs):
+        assert_sample_equal(out, oo)
+    check_gpu_tree(g, o)
+    # several steps in one call, no synchronisation in between; the last `depth` sets are checked
+    rnd2 = rng.integers(0, U64, (7, w.k), dtype=np.uint64)
+    newp2 = rng.lognormal(0, 1, (7, w.k)).astype(F32)
+    d2 = (dev(rnd2), dev(newp2))
+    torch.cuda.synchronize()
+    assert pipe.fork() == 0
+    rc, first = pipe.steps(7, 0.4, *d2)
+    assert rc == 0 and first == n_steps % depth
+    assert pipe.join() == 0
+    torch.cuda.synchronize()
+    refs2 = []
+    for s in range(7):
+        rco, oo = o.sample(1, w.k, 0.4, rnd2[s])
+        o.update_priorities(oo["key"], newp2[s])
+        refs2.append(oo)
+    for s in range(7 - depth, 7):
+        assert_sample_equal(pipe.sets[(n_steps + s) % depth], refs2[s])
+    check_gpu_tree(g, o)
+    pipe.close()
+
+
+def test_pipeline_graph_replays():
+    """One cycle (an add round beside six learner steps, then eviction) captured as a HIP graph by the
+    pipeline and replayed; every replay is checked against the oracle, with eager work in between."""
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=96)
+    rng = np.random.default_rng(15)
+    g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    add_both(g, o, rng, w.capacity)
+    depth, n_steps = 3, 6
+    pipe = apex.Pipeline(g, depth, 1, w.k)
+    rnd = rng.integers(0, U64, (n_steps, w.k), dtype=np.uint64)
+    newp = rng.lognormal(0, 1, (n_steps, w.k)).astype(F32)
+    d_rnd, d_newp = dev(rnd), dev(newp)
+    S, T = w.streams, w.chunk
+    scratch = [torch.empty(S * T, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    d = synth.actor_round(w, 0)
+    d["obs"] = rng.integers(0, 256, (S * T, w.obs_bytes), dtype=np.uint8)
+    dd = {k2: dev(v) for k2, v in d.items()}
+    torch.cuda.synchronize()
+
+    def cycle():
+        assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                              dd["obs"], dd["act"], *scratch) == 0
+        assert pipe.steps(n_steps, 0.4, d_rnd, d_newp)[0] == 0
+        rc, _, ev = pipe.add_end(True)
+        assert (rc, ev) == (0, S * T)
+
+    def oracle_cycle():
+        res = []
+        for s in range(n_steps):
+            res.append(o.sample(1, w.k, 0.4, rnd[s])[1])
+            o.update_priorities(res[-1]["key"], newp[s])
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+        assert o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1), ref[2].reshape(-1))[0] == 0
+        assert o.evict() == (0, S * T)
+        return res
+
+    assert pipe.capture_begin() == 0
+    cycle()
+    assert pipe.capture_end() == 0
+    for replay in range(4):
+        assert pipe.fork() == 0
+        assert pipe.replay(1) == 0
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        res = oracle_cycle()
+        for s in range(n_steps - depth, n_steps):
+            assert_sample_equal(pipe.sets[s % depth], res[s])
+        assert g.resync() == 0
+        check_gpu_tree(g, o)
+        if replay == 1:                       # eager calls between replays, on the same memory
+            add_both(g, o, rng, 30)
+            sample_both(g, o, rng, 1, 32)
+            assert g.evict() == o.evict()
+    # several replays back to back
+    assert pipe.fork() == 0
+    assert pipe.replay(3) == 0
+    assert pipe.join() == 0
+    torch.cuda.synchronize()
+    for _ in range(3):
+        res = oracle_cycle()
+    for s in range(n_steps - depth, n_steps):
+        assert_sample_equal(pipe.sets[s % depth], res[s])
+    assert g.resync() == 0
+    check_gpu_tree(g, o)
+    pipe.close()
+
+
+@pytest.mark.parametrize("ob,k,extra", [(28224, 512, 0), (4224, 100, 0), (64, 128, 0), (4224, 700, 600)])
+def test_finish_with_update_riding_along(ob, k, extra):
+    """apex_replay_sample_finish_update == finish, then update (in the gather kernel's extra workgroup when
+    the batch fits one, by launches of its own otherwise)."""
+    rng = np.random.default_rng(16 + k)
+    g, o = make_pair(3000, 4096, ob, 4)
+    add_both(g, o, rng, 3000)
+    for step in range(4):
+        rnd = rng.integers(0, U64, k, dtype=np.uint64)
+        rco, oo = o.sample(1, k, 0.4, rnd)
+        keys = np.concatenate([oo["key"], rng.integers(0, 3000, extra).astype(np.uint64)])   # extra: > 1024 pairs
+        newp = rng.lognormal(0, 1, len(keys)).astype(F32)
+        o.update_priorities(keys, newp)
+        out = g.alloc_sample_outputs(1, k)
+        out["mass"] = torch.empty(k, dtype=torch.int64, device="cuda:0")
+        assert g.sample_begin(1, k, dev(rnd), out) == 0
+        assert g.sample_finish_update(1, k, 0.4, out, dev(keys), dev(newp)) == 0
+        torch.cuda.synchronize()
+        assert_sample_equal(out, oo)
+        check_gpu_tree(g, o)
