@@ -136,6 +136,12 @@ class GpuJob:
             rc, _, _ = pipe.add_end(evict=(f + ADD_EVERY) % EVICT_EVERY == 0)
             assert rc == 0, rc
 
+    def run_pipelined_learner_only(self, first, count):
+        assert self.pipe.fork() == 0
+        rc, _ = self.pipe.steps(count, self.w.beta, self.rnd[first:first + count], self.td[first:first + count])
+        assert rc == 0, rc
+        assert self.pipe.join() == 0
+
     def run_pipelined(self, first, count):
         assert self.pipe.fork() == 0
         self.issue_windows(first, count)
@@ -257,6 +263,8 @@ def main():
     # (2) the library's pipeline (learner steps as two launches each; add payloads on a second stream)
     dt_pipe, host_pipe = job.timed(lambda: job.run_pipelined(W, K))
     log("pipeline, two streams: %.2f us/step (host enqueue %.2f us/step)" % (dt_pipe / K * 1e6, host_pipe / K * 1e6))
+    dt_pipe_learner, _ = job.timed(lambda: job.run_pipelined_learner_only(W + K, K))
+    log("pipeline, learner steps only: %.2f us/step" % (dt_pipe_learner / K * 1e6))
     mode, dt = "apex_pipeline: two streams, eager launches", dt_pipe
     # (3) one cycle of the same pipeline captured as a HIP graph and replayed
     job.capture_cycle(W)
@@ -298,7 +306,7 @@ def main():
         "priority_updates_per_s": w.k * K / dt,
         "adds_per_s": w.add_count * (K // ADD_EVERY) / dt,
         "variants_us_per_step": {"one_stream": dt_serial / K * 1e6, "one_stream_learner_only": dt_learner / K * 1e6,
-                                 "pipeline": dt_pipe / K * 1e6, "pipeline_graph": dt_graph / K * 1e6},
+                                 "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6},
         "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel (frame-stack gather)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_GATHER_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,
