@@ -27,9 +27,11 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 ADD_EVERY, EVICT_EVERY = 25, 100
 
-# HBM bytes per launch of the gather kernel measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE),
-# scaled by a plain copy of known size; see profiles/.  None until measured.
-MEASURED_GATHER_TRAFFIC_BYTES = None
+# HBM bytes per launch of the gather(+weights+update) kernel, from two rocprofv3 --pmc runs of this
+# script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads
+# for a plain 508,032,000-byte copy in the same run (FETCH_SIZE reads half the bytes, WRITE_SIZE all):
+#   (7164.6 * 1.99984 + 14229.0 * 1.0) KiB.   See profiles/gather_atari_hbm_traffic.txt.
+MEASURED_GATHER_TRAFFIC_BYTES = int((7164.6 * 496125.0 / 248085.8 + 14229.0) * 1024)
 
 
 def dev(a):
@@ -167,19 +169,24 @@ class GpuJob:
         torch.cuda.synchronize()
         return time.perf_counter() - t0, t_host
 
-    def gather_kernel_ms(self, launches=50, replays=10):
-        """Average duration of the dominant kernel (the frame-stack gather of one batch of 512), between
-        HIP events on the launch stream.  The launches are captured once and replayed, so that the host's
-        launch rate does not enter the figure."""
-        torch = self.torch
-        out = self.outs[0]
-        slot = out["slot"]
+    def gather_kernel_ms(self, sets=64, replays=8):
+        """Average duration of the dominant kernel as it runs in the timed loop: the launch that gathers the
+        512 frame stacks of one batch, with that batch's importance weights and the write-back of its
+        priorities riding along.  `sets` batches are drawn first, so that every launch reads and writes other
+        rows (nothing is served from the 256 MB memory-side cache); the launches are then captured once and
+        replayed, so that the host's launch rate does not enter the figure; HIP events on the launch stream."""
+        torch, w = self.torch, self.w
+        pipe = self.apex.Pipeline(self.rep, sets, 1, w.k)
+        assert pipe.fork() == 0
+        assert pipe.steps(sets, w.beta, self.rnd[:sets], None)[0] == 0
+        assert pipe.join() == 0
         s = torch.cuda.Stream()
         torch.cuda.synchronize()
         graph = torch.cuda.CUDAGraph()
         with torch.cuda.graph(graph, stream=s):
-            for _ in range(launches):
-                assert self.rep.gather(slot, out["obs"]) == 0
+            for i in range(sets):
+                o = pipe.sets[i]
+                assert self.rep.sample_finish_writeback(1, w.k, w.beta, o, self.td[i]) == 0
         graph.replay()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
@@ -188,7 +195,9 @@ class GpuJob:
             graph.replay()
         e1.record()
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / (launches * replays)
+        ms = e0.elapsed_time(e1) / (sets * replays)
+        pipe.close()
+        return ms
 
 
 def cpu_baseline(w, budget_steps, log):
@@ -307,7 +316,8 @@ def main():
         "adds_per_s": w.add_count * (K // ADD_EVERY) / dt,
         "variants_us_per_step": {"one_stream": dt_serial / K * 1e6, "one_stream_learner_only": dt_learner / K * 1e6,
                                  "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6},
-        "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel (frame-stack gather)",
+        "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel<u32x4,2,weights,update> (frame-stack gather "
+                                               "of one batch, distinct rows every launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_GATHER_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,
                      "us_per_launch": gather_ms * 1e3},

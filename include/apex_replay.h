@@ -176,7 +176,8 @@ int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio,
  * interval of the cumulative mass, taken in slot order, contains x.  rnd is a device array
  * [num_batches,k] of uniform 64-bit integers supplied by the caller.
  * weight_out[b,j] = (N * P(i))^-beta / max over the batch, N = size, P(i) = mass_i / total:
- * importance-sampling weights normalised by the largest weight of the same batch of k.
+ * importance-sampling weights normalised by the largest weight of the same batch of k; beta in
+ * [0, 1] (Section 4.1: 0.4), fp32, relative error below 1e-6.
  * Device outputs, each may be NULL except slot_out: key_out [nb,k] u64, slot_out [nb,k] u32,
  * weight_out [nb,k] f32, obs_out [nb,k,obs_bytes], act_out [nb,k,act_bytes], ret_out, gacc_out
  * [nb,k] f32 (copies of what apex_replay_add stored).
@@ -210,6 +211,18 @@ int apex_replay_sample_finish(apex_replay_t *r, uint32_t num_batches, uint32_t k
 int apex_replay_sample_finish_update(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta,
                                      const uint32_t *slot, const uint64_t *mass, float *weight_out, void *obs_out,
                                      uint64_t m, const uint64_t *key, const float *prio, void *hip_stream);
+/*
+ * apex_replay_sample_finish, and the new priorities of the very batch being finished written back
+ * in the same launch: prio[i] (device, [nb*k]) becomes the priority of key[i], the transition
+ * drawn as sample i (key, slot, mass as written by the matching apex_replay_sample_begin).
+ * Allowed only if nothing has touched the sum tree since that apex_replay_sample_begin (no update,
+ * add or eviction in between): the write-back then takes slot and mass as known, skipping the
+ * loads key -> slot -> mass.  Result: that of apex_replay_sample_finish followed by
+ * apex_replay_update_priorities(nb*k, key, prio).
+ */
+int apex_replay_sample_finish_writeback(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta,
+                                        const uint64_t *key, const uint32_t *slot, const uint64_t *mass,
+                                        float *weight_out, void *obs_out, const float *prio, void *hip_stream);
 
 /*
  * The read half of replay.Sample on its own (Appendix "Implementation", "Data Storage": reading

@@ -22,7 +22,7 @@ TREE_MAX_LEVELS = 8
 EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_destroy", "apex_replay_layout",
            "apex_nstep_priorities", "apex_replay_add", "apex_replay_add_payload", "apex_replay_add_publish",
            "apex_replay_sample", "apex_replay_sample_begin", "apex_replay_sample_finish",
-           "apex_replay_sample_finish_update", "apex_replay_gather",
+           "apex_replay_sample_finish_update", "apex_replay_sample_finish_writeback", "apex_replay_gather",
            "apex_replay_update_priorities", "apex_replay_evict", "apex_replay_resync", "apex_replay_stats",
            "apex_last_hip_error", "apex_pipeline_create", "apex_pipeline_destroy", "apex_pipeline_fork",
            "apex_pipeline_join", "apex_pipeline_steps", "apex_pipeline_add_begin", "apex_pipeline_add_end",
@@ -68,6 +68,7 @@ lib.apex_replay_add_publish.argtypes = [_vp, _u64, _vp, C.POINTER(_u64), _vp]
 lib.apex_replay_sample_begin.argtypes = [_vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_sample_finish.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_sample_finish_update.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _u64, _vp, _vp, _vp]
+lib.apex_replay_sample_finish_writeback.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_resync.argtypes = [_vp, _vp]
 lib.apex_replay_gather.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
@@ -229,6 +230,11 @@ class Replay:
                                                     _ptr(out.get("mass")), _ptr(out.get("weight")),
                                                     _ptr(out.get("obs")), key.shape[0], _ptr(key), _ptr(prio),
                                                     _stream(stream))
+
+    def sample_finish_writeback(self, num_batches, k, beta, out, prio, stream=None):
+        return lib.apex_replay_sample_finish_writeback(self.h, num_batches, k, beta, _ptr(out["key"]), _ptr(out["slot"]),
+                                                       _ptr(out["mass"]), _ptr(out.get("weight")), _ptr(out.get("obs")),
+                                                       _ptr(prio), _stream(stream))
 
     def resync(self, stream=None):
         return lib.apex_replay_resync(self.h, _stream(stream))

@@ -128,22 +128,25 @@ int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const Ro
     const uint32_t cpr = (vpr + kThreads * kUnroll - 1) / (kThreads * kUnroll);
     if (nrows * cpr > 0x7ffffff0ull) return APEX_ERR_TOO_LARGE;
     const uint32_t blocks = (uint32_t)(nrows * cpr);
-    const bool w = jobs && jobs->wa.weight_out, u = jobs && jobs->ua.m;
+    bool w = jobs && jobs->wa.weight_out, u = jobs && jobs->ua.m;
+    uint32_t nb = w ? (uint32_t)(nrows / jobs->wa.k) : 0;  // one workgroup per batch takes its weights along
+    if (blocks < nb + (u ? 1u : 0u)) w = u = false, nb = 0;    // too few workgroups to carry the side jobs
     const WeightArgs wa = w ? jobs->wa : WeightArgs{nullptr, nullptr, 1, 0.f};
     const UpdateArgs ua = u ? jobs->ua : UpdateArgs{};
-    const uint32_t nb = w ? (uint32_t)(nrows / wa.k) : 0;  // one leading workgroup per batch
-    const dim3 grid(blocks + nb + (u ? 1 : 0)), block(kThreads);
+    const dim3 grid(blocks), block(kThreads);
+    // a same-batch write-back (slot/mass known) has one pair per copied row: spread it over the rows
+    const int umode = !u ? 0 : (ua.slot_hint && ua.m == nrows) ? 2 : 1;
 #define APEX_LAUNCH_COPY(W, U) \
   copy_rows_long_kernel<Vec, kUnroll, W, U><<<grid, block, 0, stream>>>(src, smap, dst, dmap, vpr, cpr, row_bytes, wa, nb, ua)
-    if (w && u) APEX_LAUNCH_COPY(true, true);
-    else if (w) APEX_LAUNCH_COPY(true, false);
-    else if (u) APEX_LAUNCH_COPY(false, true);
-    else APEX_LAUNCH_COPY(false, false);
+    if (w && umode == 2) APEX_LAUNCH_COPY(true, 2);
+    else if (w && umode == 1) APEX_LAUNCH_COPY(true, 1);
+    else if (w) APEX_LAUNCH_COPY(true, 0);
+    else if (umode == 2) APEX_LAUNCH_COPY(false, 2);
+    else if (umode == 1) APEX_LAUNCH_COPY(false, 1);
+    else APEX_LAUNCH_COPY(false, 0);
 #undef APEX_LAUNCH_COPY
-    if (jobs) {
-      jobs->wa.weight_out = nullptr;
-      jobs->ua.m = 0;
-    }
+    if (w) jobs->wa.weight_out = nullptr;
+    if (u) jobs->ua.m = 0;
   } else {
     uint32_t lanes_log2 = 0;
     while ((1u << lanes_log2) < vpr) ++lanes_log2;
@@ -348,7 +351,7 @@ namespace {
 int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *prio, hipStream_t stream)
 {
   if (m <= 1024) {
-    const UpdateArgs ua{r->tv, r->state(), (uint32_t)m, key, prio, r->qp};
+    const UpdateArgs ua{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, nullptr, nullptr};
     update_small_kernel<<<dim3(1), dim3((uint32_t)round_up(m, kWave)), 0, stream>>>(ua);
   } else {
     const dim3 grid(blocks_for(m, 256)), block(256);
@@ -359,13 +362,18 @@ int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *
 }
 
 // gather + importance weights (+ a priority update riding along when it fits one workgroup)
+// same_batch: the pairs are the batch being finished (key[i] lives in slot[i] and weighs mass[i]) and
+// nothing has touched the tree since it was drawn.
 int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
                 const uint64_t *mass, float *weight_out, void *obs_out, uint64_t m, const uint64_t *key,
-                const float *prio, hipStream_t stream)
+                const float *prio, hipStream_t stream, bool same_batch = false)
 {
   SideJobs jobs;
   jobs.wa = WeightArgs{mass, weight_out, k, beta};
-  if (m && m <= 1024) jobs.ua = UpdateArgs{r->tv, r->state(), (uint32_t)m, key, prio, r->qp};
+  const bool hint = same_batch && mass && m == (uint64_t)num_batches * k;
+  if (m && (m <= 1024 || hint)) {
+    jobs.ua = UpdateArgs{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, hint ? slot : nullptr, hint ? mass : nullptr};
+  }
   if (obs_out) {
     const RowMap by_slot{slot, nullptr, 0};
     const RowMap ident{nullptr, nullptr, 0};
@@ -376,14 +384,14 @@ int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, co
     batch_weights_kernel<<<dim3(num_batches), dim3(256), 0, stream>>>(jobs.wa);
     APEX_HIP(hipGetLastError());
   }
-  if (m && (m > 1024 || jobs.ua.m)) return launch_update(r, m, key, prio, stream);
+  if (m && (jobs.ua.m || !(m <= 1024 || hint))) return launch_update(r, m, key, prio, stream);
   return APEX_OK;
 }
 
 int check_finish_args(const apex_replay *r, uint32_t num_batches, uint32_t k, float beta, const uint32_t *slot,
                       const uint64_t *mass, const float *weight_out)
 {
-  if (!r || !num_batches || !k || !slot || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  if (!r || !num_batches || !k || !slot || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
   if (weight_out && !mass) return APEX_ERR_INVALID_ARG;
   if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
     return APEX_ERR_TOO_LARGE;
@@ -407,17 +415,29 @@ int apex_replay_sample_finish_update(apex_replay_t *r, uint32_t num_batches, uin
 {
   const int rc = check_finish_args(r, num_batches, k, beta, slot, mass, weight_out);
   if (rc != APEX_OK) return rc;
-  if (m && (!key || !prio)) return APEX_ERR_INVALID_ARG;
+  if (m && !prio) return APEX_ERR_INVALID_ARG;
   if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
+  if (m && !key) return APEX_ERR_INVALID_ARG;
   return finish_impl(r, num_batches, k, beta, slot, mass, weight_out, obs_out, m, key, prio,
                      static_cast<hipStream_t>(hip_stream));
+}
+
+int apex_replay_sample_finish_writeback(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta,
+                                        const uint64_t *key, const uint32_t *slot, const uint64_t *mass,
+                                        float *weight_out, void *obs_out, const float *prio, void *hip_stream)
+{
+  const int rc = check_finish_args(r, num_batches, k, beta, slot, mass, weight_out);
+  if (rc != APEX_OK) return rc;
+  if (!key || !mass || !prio) return APEX_ERR_INVALID_ARG;
+  return finish_impl(r, num_batches, k, beta, slot, mass, weight_out, obs_out, (uint64_t)num_batches * k, key, prio,
+                     static_cast<hipStream_t>(hip_stream), /*same_batch=*/true);
 }
 
 int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
                        uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
                        float *ret_out, float *gacc_out, void *hip_stream)
 {
-  if (!r || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  if (!r || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
   const int rc = apex_replay_sample_begin(r, num_batches, k, rnd, key_out, slot_out, r->mass(), act_out, ret_out,
                                           gacc_out, hip_stream);
   if (rc != APEX_OK) return rc;

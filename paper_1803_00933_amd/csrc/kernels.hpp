@@ -149,10 +149,45 @@ struct UpdateArgs {
   const uint64_t *key;
   const float *prio;
   QuantParams qp;
+  // Set by callers that draw a batch and write its priorities back with nothing touching the tree
+  // in between: pair i is known to be valid, to live in slot_hint[i] and to weigh mass_hint[i],
+  // which saves the two dependent loads key -> slot -> mass.
+  const uint32_t *slot_hint;
+  const uint64_t *mass_hint;
 };
 
-// h_slot, h_pos: LDS, kDedupeSlots words each.  Called by every thread of the workgroup.
-__device__ __forceinline__ void update_batch_in_block(const UpdateArgs &ua, uint32_t *h_slot, uint32_t *h_pos)
+// What one lane holds of its pair between the two halves below.
+struct UpdateLane {
+  uint64_t key, old;
+  uint32_t slot;
+  float prio;
+  uint64_t head, tail;
+};
+
+// First half: only loads, so that a caller can put other memory work behind them.
+__device__ __forceinline__ UpdateLane update_batch_load(const UpdateArgs &ua)
+{
+  UpdateLane u{0, 0, 0, 0.0f, 0, ~0ull};
+  const uint32_t i = threadIdx.x;
+  if (i < ua.m) {
+    u.prio = ua.prio[i];
+    if (ua.slot_hint) {
+      u.slot = ua.slot_hint[i];
+      u.old = ua.mass_hint[i];
+    } else {
+      u.key = ua.key[i];
+    }
+  }
+  if (!ua.slot_hint) {
+    u.head = ua.st->head;
+    u.tail = ua.st->tail;
+  }
+  return u;
+}
+
+// Second half.  h_slot, h_pos: LDS, kDedupeSlots words each.  Called by every thread of the workgroup.
+__device__ __forceinline__ void update_batch_apply(const UpdateArgs &ua, UpdateLane u, uint32_t *h_slot,
+                                                   uint32_t *h_pos)
 {
   const TreeView &tv = ua.tv;
   const uint32_t i = threadIdx.x;
@@ -160,22 +195,17 @@ __device__ __forceinline__ void update_batch_in_block(const UpdateArgs &ua, uint
     h_slot[t] = 0xffffffffu;  // no slot has this number: max_slots <= 2^31
     h_pos[t] = 0;
   }
-  uint64_t k = 0;
-  float p = 0.0f;
-  if (i < ua.m) {
-    k = ua.key[i];
-    p = ua.prio[i];
-  }
-  const uint64_t head = ua.st->head, tail = ua.st->tail;
   __syncthreads();
-  const bool valid = i < ua.m && k >= head && k < tail;
+  const bool valid = i < ua.m && u.key >= u.head && u.key < u.tail;
   const bool stale = i < ua.m && !valid;
   bool clamped = false;
-  uint32_t slot = 0, h = 0;
-  uint64_t q = 0, old = 0;
+  uint32_t slot = u.slot, h = 0;
+  uint64_t q = 0, old = u.old;
   if (valid) {
-    slot = (uint32_t)(k % tv.P);
-    old = tv.level[0][slot];  // in flight during the dedupe
+    if (!ua.slot_hint) {
+      slot = (uint32_t)(u.key % tv.P);
+      old = tv.level[0][slot];  // in flight during the dedupe
+    }
     h = (slot * 2654435761u) >> 21;  // top 11 bits
     for (;;) {
       const uint32_t prev = atomicCAS(&h_slot[h], 0xffffffffu, slot);
@@ -183,7 +213,7 @@ __device__ __forceinline__ void update_batch_in_block(const UpdateArgs &ua, uint
       h = (h + 1) & (kDedupeSlots - 1);
     }
     atomicMax(&h_pos[h], i + 1);
-    q = quantise_priority(p, ua.qp, &clamped);
+    q = quantise_priority(u.prio, ua.qp, &clamped);
   }
   __syncthreads();
   if (valid && h_pos[h] == i + 1) {
@@ -195,6 +225,11 @@ __device__ __forceinline__ void update_batch_in_block(const UpdateArgs &ua, uint
     if (ns) atomic_add_u64(&ua.st->n_stale, ns);
     if (nc) atomic_add_u64(&ua.st->n_clamped, nc);
   }
+}
+
+__device__ __forceinline__ void update_batch_in_block(const UpdateArgs &ua, uint32_t *h_slot, uint32_t *h_pos)
+{
+  update_batch_apply(ua, update_batch_load(ua), h_slot, h_pos);
 }
 
 __global__ __launch_bounds__(1024) void update_small_kernel(UpdateArgs ua)
@@ -224,8 +259,11 @@ __device__ __forceinline__ void batch_weights(const WeightArgs &wa, uint32_t b, 
   if (lane_id() == 0) red[tid / kWave] = mn;
   __syncthreads();
   for (uint32_t w = 0; w < nwave; ++w) mn = red[w] < mn ? red[w] : mn;
+  // fp32 with the library's own power routine (relative error below 1e-6 here): a double-precision
+  // pow would cost this kernel 70 registers per lane and half of its occupancy
+  const float fmn = (float)mn;
   for (uint32_t i = tid; i < wa.k; i += nthr)
-    wa.weight_out[(uint64_t)b * wa.k + i] = (float)pow((double)mn / (double)bm[i], (double)wa.beta);
+    wa.weight_out[(uint64_t)b * wa.k + i] = pow_fixed_sequence(fmn / (float)bm[i], wa.beta);
 }
 
 constexpr int kLongCopyThreads = 1024;  // one workgroup of 16 waves per 28 KB frame stack
@@ -239,35 +277,25 @@ __global__ __launch_bounds__(256) void batch_weights_kernel(WeightArgs wa)
 
 // Long rows (frame stacks): a workgroup copies kUnroll * blockDim consecutive vectors of one row,
 // all loads issued before the first store so that a whole row can be in flight.
-// The grid may carry leading workgroups with side jobs that touch none of the copied bytes, so
-// that a learner step needs no launch of their own for them:
-//   kUpdate   workgroup 0 writes a batch of priorities back into the sum tree;
-//   kWeights  the next weight_blocks workgroups write one batch's importance weights each.
-template <typename Vec, int kUnroll, bool kWeights, bool kUpdate>
+// Some workgroups can take a side job that touches none of the copied bytes (its loads issued
+// behind the row loads, its work done once the row has been stored), so that a learner step
+// needs no launch of its own for it and the grid stays at one workgroup per row (the chip holds
+// exactly 512 workgroups of 1024 lanes at a time, the size of a learner batch):
+//   kUpdate = 1  workgroup 0 writes a batch of (key, priority) pairs back into the sum tree;
+//   kUpdate = 2  the rows are a freshly drawn batch whose own priorities are written back: the
+//                workgroup of row i handles pair i (slot and old mass are known from the draw;
+//                it wins unless a later sample drew the same slot), which spreads the atomics
+//                over the whole chip;
+//   kWeights     the first weight_blocks workgroups (after workgroup 0 if kUpdate = 1) write one
+//                batch's importance weights each.
+template <typename Vec, int kUnroll, bool kWeights, int kUpdate>
 __global__ __launch_bounds__(kLongCopyThreads) void copy_rows_long_kernel(const uint8_t *__restrict__ src, RowMap smap,
                                                                           uint8_t *__restrict__ dst, RowMap dmap,
                                                                           uint32_t vecs_per_row, uint32_t chunks_per_row,
                                                                           uint64_t row_bytes, WeightArgs wa,
                                                                           uint32_t weight_blocks, UpdateArgs ua)
 {
-  uint32_t blk = blockIdx.x;
-  if (kUpdate) {
-    __shared__ uint32_t h_slot[kDedupeSlots];
-    __shared__ uint32_t h_pos[kDedupeSlots];
-    if (blk == 0) {
-      update_batch_in_block(ua, h_slot, h_pos);
-      return;
-    }
-    blk -= 1;
-  }
-  if (kWeights) {
-    __shared__ uint64_t red[kLongCopyThreads / kWave];
-    if (blk < weight_blocks) {
-      batch_weights(wa, blk, red);
-      return;
-    }
-    blk -= weight_blocks;
-  }
+  const uint32_t blk = blockIdx.x;
   const uint32_t row = blk / chunks_per_row;
   const uint32_t chunk = blk - row * chunks_per_row;
   const Vec *s = reinterpret_cast<const Vec *>(src + map_row(smap, row) * row_bytes);
@@ -279,10 +307,46 @@ __global__ __launch_bounds__(kLongCopyThreads) void copy_rows_long_kernel(const 
     const uint32_t v = v0 + u * blockDim.x;
     if (v < vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
   }
+  // side-job loads go out behind the row loads; the row is stored as soon as it has arrived
+  UpdateLane ul{};
+  if (kUpdate == 1 && blk == 0) ul = update_batch_load(ua);
+  const bool writer = kUpdate == 2 && chunk == 0 && threadIdx.x < kWave;  // first wave of the row's first workgroup
+  uint32_t my_slot = 0;
+  bool later_dup = false;
+  if (writer) {
+    my_slot = ua.slot_hint[row];
+    for (uint32_t j = row + 1 + threadIdx.x; j < ua.m; j += kWave) later_dup |= ua.slot_hint[j] == my_slot;
+    if (threadIdx.x == 0) {
+      ul.old = ua.mass_hint[row];
+      ul.prio = ua.prio[row];
+    }
+  }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = v0 + u * blockDim.x;
     if (v < vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+  }
+  if (kUpdate == 1) {
+    __shared__ uint32_t h_slot[kDedupeSlots];
+    __shared__ uint32_t h_pos[kDedupeSlots];
+    if (blk == 0) update_batch_apply(ua, ul, h_slot, h_pos);
+  }
+  if (writer) {
+    const bool loses = __ballot(later_dup) != 0;  // last occurrence wins, as in a sequential loop
+    if (threadIdx.x == 0) {
+      bool clamped;
+      const uint64_t q = quantise_priority(ul.prio, ua.qp, &clamped);  // counted for losers too
+      if (!loses) {
+        ua.tv.level[0][my_slot] = q;
+        add_to_ancestors(ua.tv, my_slot, q - ul.old);
+      }
+      if (clamped) atomic_add_u64(&ua.st->n_clamped, 1);
+    }
+  }
+  if (kWeights) {
+    __shared__ uint64_t red[kLongCopyThreads / kWave];
+    const uint32_t first = kUpdate == 1 ? 1 : 0;
+    if (blk >= first && blk < first + weight_blocks) batch_weights(wa, blk - first, red);
   }
 }
 

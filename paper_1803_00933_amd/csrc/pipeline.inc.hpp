@@ -150,7 +150,7 @@ int apex_pipeline_join(apex_pipeline_t *p, void *stream)
 int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64_t *rnd, const float *new_prio,
                         uint32_t *first_set_out)
 {
-  if (!p || (n && !rnd) || !(beta >= 0.0f) || !(beta <= 16.0f)) return APEX_ERR_INVALID_ARG;
+  if (!p || (n && !rnd) || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
   if (first_set_out) *first_set_out = (uint32_t)(p->step % p->depth);
   const uint64_t per = (uint64_t)p->nb * p->k;
   for (uint32_t i = 0; i < n; ++i) {
@@ -158,9 +158,11 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
     APEX_TRY(apex_replay_sample_begin(p->r, p->nb, p->k, rnd + i * per, b.key, b.slot, b.mass, b.act, b.ret, b.gacc,
                                       p->tree));
     // the gather of this batch, its weights, and the write-back of its priorities: one launch
-    APEX_TRY(apex_replay_sample_finish_update(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs,
-                                              new_prio ? per : 0, b.key, new_prio ? new_prio + i * per : nullptr,
-                                              p->tree));
+    if (new_prio)
+      APEX_TRY(apex_replay_sample_finish_writeback(p->r, p->nb, p->k, beta, b.key, b.slot, b.mass, b.weight, b.obs,
+                                                   new_prio + i * per, p->tree));
+    else
+      APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs, p->tree));
     ++p->step;
   }
   return APEX_OK;

@@ -462,3 +462,26 @@ def test_finish_with_update_riding_along(ob, k, extra):
         torch.cuda.synchronize()
         assert_sample_equal(out, oo)
         check_gpu_tree(g, o)
+        # the batch's own priorities written back by the launch that finishes it
+        rnd = rng.integers(0, U64, k, dtype=np.uint64)
+        rco, oo = o.sample(1, k, 0.4, rnd)
+        newp = rng.lognormal(0, 1, k).astype(F32)
+        o.update_priorities(oo["key"], newp)
+        assert g.sample_begin(1, k, dev(rnd), out) == 0
+        assert g.sample_finish_writeback(1, k, 0.4, out, dev(newp)) == 0
+        torch.cuda.synchronize()
+        assert_sample_equal(out, oo)
+        check_gpu_tree(g, o)
+        # several batches per call: samples of different batches collide on heavy transitions
+        nb = 3
+        rnd = rng.integers(0, U64, nb * k, dtype=np.uint64)
+        rco, oo = o.sample(nb, k, 0.4, rnd)
+        newp = rng.lognormal(0, 1, nb * k).astype(F32)
+        o.update_priorities(oo["key"], newp)
+        out3 = g.alloc_sample_outputs(nb, k)
+        out3["mass"] = torch.empty(nb * k, dtype=torch.int64, device="cuda:0")
+        assert g.sample_begin(nb, k, dev(rnd), out3) == 0
+        assert g.sample_finish_writeback(nb, k, 0.4, out3, dev(newp)) == 0
+        torch.cuda.synchronize()
+        assert_sample_equal(out3, oo)
+        check_gpu_tree(g, o)
