@@ -30,8 +30,8 @@ ADD_EVERY, EVICT_EVERY = 25, 100
 # HBM bytes per launch of the gather(+weights+update) kernel, from two rocprofv3 --pmc runs of this
 # script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads
 # for a plain 508,032,000-byte copy in the same run (FETCH_SIZE reads half the bytes, WRITE_SIZE all):
-#   (7164.6 * 1.99984 + 14229.0 * 1.0) KiB.   See profiles/gather_atari_hbm_traffic.txt.
-MEASURED_GATHER_TRAFFIC_BYTES = int((7164.6 * 496125.0 / 248085.8 + 14229.0) * 1024)
+#   (7178.3 * 1.99982 + 14264.7 * 1.0) KiB.   See profiles/gather_atari_hbm_traffic.txt.
+MEASURED_GATHER_TRAFFIC_BYTES = int((7178.3 * 496125.0 / 248084.9 + 14264.7) * 1024)
 
 
 def dev(a):
