@@ -200,6 +200,54 @@ class GpuJob:
         return ms
 
 
+def op_timings(job):
+    """Device time of the other steps of the path on their own, microseconds (HIP events on the launch
+    stream; repeated launches are captured once and replayed so that host launch cost stays out)."""
+    torch, w, rep, apex = job.torch, job.w, job.rep, job.apex
+
+    def replayed(fn, n=32, replays=4):
+        s = torch.cuda.Stream()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            for i in range(n):
+                fn(i)
+        g.replay()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(replays):
+            g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (n * replays) * 1e3
+
+    out = {}
+    t = job.rounds[0]
+    out["nstep_priorities_18000"] = replayed(lambda i: apex.nstep_priorities(
+        t["q_online"], t["q_target"], t["action"], t["reward"], t["discount"], w.n, w.alpha, w.eps, w.frac_bits,
+        w.max_slots, want_fx=False, out=t["out"]))
+    o = job.outs[0]
+    o["mass"] = torch.empty(w.k, dtype=torch.int64, device="cuda:0")
+    out["descent_512"] = replayed(lambda i: rep.sample_begin(1, w.k, job.rnd[i], o))
+    out["update_512"] = replayed(lambda i: rep.update_priorities(o["key"], job.td[i]))
+    # add rounds and the eviction that follows them change the size of the memory: timed once, eagerly
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    n_add = EVICT_EVERY // ADD_EVERY
+    for i in range(n_add):
+        job.add_round(i)
+    ev[1].record()
+    rc, e = rep.evict()
+    ev[2].record()
+    torch.cuda.synchronize()
+    assert rc == 0 and e == n_add * w.add_count
+    out["add_round_18000_incl_nstep"] = ev[0].elapsed_time(ev[1]) / n_add * 1e3
+    out["evict_%d" % e] = ev[1].elapsed_time(ev[2]) * 1e3
+    return out
+
+
 def cpu_baseline(w, budget_steps, log):
     """The oracle, untouched, on one host core: same schedule, bounded number of steps."""
     import oracle
@@ -294,6 +342,8 @@ def main():
     achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
     log("gather kernel: %.2f us/launch, %.0f GB/s" % (gather_ms * 1e3, achieved))
 
+    ops = op_timings(job)
+    log("other steps alone, us: %s" % {k: round(v, 2) for k, v in ops.items()})
     cpu = cpu_baseline(w, args.cpu_steps, log) if args.cpu_steps > 0 else None
 
     line = {
@@ -314,6 +364,8 @@ def main():
                    "launch_mode": mode},
         "priority_updates_per_s": w.k * K / dt,
         "adds_per_s": w.add_count * (K // ADD_EVERY) / dt,
+        "nstep_priorities_per_s": w.add_count / (ops["nstep_priorities_18000"] * 1e-6),
+        "ops_us": ops,
         "variants_us_per_step": {"one_stream": dt_serial / K * 1e6, "one_stream_learner_only": dt_learner / K * 1e6,
                                  "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6},
         "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel<u32x4,2,weights,update> (frame-stack gather "

@@ -171,6 +171,14 @@ def test_atari_shape_full_size():
             assert_close(host(g_["weight"]), o_["weight"], "weight")
             idx = torch.from_numpy(o_["slot"][:32].astype(np.int64)).to("cuda:0")
             assert torch.equal(g_["obs"][:32], p.g.obs_view()[idx])
+        # the add round's payload (copied on the second stream) sits in the slots of its keys
+        first = p.o.tail - w.add_count
+        rows = np.linspace(0, w.add_count - 1, 97).astype(np.int64)
+        slots_new = torch.from_numpy((first + rows) % w.max_slots).to("cuda:0")
+        rows_t = torch.from_numpy(rows).to("cuda:0")
+        assert torch.equal(p.g.obs_view()[slots_new], obs[rows_t])
+        assert torch.equal(p.g.act_view()[slots_new], dd["act"][rows_t])
+        assert np.array_equal(host(p.g.ret_view()[slots_new]).view(np.uint32), ref_n[1].reshape(-1)[rows].view(np.uint32))
 
     torch.cuda.synchronize()
     assert pipe.fork() == 0
