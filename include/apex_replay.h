@@ -244,6 +244,21 @@ int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *
                                   void *hip_stream);
 
 /*
+ * ComputePriorities and replay.SetPriority of Algorithm 2 as one call: the learner hands over the
+ * Q-values it has just evaluated for a sampled batch and the library recomputes the priorities
+ * from the partial return and accumulated discount it stores with every transition (Appendix
+ * "Implementation", "Adding Data"): for i in [0,m), with ret and gacc those of key[i],
+ *     prio = | ret + gacc * q_target_next[i, argmax_a q_online_next[i,a]] - q_taken[i] |
+ * (the target of Section 3.1; A = 1 with critic values gives that of Section 3.2), fp32 in the same
+ * order as apex_nstep_priorities, then exactly as apex_replay_update_priorities(m, key, prio).
+ * Device arrays: key [m] u64, q_taken [m], q_online_next and q_target_next [m,A] fp32; prio_out
+ * [m] (may be NULL) receives the priorities (0 for pairs skipped because their key is not valid).
+ */
+int apex_replay_update_from_q(apex_replay_t *r, uint64_t m, const uint64_t *key, uint32_t A, const float *q_taken,
+                              const float *q_online_next, const float *q_target_next, float *prio_out,
+                              void *hip_stream);
+
+/*
  * replay.RemoveToFit (Algorithm 2; Section 4.1: excess above the soft capacity is removed en
  * masse, oldest first): removes the size - capacity oldest keys, if any.  *evicted_out (host,
  * may be NULL) receives their number.

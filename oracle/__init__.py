@@ -56,6 +56,8 @@ def lib():
         L.oracle_replay_sample_linear.argtypes = [_vp, _u32, _vp, _vp]
         L.oracle_replay_update_priorities.restype = C.c_int
         L.oracle_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp]
+        L.oracle_replay_update_from_q.restype = C.c_int
+        L.oracle_replay_update_from_q.argtypes = [_vp, _u64, _vp, _u32, _vp, _vp, _vp, _vp]
         L.oracle_replay_evict.restype = C.c_int
         L.oracle_replay_evict.argtypes = [_vp, C.POINTER(_u64)]
         for name in ("head", "tail", "root", "n_stale", "n_clamped", "tree_leaves"):
@@ -182,6 +184,14 @@ class Replay:
     def update_priorities(self, key, prio):
         key, prio = _arr(key, np.uint64), _arr(prio, np.float32)
         return lib().oracle_replay_update_priorities(self.h, key.shape[0], _p(key), _p(prio))
+
+    def update_from_q(self, key, q_taken, q_online_next, q_target_next):
+        key = _arr(key, np.uint64)
+        q_taken, qo, qt = _arr(q_taken, np.float32), _arr(q_online_next, np.float32), _arr(q_target_next, np.float32)
+        prio = np.zeros(key.shape[0], np.float32)
+        rc = lib().oracle_replay_update_from_q(self.h, key.shape[0], _p(key), qo.shape[1], _p(q_taken), _p(qo), _p(qt),
+                                               _p(prio))
+        return rc, prio
 
     def evict(self):
         e = _u64(0)

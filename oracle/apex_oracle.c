@@ -386,6 +386,41 @@ int oracle_replay_update_priorities(oracle_replay *r, uint64_t m, const uint64_t
 }
 
 /*
+ * ComputePriorities of Algorithm 2 followed by replay.SetPriority: the learner's new priority of a
+ * sampled transition is the absolute n-step TD error again, now with the Q-values of the current
+ * networks, and with the partial return and accumulated discount that were stored with the
+ * transition (Appendix "Implementation", "Adding Data"):
+ *     | ret + gacc * q_target_next[argmax_a q_online_next[a]] - q_taken |
+ * Needs a memory that keeps its payload un-aliased.  Pairs are applied one after the other; a
+ * pair whose key is no longer valid is skipped and reports priority 0.
+ */
+int oracle_replay_update_from_q(oracle_replay *r, uint64_t m, const uint64_t *key, uint32_t A, const float *q_taken,
+                                const float *q_online_next, const float *q_target_next, float *prio_out)
+{
+  if (!r || !A || r->payload_slots != r->max_slots || (m && (!key || !q_taken || !q_online_next || !q_target_next)))
+    return ORACLE_ERR_INVALID_ARG;
+  for (uint64_t i = 0; i < m; ++i) {
+    if (key[i] < r->head || key[i] >= r->tail) {
+      r->n_stale++;
+      if (prio_out) prio_out[i] = 0.0f;
+      continue;
+    }
+    const uint64_t slot = key[i] % r->max_slots;
+    const float *row = q_online_next + i * A;
+    uint32_t best = 0;
+    for (uint32_t a = 1; a < A; ++a) if (row[a] > row[best]) best = a;
+    const float boot = q_target_next[i * A + best];
+    const float target = fmaf(r->gacc[slot], boot, r->ret[slot]);
+    const float p = fabsf(target - q_taken[i]);
+    if (prio_out) prio_out[i] = p;
+    int c;
+    set_leaf(r, slot, oracle_quantise(p, r->alpha, r->eps, r->frac_bits, r->qmax, &c));
+    r->n_clamped += (uint64_t)c;
+  }
+  return ORACLE_OK;
+}
+
+/*
  * replay.RemoveToFit (Algorithm 2; Atari experiments): whatever exceeds the soft
  * capacity is removed in one go, oldest first.
  */

@@ -23,7 +23,7 @@ EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_des
            "apex_nstep_priorities", "apex_replay_add", "apex_replay_add_payload", "apex_replay_add_publish",
            "apex_replay_sample", "apex_replay_sample_begin", "apex_replay_sample_finish",
            "apex_replay_sample_finish_update", "apex_replay_sample_finish_writeback", "apex_replay_gather",
-           "apex_replay_update_priorities", "apex_replay_evict", "apex_replay_resync", "apex_replay_stats",
+           "apex_replay_update_priorities", "apex_replay_update_from_q", "apex_replay_evict", "apex_replay_resync", "apex_replay_stats",
            "apex_last_hip_error", "apex_pipeline_create", "apex_pipeline_destroy", "apex_pipeline_fork",
            "apex_pipeline_join", "apex_pipeline_steps", "apex_pipeline_add_begin", "apex_pipeline_add_end",
            "apex_pipeline_capture_begin", "apex_pipeline_capture_end", "apex_pipeline_replay"]
@@ -72,6 +72,7 @@ lib.apex_replay_sample_finish_writeback.argtypes = [_vp, _u32, _u32, _f32, _vp, 
 lib.apex_replay_resync.argtypes = [_vp, _vp]
 lib.apex_replay_gather.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
+lib.apex_replay_update_from_q.argtypes = [_vp, _u64, _vp, _u32, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_evict.argtypes = [_vp, C.POINTER(_u64), _vp]
 lib.apex_replay_stats.argtypes = [_vp, C.POINTER(Stats), _vp]
 lib.apex_last_hip_error.argtypes = []
@@ -245,6 +246,11 @@ class Replay:
 
     def update_priorities(self, key, prio, stream=None):
         return lib.apex_replay_update_priorities(self.h, key.shape[0], _ptr(key), _ptr(prio), _stream(stream))
+
+    def update_from_q(self, key, q_taken, q_online_next, q_target_next, prio_out=None, stream=None):
+        return lib.apex_replay_update_from_q(self.h, key.shape[0], _ptr(key), q_online_next.shape[1], _ptr(q_taken),
+                                             _ptr(q_online_next), _ptr(q_target_next), _ptr(prio_out),
+                                             _stream(stream))
 
     def evict(self, stream=None):
         e = _u64(0)

@@ -348,15 +348,16 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
 
 namespace {
 
-int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *prio, hipStream_t stream)
+int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *prio, hipStream_t stream,
+                  const QSource &qs = QSource{})
 {
   if (m <= 1024) {
-    const UpdateArgs ua{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, nullptr, nullptr};
+    const UpdateArgs ua{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, nullptr, nullptr, qs};
     update_small_kernel<<<dim3(1), dim3((uint32_t)round_up(m, kWave)), 0, stream>>>(ua);
   } else {
     const dim3 grid(blocks_for(m, 256)), block(256);
     update_claim_kernel<<<grid, block, 0, stream>>>(r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim());
-    update_apply_kernel<<<grid, block, 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim());
+    update_apply_kernel<<<grid, block, 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim(), qs);
   }
   return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
 }
@@ -372,7 +373,8 @@ int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, co
   jobs.wa = WeightArgs{mass, weight_out, k, beta};
   const bool hint = same_batch && mass && m == (uint64_t)num_batches * k;
   if (m && (m <= 1024 || hint)) {
-    jobs.ua = UpdateArgs{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, hint ? slot : nullptr, hint ? mass : nullptr};
+    jobs.ua = UpdateArgs{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, hint ? slot : nullptr, hint ? mass : nullptr,
+                         QSource{}};
   }
   if (obs_out) {
     const RowMap by_slot{slot, nullptr, 0};
@@ -468,6 +470,17 @@ int apex_replay_update_priorities(apex_replay_t *r, uint64_t m, const uint64_t *
   if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
   if (m == 0) return APEX_OK;
   return launch_update(r, m, key, prio, static_cast<hipStream_t>(hip_stream));
+}
+
+int apex_replay_update_from_q(apex_replay_t *r, uint64_t m, const uint64_t *key, uint32_t A, const float *q_taken,
+                              const float *q_online_next, const float *q_target_next, float *prio_out,
+                              void *hip_stream)
+{
+  if (!r || !A || (m && (!key || !q_taken || !q_online_next || !q_target_next))) return APEX_ERR_INVALID_ARG;
+  if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
+  if (m == 0) return APEX_OK;
+  const QSource qs{q_taken, q_online_next, q_target_next, A, r->ret(), r->gacc(), prio_out};
+  return launch_update(r, m, key, nullptr, static_cast<hipStream_t>(hip_stream), qs);
 }
 
 int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream)

@@ -142,6 +142,38 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 // table keyed by slot (the highest position wins), so no pass over global memory is needed for
 // it, and the old mass is fetched while the table is being filled.
 constexpr uint32_t kDedupeSlots = 2048;  // >= 2 * 1024 pairs: linear probing stays short
+
+// Learner-side ComputePriorities (Algorithm 2) fused into the write-back: the new priority of a
+// sampled transition is recomputed from the partial return and accumulated discount stored with it
+// (Appendix "Implementation", "Adding Data") and the Q-values the learner has just evaluated,
+//   | ret + gacc * q_target_next[argmax_a q_online_next[a]] - q_taken |     (Section 3.1 target),
+// in the same fp32 order as the actor-side kernel.  q_taken == null: priorities are given.
+struct QSource {
+  const float *q_taken;        // [m]   q(S_t, A_t) of the online network
+  const float *q_online_next;  // [m,A] q(S_{t+n}, .) of the online network
+  const float *q_target_next;  // [m,A] q(S_{t+n}, .) of the target network
+  uint32_t A;
+  const float *ret, *gacc;     // columns of the payload ring
+  float *prio_out;             // [m] or null: the priorities that were computed (0 for skipped pairs)
+};
+
+__device__ __forceinline__ float td_priority(const QSource &qs, uint32_t i, uint64_t slot)
+{
+  const float *row = qs.q_online_next + (uint64_t)i * qs.A;
+  uint32_t best = 0;
+  float vbest = row[0];
+  for (uint32_t a = 1; a < qs.A; ++a) {
+    const float v = row[a];
+    if (v > vbest) {
+      vbest = v;
+      best = a;
+    }
+  }
+  const float boot = qs.q_target_next[(uint64_t)i * qs.A + best];
+  const float target = __builtin_fmaf(qs.gacc[slot], boot, qs.ret[slot]);
+  return __builtin_fabsf(target - qs.q_taken[i]);
+}
+
 struct UpdateArgs {
   TreeView tv;
   DeviceState *st;
@@ -154,6 +186,7 @@ struct UpdateArgs {
   // which saves the two dependent loads key -> slot -> mass.
   const uint32_t *slot_hint;
   const uint64_t *mass_hint;
+  QSource qs;
 };
 
 // What one lane holds of its pair between the two halves below.
@@ -170,7 +203,7 @@ __device__ __forceinline__ UpdateLane update_batch_load(const UpdateArgs &ua)
   UpdateLane u{0, 0, 0, 0.0f, 0, ~0ull};
   const uint32_t i = threadIdx.x;
   if (i < ua.m) {
-    u.prio = ua.prio[i];
+    if (!ua.qs.q_taken) u.prio = ua.prio[i];
     if (ua.slot_hint) {
       u.slot = ua.slot_hint[i];
       u.old = ua.mass_hint[i];
@@ -213,8 +246,11 @@ __device__ __forceinline__ void update_batch_apply(const UpdateArgs &ua, UpdateL
       h = (h + 1) & (kDedupeSlots - 1);
     }
     atomicMax(&h_pos[h], i + 1);
-    q = quantise_priority(u.prio, ua.qp, &clamped);
+    const float p = ua.qs.q_taken ? td_priority(ua.qs, i, slot) : u.prio;
+    q = quantise_priority(p, ua.qp, &clamped);
+    if (ua.qs.q_taken && ua.qs.prio_out) ua.qs.prio_out[i] = p;
   }
+  if (stale && ua.qs.q_taken && ua.qs.prio_out) ua.qs.prio_out[i] = 0.0f;
   __syncthreads();
   if (valid && h_pos[h] == i + 1) {
     tv.level[0][slot] = q;
@@ -434,7 +470,7 @@ __global__ __launch_bounds__(256) void update_claim_kernel(uint64_t P, DeviceSta
 __global__ __launch_bounds__(256) void update_apply_kernel(TreeView tv, DeviceState *__restrict__ st, uint32_t m,
                                                            const uint64_t *__restrict__ key,
                                                            const float *__restrict__ prio, QuantParams qp,
-                                                           uint32_t *__restrict__ claim)
+                                                           uint32_t *__restrict__ claim, QSource qs)
 {
   const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
   bool clamped = false;
@@ -442,13 +478,17 @@ __global__ __launch_bounds__(256) void update_apply_kernel(TreeView tv, DeviceSt
     const uint64_t k = key[i];
     if (k >= st->head && k < st->tail) {
       const uint64_t slot = k % tv.P;
-      const uint64_t q = quantise_priority(prio[i], qp, &clamped);
+      const float p = qs.q_taken ? td_priority(qs, i, slot) : prio[i];
+      if (qs.q_taken && qs.prio_out) qs.prio_out[i] = p;
+      const uint64_t q = quantise_priority(p, qp, &clamped);
       if (claim[slot] == i + 1) {
         const uint64_t old = tv.level[0][slot];
         tv.level[0][slot] = q;
         add_to_ancestors(tv, slot, q - old);
         claim[slot] = 0;
       }
+    } else if (qs.q_taken && qs.prio_out) {
+      qs.prio_out[i] = 0.0f;
     }
   }
   const uint64_t nc = __popcll(__ballot(clamped));

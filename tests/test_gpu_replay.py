@@ -485,3 +485,27 @@ def test_finish_with_update_riding_along(ob, k, extra):
         torch.cuda.synchronize()
         assert_sample_equal(out3, oo)
         check_gpu_tree(g, o)
+
+
+@pytest.mark.parametrize("m,A", [(512, 18), (96, 1), (3000, 4)])
+def test_update_from_learner_q_values(m, A):
+    """apex_replay_update_from_q: priorities recomputed from the stored (ret, gacc) and fresh Q-values, in the
+    one-workgroup path and in the two-pass path, with repeats and stale keys."""
+    rng = np.random.default_rng(17 + m)
+    g, o = make_pair(5000, 8192, 16, 4)
+    add_both(g, o, rng, 5000)
+    add_both(g, o, rng, 2000)
+    assert g.evict() == o.evict()                      # keys 0..1999 are stale now
+    for it in range(3):
+        keys = rng.integers(1500, 7300, m).astype(np.uint64)      # some stale, some not yet added, many repeats
+        q_taken = rng.standard_normal(m).astype(F32)
+        q_on = np.round(rng.standard_normal((m, A)) * 2).astype(F32) / 2       # ties in the argmax
+        q_tg = rng.standard_normal((m, A)).astype(F32)
+        rco, p_ref = o.update_from_q(keys, q_taken, q_on, q_tg)
+        p_out = torch.empty(m, dtype=torch.float32, device="cuda:0")
+        rcg = g.update_from_q(dev(keys), dev(q_taken), dev(q_on), dev(q_tg), p_out)
+        assert rcg == rco == 0
+        torch.cuda.synchronize()
+        assert np.array_equal(host(p_out).view(np.uint32), p_ref.view(np.uint32))
+        check_gpu_tree(g, o)
+    sample_both(g, o, rng, 2, 128)

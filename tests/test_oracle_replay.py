@@ -289,3 +289,43 @@ def test_soft_capacity_sawtooth_matches_the_reported_median_size():
         sizes.append(r.size)
     assert abs(np.median(sizes) * 100 - 2_035_050) / 2_035_050 < 2e-3
     assert r.root == C * r.leaves()[r.head % 32768]
+
+
+def test_update_from_q_hand_values_and_stale_keys():
+    # stored (ret, gacc) and fresh Q-values, all dyadic: | ret + gacc * q_target[argmax q_online] - q_taken |
+    r = oracle.Replay(4, 8, 4, 4, alpha=1.0, eps=0.0)
+    ret = np.array([2, 4, 0, -1], F32)
+    gacc = np.array([0.25, 0, 0.25, 0.5], F32)
+    r.add(np.ones(4, F32), np.zeros((4, 4), np.uint8), np.zeros((4, 4), np.uint8), ret, gacc)
+    q_on = np.array([[0, 8, 8], [9, 9, 9], [2, 2, 1], [-3, -2, -1]], F32)       # argmax 1 (tie), 0 (tie), 0 (tie), 2
+    q_tg = np.array([[10, 20, 30], [5, 6, 7], [12, 100, 100], [1, 2, 4]], F32)
+    q_taken = np.array([3, 4, -2, 0.5], F32)
+    # 0: 2 + .25*20 - 3 = 4    1: 4 + 0 - 4 = 0    2: 0 + .25*12 + 2 = 5    3: -1 + .5*4 - .5 = .5
+    rc, prio = r.update_from_q(np.arange(4, dtype=np.uint64), q_taken, q_on, q_tg)
+    assert rc == 0 and prio.tolist() == [4.0, 0.0, 5.0, 0.5]
+    assert r.leaves()[:4].tolist() == [4 << 24, 1, 5 << 24, 1 << 23]            # alpha 1: mass = p * 2^24 (0 -> clamp 1)
+    check_tree(r)
+    rc, prio = r.update_from_q(np.array([7, 2, 2], np.uint64), np.array([0, 0, 1], F32),
+                               np.zeros((3, 3), F32), np.zeros((3, 3), F32))
+    assert prio.tolist() == [0.0, 0.0, 1.0] and r.n_stale == 1                  # key 7 was never added
+    assert r.leaves()[2] == 1 << 24                                             # the later pair for key 2 stands
+
+
+def test_update_from_q_reproduces_the_actor_side_priorities():
+    # with the Q-values the actors used, the learner-side recompute gives the actor-side priorities back
+    from paper_1803_00933_amd import synth
+    w = synth.WORKLOADS["tiny"]
+    d = synth.actor_round(w, 5)
+    prio, ret, gacc, fx = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"],
+                                                  d["discount"], w.n, w.alpha, w.eps, w.frac_bits, 512)
+    S, T, n = w.streams, w.chunk, w.n
+    r = oracle.Replay(512, 512, 4, 4)
+    cnt = S * T
+    r.add(np.full(cnt, 7.0, F32), np.zeros((cnt, 4), np.uint8), np.zeros((cnt, 4), np.uint8),
+          ret.reshape(-1), gacc.reshape(-1))
+    q_taken = np.take_along_axis(d["q_online"][:, :T], d["action"][:, :T, None].astype(np.int64), 2)[..., 0]
+    rc, p2 = r.update_from_q(np.arange(cnt, dtype=np.uint64), q_taken.reshape(-1),
+                             d["q_online"][:, n:].reshape(cnt, -1), d["q_target"][:, n:].reshape(cnt, -1))
+    assert rc == 0
+    assert np.array_equal(p2.view(np.uint32), prio.reshape(-1).view(np.uint32))
+    assert np.array_equal(r.leaves()[:cnt], fx.reshape(-1))
