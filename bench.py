@@ -144,6 +144,38 @@ class GpuJob:
         assert rc == 0, rc
         assert self.pipe.join() == 0
 
+    def prefetch16_us_per_batch(self, batches, with_actors):
+        """The paper's prefetch depth as the unit of work: 16 batches of 512 drawn per call from one state of
+        the memory, gathered and written back together (two launches per 16 batches).  With the actors' side:
+        the same insert rate (one add round per 25 batches) and eviction every 100 batches."""
+        torch, w = self.torch, self.w
+        nb = 16
+        calls = batches // nb
+        pipe = self.apex.Pipeline(self.rep, 2, nb, w.k)
+        rnd = self.rnd[:calls * nb].reshape(calls, nb * w.k)
+        td = self.td[:calls * nb].reshape(calls, nb * w.k)
+
+        def go(n_calls):
+            assert pipe.fork() == 0
+            for c in range(n_calls):
+                done, due = c * nb // ADD_EVERY, (c + 1) * nb // ADD_EVERY
+                if with_actors and due > done:
+                    t = self.rounds[done % self.n_pool]
+                    prio, ret, gacc, _ = t["out"]
+                    assert pipe.add_begin(t["q_online"], t["q_target"], t["action"], t["reward"], t["discount"], w.n,
+                                          self.obs_stage, t["act"], prio, ret, gacc) == 0
+                assert pipe.steps(1, w.beta, rnd[c], td[c])[0] == 0
+                if with_actors and due > done:
+                    evict = (c + 1) * nb // EVICT_EVERY > c * nb // EVICT_EVERY
+                    assert pipe.add_end(evict)[0] == 0
+            if with_actors:                      # leave the memory at its capacity
+                assert self.rep.evict(stream=torch.cuda.current_stream())[0] == 0
+            assert pipe.join() == 0
+        go(min(calls, 8))
+        dt, _ = self.timed(lambda: go(calls))
+        pipe.close()
+        return dt / (calls * nb) * 1e6
+
     def run_pipelined(self, first, count):
         assert self.pipe.fork() == 0
         self.issue_windows(first, count)
@@ -322,6 +354,10 @@ def main():
     log("pipeline, two streams: %.2f us/step (host enqueue %.2f us/step)" % (dt_pipe / K * 1e6, host_pipe / K * 1e6))
     dt_pipe_learner, _ = job.timed(lambda: job.run_pipelined_learner_only(W + K, K))
     log("pipeline, learner steps only: %.2f us/step" % (dt_pipe_learner / K * 1e6))
+    us16 = job.prefetch16_us_per_batch(K, with_actors=False)
+    us16_full = job.prefetch16_us_per_batch(K, with_actors=True)
+    log("pipeline, 16 batches of 512 per call: %.2f us per batch learner only, %.2f with adds and eviction"
+        % (us16, us16_full))
     mode, dt = "apex_pipeline: two streams, eager launches", dt_pipe
     # (3) one cycle of the same pipeline captured as a HIP graph and replayed
     job.capture_cycle(W)
@@ -367,7 +403,9 @@ def main():
         "nstep_priorities_per_s": w.add_count / (ops["nstep_priorities_18000"] * 1e-6),
         "ops_us": ops,
         "variants_us_per_step": {"one_stream": dt_serial / K * 1e6, "one_stream_learner_only": dt_learner / K * 1e6,
-                                 "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6},
+                                 "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6,
+                                 "pipeline_16_batches_per_call_learner_only": us16,
+                                 "pipeline_16_batches_per_call": us16_full},
         "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel<u32x4,2,weights,update> (frame-stack gather "
                                                "of one batch, distinct rows every launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
