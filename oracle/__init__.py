@@ -197,3 +197,114 @@ class Replay:
         e = _u64(0)
         rc = lib().oracle_replay_evict(self.h, C.byref(e))
         return rc, int(e.value)
+
+
+class PrioritizedEvictionReplay:
+    """Replay memory whose eviction is proportional prioritized sampling with its own exponent."""
+
+    def __init__(self, capacity, max_slots, obs_bytes, act_bytes, alpha=0.6, alpha_evict=-0.4, eps=1e-6, frac_bits=24,
+                 payload=True):
+        L = lib()
+        if not hasattr(L, "_pe_ready"):
+            L.oracle_pe_create.restype = _vp
+            L.oracle_pe_create.argtypes = [_u64, _u64, _u32, _u32, _f32, _f32, _f32, _u32, C.c_int]
+            L.oracle_pe_destroy.restype = None
+            L.oracle_pe_destroy.argtypes = [_vp]
+            L.oracle_pe_add.restype = C.c_int
+            L.oracle_pe_add.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
+            L.oracle_pe_sample.restype = C.c_int
+            L.oracle_pe_sample.argtypes = [_vp, _u32, _u32, _f32] + [_vp] * 9
+            L.oracle_pe_update_priorities.restype = C.c_int
+            L.oracle_pe_update_priorities.argtypes = [_vp, _u64, _vp, _vp]
+            L.oracle_pe_evict.restype = C.c_int
+            L.oracle_pe_evict.argtypes = [_vp, _u32, _vp, C.POINTER(_u64)]
+            for name in ("size", "root", "root_evict", "inserted", "evicted", "free_head", "free_tail", "n_stale",
+                         "n_clamped", "tree_leaves"):
+                f = getattr(L, "oracle_pe_" + name)
+                f.restype, f.argtypes = _u64, [_vp]
+            L.oracle_pe_leaves.restype = None
+            L.oracle_pe_leaves.argtypes = [_vp, C.c_int, _vp]
+            L.oracle_pe_nodes.restype = None
+            L.oracle_pe_nodes.argtypes = [_vp, C.c_int, _vp]
+            L.oracle_pe_gen.restype = None
+            L.oracle_pe_gen.argtypes = [_vp, _vp]
+            L.oracle_pe_free_ring.restype = None
+            L.oracle_pe_free_ring.argtypes = [_vp, _vp]
+            L._pe_ready = True
+        self.h = L.oracle_pe_create(capacity, max_slots, obs_bytes, act_bytes, alpha, alpha_evict, eps, frac_bits,
+                                    int(payload))
+        if not self.h:
+            raise ValueError("oracle_pe_create rejected the configuration")
+        self.capacity, self.max_slots, self.obs_bytes, self.act_bytes = capacity, max_slots, obs_bytes, act_bytes
+        self.has_payload = payload
+
+    def close(self):
+        if self.h:
+            lib().oracle_pe_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def _get(self, name):
+        return int(getattr(lib(), "oracle_pe_" + name)(self.h))
+
+    size = property(lambda s: s._get("size"))
+    root = property(lambda s: s._get("root"))
+    root_evict = property(lambda s: s._get("root_evict"))
+    inserted = property(lambda s: s._get("inserted"))
+    evicted = property(lambda s: s._get("evicted"))
+    free_head = property(lambda s: s._get("free_head"))
+    free_tail = property(lambda s: s._get("free_tail"))
+    n_stale = property(lambda s: s._get("n_stale"))
+    n_clamped = property(lambda s: s._get("n_clamped"))
+
+    def leaves(self, evict_tree=False):
+        out = np.empty(self.max_slots, np.uint64)
+        lib().oracle_pe_leaves(self.h, int(evict_tree), _p(out))
+        return out
+
+    def nodes(self, evict_tree=False):
+        out = np.empty(2 * self._get("tree_leaves"), np.uint64)
+        lib().oracle_pe_nodes(self.h, int(evict_tree), _p(out))
+        return out
+
+    def gen(self):
+        out = np.empty(self.max_slots, np.uint32)
+        lib().oracle_pe_gen(self.h, _p(out))
+        return out
+
+    def free_ring(self):
+        out = np.empty(self.max_slots, np.uint32)
+        lib().oracle_pe_free_ring(self.h, _p(out))
+        return out
+
+    def add(self, prio, obs=None, act=None, ret=None, gacc=None):
+        prio = _arr(prio, np.float32)
+        obs, act = _arr(obs, np.uint8), _arr(act, np.uint8)
+        ret, gacc = _arr(ret, np.float32), _arr(gacc, np.float32)
+        keys = np.zeros(prio.shape[0], np.uint64)
+        rc = lib().oracle_pe_add(self.h, prio.shape[0], _p(obs), _p(act), _p(ret), _p(gacc), _p(prio), _p(keys))
+        return rc, keys
+
+    def sample(self, num_batches, k, beta, rnd, payload=True):
+        rnd = _arr(rnd, np.uint64)
+        n = num_batches * k
+        out = dict(key=np.zeros(n, np.uint64), slot=np.zeros(n, np.uint32), weight=np.zeros(n, np.float32),
+                   mass=np.zeros(n, np.uint64))
+        if payload and self.has_payload:
+            out.update(obs=np.zeros((n, self.obs_bytes), np.uint8), act=np.zeros((n, self.act_bytes), np.uint8),
+                       ret=np.zeros(n, np.float32), gacc=np.zeros(n, np.float32))
+        rc = lib().oracle_pe_sample(self.h, num_batches, k, beta, _p(rnd), _p(out["key"]), _p(out["slot"]),
+                                    _p(out["weight"]), _p(out["mass"]), _p(out.get("obs")), _p(out.get("act")),
+                                    _p(out.get("ret")), _p(out.get("gacc")))
+        return rc, out
+
+    def update_priorities(self, key, prio):
+        key, prio = _arr(key, np.uint64), _arr(prio, np.float32)
+        return lib().oracle_pe_update_priorities(self.h, key.shape[0], _p(key), _p(prio))
+
+    def evict(self, rounds, rnd):
+        rnd = _arr(rnd, np.uint64)
+        e = _u64(0)
+        rc = lib().oracle_pe_evict(self.h, rounds, _p(rnd), C.byref(e))
+        return rc, int(e.value)

@@ -447,3 +447,228 @@ void oracle_replay_leaves(const oracle_replay *r, uint64_t first, uint64_t count
 {
   memcpy(out, r->node + r->P2 + first, count * sizeof(uint64_t));
 }
+
+/* ------------------------------------------------------------------------- */
+/* the replay memory with prioritized eviction                                 */
+/* ------------------------------------------------------------------------- */
+
+/*
+ * Appendix "Continuous Control: Additional Details": to hold the memory at its capacity,
+ * transitions are periodically evicted by proportional prioritized sampling with its own
+ * exponent (alpha_evict = -0.4: transitions with small TD error go first), instead of oldest
+ * first.  Sampling for the learner is unchanged.
+ *
+ * Readings (the paper gives the rule in one sentence):
+ *  - a second sum tree holds the eviction masses Q(p; alpha_evict) of the same transitions;
+ *  - slots freed by an eviction are re-used by later adds in the order in which they were freed
+ *    (a ring of free slots, initially 0, 1, 2, ...), so a key can no longer be the insertion
+ *    count: key = (generation of the slot << 32) | slot, the generation counting the slot's
+ *    tenants; a key is valid while its generation is the slot's and the slot is occupied;
+ *  - to evict e = size - capacity transitions without replacement: in each round draw as many
+ *    stratified points as are still to go on the eviction tree as it stands at the start of the
+ *    round (same stratum rule as for sampling); a transition drawn more than once counts once
+ *    (such repeats are neighbours, the points being ordered); remove the distinct ones in the
+ *    order of their points; repeat with what is left, for at most `rounds` rounds.
+ */
+typedef struct oracle_pe {
+  uint64_t capacity, max_slots;
+  uint32_t obs_bytes, act_bytes, frac_bits;
+  float alpha, alpha_evict, eps;
+  uint64_t qmax, P2;
+  uint64_t *ts, *te;       /* sampling tree, eviction tree: [2*P2] each */
+  uint32_t *gen;           /* [P] tenants seen by each slot */
+  uint32_t *free_ring;     /* [P] */
+  uint64_t free_head, free_tail, inserted, evicted;
+  int payload;
+  uint8_t *obs, *act;
+  float *ret, *gacc;
+  uint64_t n_stale, n_clamped;
+} oracle_pe;
+
+static void tree_set(uint64_t *node, uint64_t P2, uint64_t slot, uint64_t v)
+{
+  uint64_t j = P2 + slot;
+  node[j] = v;
+  for (j >>= 1; j >= 1; j >>= 1) node[j] = node[2 * j] + node[2 * j + 1];
+}
+
+static uint64_t tree_find(const uint64_t *node, uint64_t P2, uint64_t x)
+{
+  uint64_t j = 1;
+  while (j < P2) {
+    uint64_t left = node[2 * j];
+    if (x < left) j = 2 * j;
+    else { x -= left; j = 2 * j + 1; }
+  }
+  return j - P2;
+}
+
+void oracle_pe_destroy(oracle_pe *r)
+{
+  if (!r) return;
+  free(r->ts); free(r->te); free(r->gen); free(r->free_ring);
+  free(r->obs); free(r->act); free(r->ret); free(r->gacc); free(r);
+}
+
+oracle_pe *oracle_pe_create(uint64_t capacity, uint64_t max_slots, uint32_t obs_bytes, uint32_t act_bytes, float alpha,
+                            float alpha_evict, float eps, uint32_t frac_bits, int payload)
+{
+  if (capacity == 0 || max_slots < capacity || max_slots > ((uint64_t)1 << 31) || frac_bits > 32 ||
+      !(alpha >= -1.0f && alpha <= 1.0f) || !(alpha_evict >= -1.0f && alpha_evict <= 1.0f) || !(eps >= 0.0f))
+    return NULL;
+  oracle_pe *r = (oracle_pe *)calloc(1, sizeof *r);
+  if (!r) return NULL;
+  r->capacity = capacity; r->max_slots = max_slots;
+  r->obs_bytes = obs_bytes; r->act_bytes = act_bytes; r->frac_bits = frac_bits;
+  r->alpha = alpha; r->alpha_evict = alpha_evict; r->eps = eps;
+  r->qmax = oracle_qmax(max_slots);
+  r->P2 = 1; while (r->P2 < max_slots) r->P2 <<= 1;
+  r->ts = (uint64_t *)calloc(2 * r->P2, 8);
+  r->te = (uint64_t *)calloc(2 * r->P2, 8);
+  r->gen = (uint32_t *)calloc(max_slots, 4);
+  r->free_ring = (uint32_t *)calloc(max_slots, 4);
+  r->payload = payload;
+  if (payload) {
+    r->obs = (uint8_t *)calloc(max_slots, obs_bytes ? obs_bytes : 1);
+    r->act = (uint8_t *)calloc(max_slots, act_bytes ? act_bytes : 1);
+    r->ret = (float *)calloc(max_slots, 4);
+    r->gacc = (float *)calloc(max_slots, 4);
+  }
+  if (!r->ts || !r->te || !r->gen || !r->free_ring || (payload && (!r->obs || !r->act || !r->ret || !r->gacc))) {
+    oracle_pe_destroy(r);
+    return NULL;
+  }
+  for (uint64_t i = 0; i < max_slots; ++i) r->free_ring[i] = (uint32_t)i;
+  r->free_head = 0;
+  r->free_tail = max_slots;
+  return r;
+}
+
+static uint64_t pe_size(const oracle_pe *r) { return r->max_slots - (r->free_tail - r->free_head); }
+
+static void pe_set_priority(oracle_pe *r, uint64_t slot, float p)
+{
+  int c1, c2;
+  tree_set(r->ts, r->P2, slot, oracle_quantise(p, r->alpha, r->eps, r->frac_bits, r->qmax, &c1));
+  tree_set(r->te, r->P2, slot, oracle_quantise(p, r->alpha_evict, r->eps, r->frac_bits, r->qmax, &c2));
+  r->n_clamped += (uint64_t)(c1 + c2);
+}
+
+int oracle_pe_add(oracle_pe *r, uint64_t count, const uint8_t *obs, const uint8_t *act, const float *ret,
+                  const float *gacc, const float *prio, uint64_t *key_out)
+{
+  if (!r || (count && !prio)) return ORACLE_ERR_INVALID_ARG;
+  if (pe_size(r) + count > r->max_slots) return ORACLE_ERR_FULL;
+  for (uint64_t i = 0; i < count; ++i) {
+    const uint64_t slot = r->free_ring[(r->free_head + i) % r->max_slots];
+    r->gen[slot] += 1;
+    if (r->payload) {
+      if (obs) memcpy(r->obs + slot * r->obs_bytes, obs + i * r->obs_bytes, r->obs_bytes);
+      if (act) memcpy(r->act + slot * r->act_bytes, act + i * r->act_bytes, r->act_bytes);
+      if (ret) r->ret[slot] = ret[i];
+      if (gacc) r->gacc[slot] = gacc[i];
+    }
+    pe_set_priority(r, slot, prio[i]);
+    if (key_out) key_out[i] = ((uint64_t)r->gen[slot] << 32) | slot;
+  }
+  r->free_head += count;
+  r->inserted += count;
+  return ORACLE_OK;
+}
+
+int oracle_pe_sample(oracle_pe *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                     uint64_t *key_out, uint32_t *slot_out, float *weight_out, uint64_t *mass_out, uint8_t *obs_out,
+                     uint8_t *act_out, float *ret_out, float *gacc_out)
+{
+  if (!r || !k || !num_batches || !rnd || !slot_out) return ORACLE_ERR_INVALID_ARG;
+  const uint64_t size = pe_size(r);
+  if (size == 0) return ORACLE_ERR_EMPTY;
+  const uint64_t total = r->ts[1], w = total / k;
+  double *wt = (double *)malloc(sizeof(double) * k);
+  if (!wt) return ORACLE_ERR_INVALID_ARG;
+  for (uint32_t b = 0; b < num_batches; ++b) {
+    double wmax = 0.0;
+    for (uint32_t j = 0; j < k; ++j) {
+      const size_t o = (size_t)b * k + j;
+      const uint64_t x = (uint64_t)j * w + mulhi64(rnd[o], w);
+      const uint64_t slot = tree_find(r->ts, r->P2, x);
+      const uint64_t mass = r->ts[r->P2 + slot];
+      slot_out[o] = (uint32_t)slot;
+      if (key_out) key_out[o] = ((uint64_t)r->gen[slot] << 32) | slot;
+      if (mass_out) mass_out[o] = mass;
+      wt[j] = pow((double)size * ((double)mass / (double)total), -(double)beta);
+      if (wt[j] > wmax) wmax = wt[j];
+      if (r->payload) {
+        if (obs_out) memcpy(obs_out + o * r->obs_bytes, r->obs + slot * r->obs_bytes, r->obs_bytes);
+        if (act_out) memcpy(act_out + o * r->act_bytes, r->act + slot * r->act_bytes, r->act_bytes);
+        if (ret_out) ret_out[o] = r->ret[slot];
+        if (gacc_out) gacc_out[o] = r->gacc[slot];
+      }
+    }
+    if (weight_out)
+      for (uint32_t j = 0; j < k; ++j) weight_out[(size_t)b * k + j] = (float)(wt[j] / wmax);
+  }
+  free(wt);
+  return ORACLE_OK;
+}
+
+int oracle_pe_update_priorities(oracle_pe *r, uint64_t m, const uint64_t *key, const float *prio)
+{
+  if (!r || (m && (!key || !prio))) return ORACLE_ERR_INVALID_ARG;
+  for (uint64_t i = 0; i < m; ++i) {
+    const uint64_t slot = key[i] & 0xffffffffu, g = key[i] >> 32;
+    if (slot >= r->max_slots || r->gen[slot] != g || r->ts[r->P2 + slot] == 0) { r->n_stale++; continue; }
+    pe_set_priority(r, slot, prio[i]);
+  }
+  return ORACLE_OK;
+}
+
+/* rnd: [rounds, e] uniforms, e = size - capacity at the time of the call (row stride e). */
+int oracle_pe_evict(oracle_pe *r, uint32_t rounds, const uint64_t *rnd, uint64_t *evicted_out)
+{
+  if (!r) return ORACLE_ERR_INVALID_ARG;
+  const uint64_t size = pe_size(r);
+  const uint64_t e = size > r->capacity ? size - r->capacity : 0;
+  uint64_t remaining = e;
+  if (e && !rnd) return ORACLE_ERR_INVALID_ARG;
+  uint64_t *cand = (uint64_t *)malloc(sizeof(uint64_t) * (e ? e : 1));
+  if (!cand) return ORACLE_ERR_INVALID_ARG;
+  for (uint32_t rd = 0; rd < rounds && remaining > 0; ++rd) {
+    const uint64_t k = remaining, total = r->te[1], w = total / k;
+    for (uint64_t j = 0; j < k; ++j)
+      cand[j] = tree_find(r->te, r->P2, j * w + mulhi64(rnd[(uint64_t)rd * e + j], w));
+    for (uint64_t j = 0; j < k; ++j) {
+      if (j > 0 && cand[j] == cand[j - 1]) continue;      /* drawn again: counts once */
+      tree_set(r->ts, r->P2, cand[j], 0);
+      tree_set(r->te, r->P2, cand[j], 0);
+      r->free_ring[r->free_tail % r->max_slots] = (uint32_t)cand[j];
+      r->free_tail++;
+      r->evicted++;
+      remaining--;
+    }
+  }
+  free(cand);
+  if (evicted_out) *evicted_out = e - remaining;
+  return ORACLE_OK;
+}
+
+uint64_t oracle_pe_size(const oracle_pe *r) { return pe_size(r); }
+uint64_t oracle_pe_root(const oracle_pe *r) { return r->ts[1]; }
+uint64_t oracle_pe_root_evict(const oracle_pe *r) { return r->te[1]; }
+uint64_t oracle_pe_inserted(const oracle_pe *r) { return r->inserted; }
+uint64_t oracle_pe_evicted(const oracle_pe *r) { return r->evicted; }
+uint64_t oracle_pe_free_head(const oracle_pe *r) { return r->free_head; }
+uint64_t oracle_pe_free_tail(const oracle_pe *r) { return r->free_tail; }
+uint64_t oracle_pe_n_stale(const oracle_pe *r) { return r->n_stale; }
+uint64_t oracle_pe_n_clamped(const oracle_pe *r) { return r->n_clamped; }
+void oracle_pe_leaves(const oracle_pe *r, int which, uint64_t *out)
+{
+  memcpy(out, (which ? r->te : r->ts) + r->P2, r->max_slots * sizeof(uint64_t));
+}
+void oracle_pe_nodes(const oracle_pe *r, int which, uint64_t *out)
+{
+  memcpy(out, which ? r->te : r->ts, 2 * r->P2 * sizeof(uint64_t));
+}
+uint64_t oracle_pe_tree_leaves(const oracle_pe *r) { return r->P2; }
+void oracle_pe_gen(const oracle_pe *r, uint32_t *out) { memcpy(out, r->gen, r->max_slots * 4); }
+void oracle_pe_free_ring(const oracle_pe *r, uint32_t *out) { memcpy(out, r->free_ring, r->max_slots * 4); }
