@@ -355,6 +355,71 @@ int apex_pipeline_capture_begin(apex_pipeline_t *p);
 int apex_pipeline_capture_end(apex_pipeline_t *p);
 int apex_pipeline_replay(apex_pipeline_t *p, uint32_t times);
 
+/* ------------------------------------------------------------------------------------------
+ * Replay memory with prioritized eviction (Appendix "Continuous Control: Additional Details": to
+ * hold the capacity, transitions are periodically evicted by proportional prioritized sampling
+ * with exponent alpha_evict = -0.4, instead of oldest first).  A separate object with the same
+ * verbs.  What differs from apex_replay_t:
+ *   - a second sum tree holds the eviction masses Q(p; alpha_evict) of the same transitions;
+ *   - slots freed by an eviction are re-used by later adds in the order in which they were freed,
+ *     so a key is (generation of the slot << 32) | slot, the generation counting the slot's
+ *     tenants; a key is valid while its generation is the slot's and the slot is occupied.  Keys
+ *     are handed out by apex_pe_sample only;
+ *   - apex_pe_evict removes e = size - capacity transitions without replacement in rounds: each
+ *     round draws as many stratified points as are still to go on the eviction tree as it stands
+ *     (point j of k: j*w + floor(rnd*w / 2^64), w = floor(total / k)), counts a transition drawn
+ *     more than once once, and removes the distinct ones in the order of their points.  rnd is a
+ *     device array [rounds, e] of 64-bit uniforms (row stride e).  The call synchronises
+ *     hip_stream and reports how many were removed (fewer than e only if `rounds` ran out).
+ * Everything else (device pointers, streams, status codes, sampling rule, weights) is as above.
+ * ---------------------------------------------------------------------------------------- */
+#define APEX_PE_MAX_EVICT_PER_CALL 1048576u
+
+typedef struct apex_pe_replay apex_pe_replay_t;
+
+typedef struct apex_pe_config {
+  uint64_t capacity;  /* apex_pe_evict trims to it (Appendix: 1,000,000)                          */
+  uint64_t max_slots; /* physical slots P, capacity <= P <= 2^31                                  */
+  uint32_t obs_bytes, act_bytes;
+  float alpha;        /* sampling exponent, in [-1, 1] (Appendix: 0.6)                            */
+  float alpha_evict;  /* eviction exponent, in [-1, 1] (Appendix: -0.4)                           */
+  float eps;
+  uint32_t frac_bits;
+} apex_pe_config_t;
+
+typedef struct apex_pe_stats {
+  uint64_t size, inserted, evicted;
+  uint64_t root, root_evict; /* sums of the sampling masses and of the eviction masses            */
+  uint64_t free_head, free_tail;
+  uint64_t n_stale_dropped, n_clamped;
+} apex_pe_stats_t;
+
+typedef struct apex_pe_layout {
+  uint64_t obs_offset, act_offset, ret_offset, gacc_offset; /* in d_storage, as apex_replay_layout_t */
+  uint32_t tree_levels, tree_fanout;
+  uint64_t level_offset[APEX_TREE_MAX_LEVELS]; /* sampling tree, uint64 units inside d_tree        */
+  uint64_t level_size[APEX_TREE_MAX_LEVELS];
+  uint64_t evict_tree_offset;                  /* the eviction tree: same offsets, shifted by this  */
+  uint64_t gen_offset, free_ring_offset;       /* byte offsets in d_scratch: u32 [P] each           */
+} apex_pe_layout_t;
+
+int apex_pe_workspace_bytes(const apex_pe_config_t *cfg, size_t *storage_bytes, size_t *tree_bytes,
+                            size_t *scratch_bytes);
+int apex_pe_create(const apex_pe_config_t *cfg, void *d_storage, void *d_tree, void *d_scratch,
+                   apex_pe_replay_t **out);
+int apex_pe_destroy(apex_pe_replay_t *r);
+int apex_pe_layout(const apex_pe_replay_t *r, apex_pe_layout_t *out /*host*/);
+int apex_pe_add(apex_pe_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                const float *gacc, const float *prio, void *hip_stream);
+int apex_pe_sample(apex_pe_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                   uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
+                   float *ret_out, float *gacc_out, void *hip_stream);
+int apex_pe_update_priorities(apex_pe_replay_t *r, uint64_t m, const uint64_t *key, const float *prio,
+                              void *hip_stream);
+int apex_pe_evict(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uint64_t *evicted_out /*host*/,
+                  void *hip_stream);
+int apex_pe_stats(apex_pe_replay_t *r, apex_pe_stats_t *out /*host*/, void *hip_stream);
+
 /* hipError_t of the last failed HIP call of the calling thread (0 if none). */
 int apex_last_hip_error(void);
 

@@ -26,7 +26,9 @@ EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_des
            "apex_replay_update_priorities", "apex_replay_update_from_q", "apex_replay_evict", "apex_replay_resync", "apex_replay_stats",
            "apex_last_hip_error", "apex_pipeline_create", "apex_pipeline_destroy", "apex_pipeline_fork",
            "apex_pipeline_join", "apex_pipeline_steps", "apex_pipeline_add_begin", "apex_pipeline_add_end",
-           "apex_pipeline_capture_begin", "apex_pipeline_capture_end", "apex_pipeline_replay"]
+           "apex_pipeline_capture_begin", "apex_pipeline_capture_end", "apex_pipeline_replay",
+           "apex_pe_workspace_bytes", "apex_pe_create", "apex_pe_destroy", "apex_pe_layout", "apex_pe_add",
+           "apex_pe_sample", "apex_pe_update_priorities", "apex_pe_evict", "apex_pe_stats"]
 
 
 class Config(C.Structure):
@@ -48,6 +50,26 @@ class Layout(C.Structure):
 class BatchBuffers(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("key", "slot", "mass", "weight", "obs", "act", "ret", "gacc")]
 
+
+class PeConfig(C.Structure):
+    _fields_ = [("capacity", C.c_uint64), ("max_slots", C.c_uint64), ("obs_bytes", C.c_uint32),
+                ("act_bytes", C.c_uint32), ("alpha", C.c_float), ("alpha_evict", C.c_float), ("eps", C.c_float),
+                ("frac_bits", C.c_uint32)]
+
+
+class PeStats(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in ("size", "inserted", "evicted", "root", "root_evict", "free_head",
+                                          "free_tail", "n_stale_dropped", "n_clamped")]
+
+
+class PeLayout(C.Structure):
+    _fields_ = [("obs_offset", C.c_uint64), ("act_offset", C.c_uint64), ("ret_offset", C.c_uint64),
+                ("gacc_offset", C.c_uint64), ("tree_levels", C.c_uint32), ("tree_fanout", C.c_uint32),
+                ("level_offset", C.c_uint64 * TREE_MAX_LEVELS), ("level_size", C.c_uint64 * TREE_MAX_LEVELS),
+                ("evict_tree_offset", C.c_uint64), ("gen_offset", C.c_uint64), ("free_ring_offset", C.c_uint64)]
+
+
+PE_MAX_EVICT_PER_CALL = 1 << 20
 
 if not os.path.exists(LIB_PATH):
     raise ImportError("%s is missing: build it first (python paper_1803_00933_amd/build.py or "
@@ -86,6 +108,15 @@ lib.apex_pipeline_add_end.argtypes = [_vp, C.c_int, C.POINTER(_u64), C.POINTER(_
 lib.apex_pipeline_capture_begin.argtypes = [_vp]
 lib.apex_pipeline_capture_end.argtypes = [_vp]
 lib.apex_pipeline_replay.argtypes = [_vp, _u32]
+lib.apex_pe_workspace_bytes.argtypes = [C.POINTER(PeConfig)] + [C.POINTER(C.c_size_t)] * 3
+lib.apex_pe_create.argtypes = [C.POINTER(PeConfig), _vp, _vp, _vp, C.POINTER(_vp)]
+lib.apex_pe_destroy.argtypes = [_vp]
+lib.apex_pe_layout.argtypes = [_vp, C.POINTER(PeLayout)]
+lib.apex_pe_add.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.apex_pe_sample.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.apex_pe_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
+lib.apex_pe_evict.argtypes = [_vp, _u32, _vp, C.POINTER(_u64), _vp]
+lib.apex_pe_stats.argtypes = [_vp, C.POINTER(PeStats), _vp]
 for _name in EXPORTS:
     getattr(lib, _name).restype = C.c_int
 
@@ -321,3 +352,88 @@ class Pipeline:
         first, ev = _u64(0), _u64(0)
         rc = lib.apex_pipeline_add_end(self.h, int(evict), C.byref(first), C.byref(ev))
         return rc, int(first.value), int(ev.value)
+
+
+class PeReplay:
+    """Binding of apex_pe_*: the memory with prioritized eviction.  Owns its three device regions."""
+
+    def __init__(self, capacity, max_slots, obs_bytes, act_bytes, alpha=0.6, alpha_evict=-0.4, eps=1e-6, frac_bits=24,
+                 device="cuda:0"):
+        self.cfg = PeConfig(capacity, max_slots, obs_bytes, act_bytes, alpha, alpha_evict, eps, frac_bits)
+        a, b, c = C.c_size_t(0), C.c_size_t(0), C.c_size_t(0)
+        rc = lib.apex_pe_workspace_bytes(C.byref(self.cfg), C.byref(a), C.byref(b), C.byref(c))
+        if rc != OK:
+            raise ValueError("configuration rejected: %s" % STATUS_NAMES.get(rc, rc))
+        self.device = torch.device(device)
+        self.storage = torch.empty(a.value, dtype=torch.uint8, device=self.device)
+        self.tree = torch.empty(b.value // 8, dtype=torch.int64, device=self.device)
+        self.scratch = torch.empty(c.value, dtype=torch.uint8, device=self.device)
+        torch.cuda.synchronize(self.device)
+        h = _vp(None)
+        rc = lib.apex_pe_create(C.byref(self.cfg), self.storage.data_ptr(), self.tree.data_ptr(),
+                                self.scratch.data_ptr(), C.byref(h))
+        if rc != OK:
+            raise RuntimeError("apex_pe_create: %s" % STATUS_NAMES.get(rc, rc))
+        self.h = h
+        self.capacity, self.max_slots, self.obs_bytes, self.act_bytes = capacity, max_slots, obs_bytes, act_bytes
+        self.layout = PeLayout()
+        lib.apex_pe_layout(self.h, C.byref(self.layout))
+
+    def close(self):
+        if getattr(self, "h", None) and lib is not None:
+            lib.apex_pe_destroy(self.h)
+            self.h = None
+
+    __del__ = close
+
+    def level_view(self, l, evict_tree=False):
+        o = self.layout.level_offset[l] + (self.layout.evict_tree_offset if evict_tree else 0)
+        return self.tree[o:o + self.layout.level_size[l]]
+
+    def gen_view(self):
+        o = self.layout.gen_offset
+        return self.scratch[o:o + 4 * self.max_slots].view(torch.int32)
+
+    def free_ring_view(self):
+        o = self.layout.free_ring_offset
+        return self.scratch[o:o + 4 * self.max_slots].view(torch.int32)
+
+    def obs_view(self):
+        o = self.layout.obs_offset
+        return self.storage[o:o + self.max_slots * self.obs_bytes].view(self.max_slots, self.obs_bytes)
+
+    def add(self, prio, obs=None, act=None, ret=None, gacc=None, stream=None):
+        return lib.apex_pe_add(self.h, prio.shape[0], _ptr(obs), _ptr(act), _ptr(ret), _ptr(gacc), _ptr(prio),
+                               _stream(stream))
+
+    def alloc_sample_outputs(self, num_batches, k):
+        n, dev = num_batches * k, self.device
+        return dict(key=torch.empty(n, dtype=torch.int64, device=dev), slot=torch.empty(n, dtype=torch.int32, device=dev),
+                    weight=torch.empty(n, dtype=torch.float32, device=dev),
+                    obs=torch.empty((n, self.obs_bytes), dtype=torch.uint8, device=dev),
+                    act=torch.empty((n, self.act_bytes), dtype=torch.uint8, device=dev),
+                    ret=torch.empty(n, dtype=torch.float32, device=dev),
+                    gacc=torch.empty(n, dtype=torch.float32, device=dev))
+
+    def sample(self, num_batches, k, beta, rnd, out=None, stream=None):
+        if out is None:
+            out = self.alloc_sample_outputs(num_batches, k)
+        rc = lib.apex_pe_sample(self.h, num_batches, k, beta, _ptr(rnd), _ptr(out.get("key")), _ptr(out["slot"]),
+                                _ptr(out.get("weight")), _ptr(out.get("obs")), _ptr(out.get("act")),
+                                _ptr(out.get("ret")), _ptr(out.get("gacc")), _stream(stream))
+        return rc, out
+
+    def update_priorities(self, key, prio, stream=None):
+        return lib.apex_pe_update_priorities(self.h, key.shape[0], _ptr(key), _ptr(prio), _stream(stream))
+
+    def evict(self, rounds, rnd, stream=None):
+        e = _u64(0)
+        rc = lib.apex_pe_evict(self.h, rounds, _ptr(rnd), C.byref(e), _stream(stream))
+        return rc, int(e.value)
+
+    def stats(self, stream=None):
+        st = PeStats()
+        rc = lib.apex_pe_stats(self.h, C.byref(st), _stream(stream))
+        if rc != OK:
+            raise RuntimeError("apex_pe_stats: %s" % STATUS_NAMES.get(rc, rc))
+        return {n: int(getattr(st, n)) for n, _ in PeStats._fields_}

@@ -327,6 +327,8 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
   a.tv = r->tv;
   a.st = r->state();
   a.k = k;
+  a.k_dev = nullptr;
+  a.gen = nullptr;
   a.rnd = rnd;
   a.key_out = key_out;
   a.slot_out = slot_out;
@@ -534,3 +536,4 @@ int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out, void *hip_stre
 }  // extern "C"
 
 #include "pipeline.inc.hpp"
+#include "evict_prio.inc.hpp"

@@ -1,0 +1,522 @@
+// apex_pe_*: a replay memory whose eviction is proportional prioritized sampling with its own
+// exponent (Appendix "Continuous Control: Additional Details": alpha_evict = -0.4) instead of oldest
+// first.  Included by apex_replay.hip (one translation unit).
+//
+// Two sum trees of the same shape over the same slots: sampling masses Q(p; alpha) and eviction
+// masses Q(p; alpha_evict).  Slots freed by evictions go into a ring of free slots and are re-used
+// by later adds in the order in which they were freed; a key is (generation of the slot << 32) |
+// slot.  Evicting e transitions without replacement takes rounds: draw as many stratified points
+// as are still to go on the eviction tree (the sampling kernel, pointed at that tree), drop
+// repeats (they are neighbours, the points being ordered), remove the rest in the order of their
+// points (a device-wide prefix sum gives each its place in the free ring), repeat.
+
+namespace apex {
+
+struct PeState {
+  DeviceState base;  // head = evicted so far, tail = inserted so far, and the two counters
+  uint64_t free_head, free_tail;   // the free ring holds slots free_ring[free_head .. free_tail) mod P
+  uint64_t remaining;              // evictions still to go in the current call
+  uint64_t round_total;            // evictions of the current round
+};
+
+struct PeView {
+  TreeView ts, te;  // sampling masses, eviction masses
+  uint32_t *gen;
+  uint32_t *free_ring;
+  QuantParams qs, qe;
+};
+
+__device__ __forceinline__ bool pe_key_valid(const PeView &v, uint64_t key, uint32_t *slot_out)
+{
+  const uint64_t slot = key & 0xffffffffu;
+  if (slot >= v.ts.P) return false;
+  *slot_out = (uint32_t)slot;
+  return v.gen[slot] == (uint32_t)(key >> 32) && v.ts.level[0][slot] != 0;
+}
+
+__global__ __launch_bounds__(256) void pe_add_kernel(PeView v, PeState *__restrict__ st, uint64_t count,
+                                                     const float *__restrict__ prio)
+{
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t nclamp = 0;
+  if (i < count) {
+    const uint32_t slot = v.free_ring[(st->free_head + i) % v.ts.P];
+    v.gen[slot] += 1;
+    bool c1, c2;
+    const float p = prio[i];
+    const uint64_t q1 = quantise_priority(p, v.qs, &c1), q2 = quantise_priority(p, v.qe, &c2);
+    v.ts.level[0][slot] = q1;  // a free slot weighs nothing in either tree
+    v.te.level[0][slot] = q2;
+    add_to_ancestors(v.ts, slot, q1);
+    add_to_ancestors(v.te, slot, q2);
+    nclamp = (uint32_t)c1 + (uint32_t)c2;
+  }
+  const uint64_t nc = wave_sum(nclamp);
+  if (nc && lane_id() == 0) atomic_add_u64(&st->base.n_clamped, nc);
+}
+
+__global__ void pe_after_add_kernel(PeState *st, uint64_t count)
+{
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    st->free_head += count;
+    st->base.tail += count;
+  }
+}
+
+__global__ __launch_bounds__(256) void pe_update_claim_kernel(PeView v, PeState *__restrict__ st, uint32_t m,
+                                                              const uint64_t *__restrict__ key,
+                                                              uint32_t *__restrict__ claim)
+{
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  bool stale = false;
+  if (i < m) {
+    uint32_t slot;
+    if (pe_key_valid(v, key[i], &slot))
+      __hip_atomic_fetch_max(claim + slot, i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else
+      stale = true;
+  }
+  const uint64_t ns = __popcll(__ballot(stale));
+  if (ns && lane_id() == 0) atomic_add_u64(&st->base.n_stale, ns);
+}
+
+__global__ __launch_bounds__(256) void pe_update_apply_kernel(PeView v, PeState *__restrict__ st, uint32_t m,
+                                                              const uint64_t *__restrict__ key,
+                                                              const float *__restrict__ prio,
+                                                              uint32_t *__restrict__ claim)
+{
+  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  uint32_t nclamp = 0;
+  if (i < m) {
+    uint32_t slot;
+    if (pe_key_valid(v, key[i], &slot)) {  // a winner only ever writes non-zero masses, so this cannot flip
+      bool c1, c2;
+      const float p = prio[i];
+      const uint64_t q1 = quantise_priority(p, v.qs, &c1), q2 = quantise_priority(p, v.qe, &c2);
+      nclamp = (uint32_t)c1 + (uint32_t)c2;
+      if (claim[slot] == i + 1) {
+        const uint64_t o1 = v.ts.level[0][slot], o2 = v.te.level[0][slot];
+        v.ts.level[0][slot] = q1;
+        v.te.level[0][slot] = q2;
+        add_to_ancestors(v.ts, slot, q1 - o1);
+        add_to_ancestors(v.te, slot, q2 - o2);
+        claim[slot] = 0;
+      }
+    }
+  }
+  const uint64_t nc = wave_sum(nclamp);
+  if (nc && lane_id() == 0) atomic_add_u64(&st->base.n_clamped, nc);
+}
+
+__global__ void pe_begin_evict_kernel(PeState *st, uint64_t e)
+{
+  if (threadIdx.x == 0 && blockIdx.x == 0) st->remaining = e;
+}
+
+constexpr uint32_t kPeScanThreads = 1024;
+
+// Which drawn candidates count (the first of each run of equal slots), and where each stands among
+// those of its workgroup; the workgroup's count goes to block_sums.
+__global__ __launch_bounds__(kPeScanThreads) void pe_flag_scan_kernel(const uint32_t *__restrict__ cand,
+                                                                      const PeState *__restrict__ st,
+                                                                      uint32_t *__restrict__ pos,
+                                                                      uint32_t *__restrict__ block_sums)
+{
+  __shared__ uint32_t wave_tot[kPeScanThreads / kWave];
+  const uint64_t rem = st->remaining;
+  const uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const bool acc = j < rem && (j == 0 || cand[j] != cand[j - 1]);
+  const uint64_t mask = __ballot(acc);
+  const int lane = lane_id();
+  const uint32_t wave = threadIdx.x / kWave;
+  const uint32_t in_wave = __popcll(mask & ((1ull << lane) - 1));
+  if (lane == 0) wave_tot[wave] = __popcll(mask);
+  __syncthreads();
+  uint32_t before = 0, total = 0;
+  for (uint32_t w = 0; w < kPeScanThreads / kWave; ++w) {
+    if (w < wave) before += wave_tot[w];
+    total += wave_tot[w];
+  }
+  if (j < rem) pos[j] = acc ? before + in_wave : 0xffffffffu;
+  if (threadIdx.x == 0) block_sums[blockIdx.x] = total;
+}
+
+// Exclusive prefix sum of at most kPeScanThreads workgroup counts, in place; the total of the round.
+__global__ __launch_bounds__(kPeScanThreads) void pe_scan_blocks_kernel(uint32_t *__restrict__ block_sums,
+                                                                        uint32_t nblocks, PeState *__restrict__ st)
+{
+  __shared__ uint32_t wave_tot[kPeScanThreads / kWave];
+  const uint32_t t = threadIdx.x;
+  const uint32_t v = t < nblocks ? block_sums[t] : 0;
+  uint32_t incl = v;
+  const int lane = lane_id();
+  for (int d = 1; d < kWave; d <<= 1) {
+    const uint32_t o = __shfl_up(incl, d, kWave);
+    if (lane >= d) incl += o;
+  }
+  if (lane == kWave - 1) wave_tot[t / kWave] = incl;
+  __syncthreads();
+  uint32_t before = 0, total = 0;
+  for (uint32_t w = 0; w < kPeScanThreads / kWave; ++w) {
+    if (w < t / kWave) before += wave_tot[w];
+    total += wave_tot[w];
+  }
+  if (t < nblocks) block_sums[t] = before + incl - v;
+  if (t == 0) st->round_total = total;
+}
+
+__global__ __launch_bounds__(kPeScanThreads) void pe_remove_kernel(PeView v, const PeState *__restrict__ st,
+                                                                   const uint32_t *__restrict__ cand,
+                                                                   const uint32_t *__restrict__ pos,
+                                                                   const uint32_t *__restrict__ block_offsets)
+{
+  const uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= st->remaining) return;
+  const uint32_t p = pos[j];
+  if (p == 0xffffffffu) return;
+  const uint32_t slot = cand[j];
+  const uint64_t o1 = v.ts.level[0][slot], o2 = v.te.level[0][slot];
+  v.ts.level[0][slot] = 0;
+  v.te.level[0][slot] = 0;
+  add_to_ancestors(v.ts, slot, 0 - o1);
+  add_to_ancestors(v.te, slot, 0 - o2);
+  v.free_ring[(st->free_tail + block_offsets[blockIdx.x] + p) % v.ts.P] = slot;
+}
+
+__global__ void pe_round_end_kernel(PeState *st)
+{
+  if (threadIdx.x == 0 && blockIdx.x == 0) {
+    st->free_tail += st->round_total;
+    st->base.head += st->round_total;
+    st->remaining -= st->round_total;
+  }
+}
+
+__global__ __launch_bounds__(256) void pe_init_free_ring_kernel(uint32_t *ring, uint64_t P, PeState *st)
+{
+  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < P) ring[i] = (uint32_t)i;
+  if (i == 0) {
+    st->free_head = 0;
+    st->free_tail = P;
+  }
+}
+
+}  // namespace apex
+
+namespace {
+
+struct PeGeometry {
+  uint64_t obs_off, act_off, ret_off, gacc_off, storage_bytes;
+  uint32_t nlev;
+  uint64_t level_off[kMaxLevels], level_size[kMaxLevels], tree_words;  // of one tree; the second follows it
+  uint64_t state_off, mass_off, cand_off, pos_off, sums_off, gen_off, ring_off, claim_off, scratch_bytes;
+};
+
+int pe_validate(const apex_pe_config_t *c)
+{
+  if (!c) return APEX_ERR_INVALID_ARG;
+  if (c->capacity == 0 || c->max_slots < c->capacity || c->max_slots > (1ull << 31)) return APEX_ERR_INVALID_ARG;
+  if (c->obs_bytes == 0 || c->act_bytes == 0 || c->frac_bits > 32) return APEX_ERR_INVALID_ARG;
+  if (!(c->alpha >= -1.0f && c->alpha <= 1.0f) || !(c->alpha_evict >= -1.0f && c->alpha_evict <= 1.0f))
+    return APEX_ERR_INVALID_ARG;
+  if (!(c->eps >= 0.0f) || !(c->eps < 1e30f)) return APEX_ERR_INVALID_ARG;
+  return APEX_OK;
+}
+
+int pe_geometry(const apex_pe_config_t *c, PeGeometry *g)
+{
+  apex_replay_config_t rc{};
+  rc.capacity = c->capacity;
+  rc.max_slots = c->max_slots;
+  rc.obs_bytes = c->obs_bytes;
+  rc.act_bytes = c->act_bytes;
+  Geometry base;
+  const int rv = geometry(&rc, &base);
+  if (rv != APEX_OK) return rv;
+  g->obs_off = base.obs_off;
+  g->act_off = base.act_off;
+  g->ret_off = base.ret_off;
+  g->gacc_off = base.gacc_off;
+  g->storage_bytes = base.storage_bytes;
+  g->nlev = base.nlev;
+  for (uint32_t l = 0; l < kMaxLevels; ++l) {
+    g->level_off[l] = base.level_off[l];
+    g->level_size[l] = base.level_size[l];
+  }
+  g->tree_words = base.tree_words;
+  const uint64_t P = c->max_slots;
+  g->state_off = 0;
+  g->mass_off = 256;
+  g->cand_off = g->mass_off + (uint64_t)APEX_PE_MAX_EVICT_PER_CALL * 8;  // also holds the masses of a sample call
+  g->pos_off = g->cand_off + (uint64_t)APEX_PE_MAX_EVICT_PER_CALL * 4;
+  g->sums_off = g->pos_off + (uint64_t)APEX_PE_MAX_EVICT_PER_CALL * 4;
+  g->gen_off = g->sums_off + round_up(kPeScanThreads * 4, 256);
+  g->ring_off = g->gen_off + round_up(P * 4, 256);
+  g->claim_off = g->ring_off + round_up(P * 4, 256);
+  g->scratch_bytes = g->claim_off + round_up(P * 4, 256);
+  return APEX_OK;
+}
+
+}  // namespace
+
+struct apex_pe_replay {
+  apex_pe_config_t cfg;
+  PeGeometry geo;
+  uint8_t *storage;
+  uint64_t *tree;
+  uint8_t *scratch;
+  uint64_t inserted, evicted;  // host mirror
+  PeView v;
+
+  PeState *state() const { return reinterpret_cast<PeState *>(scratch + geo.state_off); }
+  uint64_t *mass() const { return reinterpret_cast<uint64_t *>(scratch + geo.mass_off); }
+  uint32_t *cand() const { return reinterpret_cast<uint32_t *>(scratch + geo.cand_off); }
+  uint32_t *pos() const { return reinterpret_cast<uint32_t *>(scratch + geo.pos_off); }
+  uint32_t *sums() const { return reinterpret_cast<uint32_t *>(scratch + geo.sums_off); }
+  uint32_t *claim() const { return reinterpret_cast<uint32_t *>(scratch + geo.claim_off); }
+  uint8_t *obs() const { return storage + geo.obs_off; }
+  uint8_t *act() const { return storage + geo.act_off; }
+  float *ret() const { return reinterpret_cast<float *>(storage + geo.ret_off); }
+  float *gacc() const { return reinterpret_cast<float *>(storage + geo.gacc_off); }
+  uint64_t size() const { return inserted - evicted; }
+};
+
+extern "C" {
+
+int apex_pe_workspace_bytes(const apex_pe_config_t *cfg, size_t *storage_bytes, size_t *tree_bytes,
+                            size_t *scratch_bytes)
+{
+  int rc = pe_validate(cfg);
+  if (rc != APEX_OK) return rc;
+  PeGeometry g;
+  rc = pe_geometry(cfg, &g);
+  if (rc != APEX_OK) return rc;
+  if (storage_bytes) *storage_bytes = g.storage_bytes;
+  if (tree_bytes) *tree_bytes = 2 * g.tree_words * 8;
+  if (scratch_bytes) *scratch_bytes = g.scratch_bytes;
+  return APEX_OK;
+}
+
+int apex_pe_create(const apex_pe_config_t *cfg, void *d_storage, void *d_tree, void *d_scratch, apex_pe_replay_t **out)
+{
+  int rc = pe_validate(cfg);
+  if (rc != APEX_OK) return rc;
+  if (!d_storage || !d_tree || !d_scratch || !out) return APEX_ERR_INVALID_ARG;
+  if (((uintptr_t)d_storage | (uintptr_t)d_tree | (uintptr_t)d_scratch) & 255) return APEX_ERR_INVALID_ARG;
+  apex_pe_replay *r = new (std::nothrow) apex_pe_replay();
+  if (!r) return APEX_ERR_INVALID_ARG;
+  r->cfg = *cfg;
+  rc = pe_geometry(cfg, &r->geo);
+  if (rc != APEX_OK) {
+    delete r;
+    return rc;
+  }
+  r->storage = static_cast<uint8_t *>(d_storage);
+  r->tree = static_cast<uint64_t *>(d_tree);
+  r->scratch = static_cast<uint8_t *>(d_scratch);
+  r->inserted = r->evicted = 0;
+  const uint64_t qmax = qmax_for(cfg->max_slots);
+  r->v.qs = QuantParams{cfg->alpha, cfg->eps, cfg->frac_bits, qmax};
+  r->v.qe = QuantParams{cfg->alpha_evict, cfg->eps, cfg->frac_bits, qmax};
+  for (TreeView *tv : {&r->v.ts, &r->v.te}) {
+    tv->nlev = r->geo.nlev;
+    tv->n_top = (uint32_t)r->geo.level_size[r->geo.nlev - 1];
+    tv->P = cfg->max_slots;
+    uint64_t *base = r->tree + (tv == &r->v.te ? r->geo.tree_words : 0);
+    for (uint32_t l = 0; l < kMaxLevels; ++l) tv->level[l] = l < r->geo.nlev ? base + r->geo.level_off[l] : nullptr;
+  }
+  r->v.gen = reinterpret_cast<uint32_t *>(r->scratch + r->geo.gen_off);
+  r->v.free_ring = reinterpret_cast<uint32_t *>(r->scratch + r->geo.ring_off);
+  fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(r->tree, 2 * r->geo.tree_words);
+  fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(reinterpret_cast<uint64_t *>(r->scratch),
+                                                          r->geo.scratch_bytes / 8);
+  pe_init_free_ring_kernel<<<dim3(blocks_for(cfg->max_slots, 256)), dim3(256), 0, nullptr>>>(
+      r->v.free_ring, cfg->max_slots, r->state());
+  if (hip_failed(hipGetLastError()) || hip_failed(hipDeviceSynchronize())) {
+    delete r;
+    return APEX_ERR_HIP;
+  }
+  *out = r;
+  return APEX_OK;
+}
+
+int apex_pe_destroy(apex_pe_replay_t *r)
+{
+  if (!r) return APEX_ERR_INVALID_ARG;
+  delete r;
+  return APEX_OK;
+}
+
+int apex_pe_layout(const apex_pe_replay_t *r, apex_pe_layout_t *out)
+{
+  if (!r || !out) return APEX_ERR_INVALID_ARG;
+  out->obs_offset = r->geo.obs_off;
+  out->act_offset = r->geo.act_off;
+  out->ret_offset = r->geo.ret_off;
+  out->gacc_offset = r->geo.gacc_off;
+  out->tree_levels = r->geo.nlev;
+  out->tree_fanout = kFanout;
+  for (uint32_t l = 0; l < APEX_TREE_MAX_LEVELS; ++l) {
+    out->level_offset[l] = l < r->geo.nlev ? r->geo.level_off[l] : 0;
+    out->level_size[l] = l < r->geo.nlev ? r->geo.level_size[l] : 0;
+  }
+  out->evict_tree_offset = r->geo.tree_words;
+  out->gen_offset = r->geo.gen_off;
+  out->free_ring_offset = r->geo.ring_off;
+  return APEX_OK;
+}
+
+int apex_pe_add(apex_pe_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                const float *gacc, const float *prio, void *hip_stream)
+{
+  if (!r || (count && !prio)) return APEX_ERR_INVALID_ARG;
+  if (r->size() + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  if (count == 0) return APEX_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const RowMap ident{nullptr, nullptr, 0};
+  const RowMap freed{r->v.free_ring, &r->state()->free_head, r->cfg.max_slots};  // the next free slots, in order
+  int rc;
+  if (obs && (rc = launch_copy(obs, ident, r->obs(), freed, count, r->cfg.obs_bytes, stream)) != APEX_OK) return rc;
+  if (act && (rc = launch_copy(act, ident, r->act(), freed, count, r->cfg.act_bytes, stream)) != APEX_OK) return rc;
+  if (ret && (rc = launch_copy(ret, ident, r->ret(), freed, count, 4, stream)) != APEX_OK) return rc;
+  if (gacc && (rc = launch_copy(gacc, ident, r->gacc(), freed, count, 4, stream)) != APEX_OK) return rc;
+  pe_add_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->v, r->state(), count, prio);
+  pe_after_add_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), count);
+  APEX_HIP(hipGetLastError());
+  r->inserted += count;
+  return APEX_OK;
+}
+
+int apex_pe_sample(apex_pe_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                   uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
+                   float *ret_out, float *gacc_out, void *hip_stream)
+{
+  if (!r || !num_batches || !k || !rnd || !slot_out || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
+  if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
+    return APEX_ERR_TOO_LARGE;
+  if (r->size() == 0) return APEX_ERR_EMPTY;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  SampleArgs a;
+  a.tv = r->v.ts;
+  a.st = &r->state()->base;
+  a.k = k;
+  a.k_dev = nullptr;
+  a.gen = r->v.gen;
+  a.rnd = rnd;
+  a.key_out = key_out;
+  a.slot_out = slot_out;
+  a.mass = r->mass();
+  a.act = r->act();
+  a.act_bytes = r->cfg.act_bytes;
+  a.ret = r->ret();
+  a.gacc = r->gacc();
+  a.act_out = static_cast<uint8_t *>(act_out);
+  a.ret_out = ret_out;
+  a.gacc_out = gacc_out;
+  const uint32_t waves = 4;
+  const size_t lds = ((size_t)a.tv.n_top + waves) * sizeof(uint64_t);
+  sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds, stream>>>(a);
+  APEX_HIP(hipGetLastError());
+  SideJobs jobs;
+  jobs.wa = WeightArgs{r->mass(), weight_out, k, beta};
+  if (obs_out) {
+    const RowMap by_slot{slot_out, nullptr, 0};
+    const RowMap ident{nullptr, nullptr, 0};
+    const int rc = launch_copy(r->obs(), by_slot, obs_out, ident, (uint64_t)num_batches * k, r->cfg.obs_bytes, stream, &jobs);
+    if (rc != APEX_OK) return rc;
+  }
+  if (jobs.wa.weight_out) {
+    batch_weights_kernel<<<dim3(num_batches), dim3(256), 0, stream>>>(jobs.wa);
+    APEX_HIP(hipGetLastError());
+  }
+  return APEX_OK;
+}
+
+int apex_pe_update_priorities(apex_pe_replay_t *r, uint64_t m, const uint64_t *key, const float *prio,
+                              void *hip_stream)
+{
+  if (!r || (m && (!key || !prio))) return APEX_ERR_INVALID_ARG;
+  if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
+  if (m == 0) return APEX_OK;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const dim3 grid(blocks_for(m, 256)), block(256);
+  pe_update_claim_kernel<<<grid, block, 0, stream>>>(r->v, r->state(), (uint32_t)m, key, r->claim());
+  pe_update_apply_kernel<<<grid, block, 0, stream>>>(r->v, r->state(), (uint32_t)m, key, prio, r->claim());
+  APEX_HIP(hipGetLastError());
+  return APEX_OK;
+}
+
+int apex_pe_evict(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uint64_t *evicted_out, void *hip_stream)
+{
+  if (!r) return APEX_ERR_INVALID_ARG;
+  const uint64_t size = r->size();
+  const uint64_t e = size > r->cfg.capacity ? size - r->cfg.capacity : 0;
+  if (evicted_out) *evicted_out = 0;
+  if (e == 0) return APEX_OK;
+  if (!rnd || rounds == 0) return APEX_ERR_INVALID_ARG;
+  if (e > APEX_PE_MAX_EVICT_PER_CALL) return APEX_ERR_TOO_LARGE;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  PeState *st = r->state();
+  pe_begin_evict_kernel<<<dim3(1), dim3(64), 0, stream>>>(st, e);
+  SampleArgs a;
+  a.tv = r->v.te;
+  a.st = &st->base;
+  a.k = 0;
+  a.k_dev = &st->remaining;
+  a.gen = nullptr;
+  a.key_out = nullptr;
+  a.slot_out = r->cand();
+  a.mass = r->mass();
+  a.act = nullptr;
+  a.act_bytes = 0;
+  a.ret = a.gacc = nullptr;
+  a.act_out = nullptr;
+  a.ret_out = a.gacc_out = nullptr;
+  const uint32_t waves = 4;
+  const size_t lds = ((size_t)a.tv.n_top + waves) * sizeof(uint64_t);
+  const uint32_t scan_blocks = blocks_for(e, kPeScanThreads);  // <= 1024 since e <= 2^20
+  for (uint32_t rd = 0; rd < rounds; ++rd) {
+    a.rnd = rnd + (uint64_t)rd * e;
+    sample_descent_kernel<<<dim3(blocks_for(e, waves), 1), dim3(waves * kWave), lds, stream>>>(a);
+    pe_flag_scan_kernel<<<dim3(scan_blocks), dim3(kPeScanThreads), 0, stream>>>(r->cand(), st, r->pos(), r->sums());
+    pe_scan_blocks_kernel<<<dim3(1), dim3(kPeScanThreads), 0, stream>>>(r->sums(), scan_blocks, st);
+    pe_remove_kernel<<<dim3(scan_blocks), dim3(kPeScanThreads), 0, stream>>>(r->v, st, r->cand(), r->pos(), r->sums());
+    pe_round_end_kernel<<<dim3(1), dim3(64), 0, stream>>>(st);
+  }
+  APEX_HIP(hipGetLastError());
+  PeState h;
+  APEX_HIP(hipMemcpyAsync(&h, st, sizeof h, hipMemcpyDeviceToHost, stream));
+  APEX_HIP(hipStreamSynchronize(stream));
+  r->evicted = h.base.head;
+  if (evicted_out) *evicted_out = e - h.remaining;
+  return APEX_OK;
+}
+
+int apex_pe_stats(apex_pe_replay_t *r, apex_pe_stats_t *out, void *hip_stream)
+{
+  if (!r || !out) return APEX_ERR_INVALID_ARG;
+  hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  PeState h;
+  static thread_local uint64_t top[2][kTopMax];
+  const uint32_t n_top = r->v.ts.n_top;
+  APEX_HIP(hipMemcpyAsync(&h, r->state(), sizeof h, hipMemcpyDeviceToHost, stream));
+  APEX_HIP(hipMemcpyAsync(top[0], r->v.ts.level[r->v.ts.nlev - 1], (size_t)n_top * 8, hipMemcpyDeviceToHost, stream));
+  APEX_HIP(hipMemcpyAsync(top[1], r->v.te.level[r->v.te.nlev - 1], (size_t)n_top * 8, hipMemcpyDeviceToHost, stream));
+  APEX_HIP(hipStreamSynchronize(stream));
+  uint64_t root[2] = {0, 0};
+  for (int t = 0; t < 2; ++t)
+    for (uint32_t i = 0; i < n_top; ++i) root[t] += top[t][i];
+  out->size = h.base.tail - h.base.head;
+  out->inserted = h.base.tail;
+  out->evicted = h.base.head;
+  out->root = root[0];
+  out->root_evict = root[1];
+  out->free_head = h.free_head;
+  out->free_tail = h.free_tail;
+  out->n_stale_dropped = h.base.n_stale;
+  out->n_clamped = h.base.n_clamped;
+  return APEX_OK;
+}
+
+}  // extern "C"

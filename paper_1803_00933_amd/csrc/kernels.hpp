@@ -125,13 +125,13 @@ __global__ __launch_bounds__(256) void nstep_kernel(uint32_t S, uint32_t T, uint
 // a ring position read from device memory (keys base+i, slot = key mod ring), or the identity.
 struct RowMap {
   const uint32_t *index;     // row = index[i]
-  const uint64_t *ring_key;  // row = (*ring_key + i) mod ring
+  const uint64_t *ring_key;  // row = (*ring_key + i) mod ring; with index: row = index[(*ring_key + i) mod ring]
   uint64_t ring;
 };
 
 __device__ __forceinline__ uint64_t map_row(const RowMap &m, uint64_t i)
 {
-  if (m.index) return m.index[i];
+  if (m.index) return m.ring_key ? m.index[(*m.ring_key + i) % m.ring] : m.index[i];
   if (m.ring_key) return (*m.ring_key + i) % m.ring;
   return i;
 }
@@ -504,7 +504,8 @@ struct SampleArgs {
   TreeView tv;
   const DeviceState *st;
   uint32_t k;                // samples per batch
-  float beta;
+  const uint64_t *k_dev;     // not null: the number of samples is read here, on the device (waves beyond it idle)
+  const uint32_t *gen;       // not null: keys are (generation of the slot << 32) | slot instead of ring keys
   const uint64_t *rnd;       // [nb,k]
   uint64_t *key_out;         // [nb,k] or null
   uint32_t *slot_out;        // [nb,k]
@@ -530,9 +531,10 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
   const int lane = lane_id();
   const uint32_t b = blockIdx.y;
   const uint32_t j = blockIdx.x * nwave + wave;
-  const uint64_t o = (uint64_t)b * a.k + j;
+  const uint32_t k = a.k_dev ? (uint32_t)*a.k_dev : a.k;
+  const uint64_t o = (uint64_t)b * k + j;
   // issued ahead of the LDS work below, which does not depend on them
-  const uint64_t u = j < a.k ? a.rnd[o] : 0;
+  const uint64_t u = j < k ? a.rnd[o] : 0;
   const uint64_t head = a.st->head;
 
   // ---- top level -> LDS, exclusive prefix sums in place
@@ -561,8 +563,8 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
   __syncthreads();
 
   // ---- one sample per wavefront
-  if (j < a.k) {
-    const uint64_t w = total / a.k;                 // stratum width
+  if (j < k) {
+    const uint64_t w = total / k;                   // stratum width
     uint64_t x = (uint64_t)j * w + __umul64hi(u, w);  // point inside stratum j
 
     // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
@@ -595,7 +597,8 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
     const uint64_t slot = idx;
     if (lane == 0) {
       a.slot_out[o] = (uint32_t)slot;
-      if (a.key_out) a.key_out[o] = head + ((slot + tv.P - head % tv.P) % tv.P);
+      if (a.key_out)
+        a.key_out[o] = a.gen ? ((uint64_t)a.gen[slot] << 32) | slot : head + ((slot + tv.P - head % tv.P) % tv.P);
       a.mass[o] = mass;
       if (a.ret_out) a.ret_out[o] = a.ret[slot];
       if (a.gacc_out) a.gacc_out[o] = a.gacc[slot];

@@ -1,0 +1,124 @@
+"""GPU parity: the memory with prioritized eviction (apex_pe_*) against its oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import assert_sample_equal, dev, host
+
+pytestmark = pytest.mark.gpu
+F32 = np.float32
+U64 = 1 << 64
+
+
+def check(g, o):
+    lay = g.layout
+    for which in (False, True):
+        levels = [host(g.level_view(l, which), np.uint64) for l in range(lay.tree_levels)]
+        assert np.array_equal(levels[0], o.leaves(which)), "leaves %s" % which
+        for l in range(1, lay.tree_levels):
+            child = levels[l - 1]
+            pad = (-len(child)) % lay.tree_fanout
+            sums = np.concatenate([child, np.zeros(pad, np.uint64)]).reshape(-1, lay.tree_fanout).sum(1, dtype=np.uint64)
+            assert np.array_equal(levels[l], sums), "level %d %s" % (l, which)
+    st = g.stats()
+    assert (st["root"], st["root_evict"]) == (o.root, o.root_evict)
+    assert (st["size"], st["inserted"], st["evicted"]) == (o.size, o.inserted, o.evicted)
+    assert (st["free_head"], st["free_tail"]) == (o.free_head, o.free_tail)
+    assert (st["n_stale_dropped"], st["n_clamped"]) == (o.n_stale, o.n_clamped)
+    assert np.array_equal(host(g.gen_view(), np.uint32), o.gen())
+    P = o.max_slots
+    idx = np.arange(o.free_head, o.free_tail) % P
+    assert np.array_equal(host(g.free_ring_view(), np.uint32)[idx], o.free_ring()[idx])     # the live part of the ring
+
+
+@pytest.mark.parametrize("P,C,ob,ab", [(600, 400, 32, 4), (70_000, 60_000, 4112, 8), (400_000, 300_000, 12, 4)])
+def test_random_sequences_with_prioritized_eviction(P, C, ob, ab):
+    from paper_1803_00933_amd import apex
+    rng = np.random.default_rng(P)
+    g = apex.PeReplay(C, P, ob, ab)
+    o = oracle.PrioritizedEvictionReplay(C, P, ob, ab)
+    rounds = 6
+    for it in range(8):
+        cnt = P - o.size if it == 0 else int(rng.integers(1, P - o.size + 1))
+        obs = rng.integers(0, 256, (cnt, ob), dtype=np.uint8)
+        act = rng.integers(0, 256, (cnt, ab), dtype=np.uint8)
+        ret, gacc = rng.standard_normal(cnt).astype(F32), rng.random(cnt).astype(F32)
+        prio = np.where(rng.random(cnt) < 0.1, 0.0, rng.lognormal(0, 1.5, cnt)).astype(F32)
+        assert o.add(prio, obs, act, ret, gacc)[0] == 0
+        assert g.add(dev(prio), dev(obs), dev(act), dev(ret), dev(gacc)) == 0
+        assert g.add(dev(np.ones(P, F32))) == apex.ERR_FULL
+        check(g, o)
+        for nb, k in ((2, 64), (1, 300)):
+            rnd = rng.integers(0, U64, nb * k, dtype=np.uint64)
+            rco, oo = o.sample(nb, k, 0.5, rnd)
+            rcg, go = g.sample(nb, k, 0.5, dev(rnd))
+            assert rcg == rco == 0
+            torch.cuda.synchronize()
+            assert_sample_equal(go, oo)
+        keys = np.concatenate([oo["key"], oo["key"][:50], np.array([0, U64 - 1, (5 << 32) | 3], np.uint64)])
+        newp = rng.lognormal(0, 1.5, len(keys)).astype(F32)
+        newp[:2] = [np.inf, 0.0]
+        assert o.update_priorities(keys, newp) == 0
+        assert g.update_priorities(dev(keys), dev(newp)) == 0
+        check(g, o)
+        e = max(0, o.size - C)
+        rnd = rng.integers(0, U64, (rounds, max(e, 1)), dtype=np.uint64)
+        rco, eo = o.evict(rounds, rnd)
+        rcg, eg = g.evict(rounds, dev(rnd))
+        assert (rcg, eg) == (rco, eo) and eo == e
+        check(g, o)
+        # keys drawn before the eviction: those of evicted transitions are dropped on both sides
+        assert o.update_priorities(keys, newp) == 0
+        assert g.update_priorities(dev(keys), dev(newp)) == 0
+        check(g, o)
+
+
+def test_rounds_running_out_and_edges():
+    from paper_1803_00933_amd import apex
+    rng = np.random.default_rng(3)
+    g = apex.PeReplay(2, 4, 16, 4, alpha=1.0, alpha_evict=-1.0, eps=0.0)
+    o = oracle.PrioritizedEvictionReplay(2, 4, 16, 4, alpha=1.0, alpha_evict=-1.0, eps=0.0)
+    prio = np.array([1, 2, 4, 8], F32)
+    o.add(prio), g.add(dev(prio))
+    # one round, both points inside the heaviest transition: one eviction short (the hand-worked case)
+    assert g.evict(1, dev(np.zeros(2, np.uint64))) == (0, 1) == o.evict(1, np.zeros(2, np.uint64))
+    check(g, o)
+    assert g.evict(3, dev(np.zeros(3, np.uint64))) == (0, 1) == o.evict(3, np.zeros(3, np.uint64))
+    check(g, o)
+    assert g.evict(3, dev(np.zeros(3, np.uint64))) == (0, 0)
+    assert g.sample(1, 4, 0.4, dev(np.zeros(4, np.uint64)))[0] == 0
+    empty = apex.PeReplay(2, 4, 16, 4)
+    assert empty.sample(1, 4, 0.4, dev(np.zeros(4, np.uint64)))[0] == apex.ERR_EMPTY
+    for bad in (dict(alpha_evict=2.0), dict(alpha=float("nan")), dict(eps=-1.0)):
+        with pytest.raises(ValueError):
+            apex.PeReplay(2, 4, 16, 4, **bad)
+
+
+def test_control_shape_with_prioritized_eviction():
+    """The continuous-control workload as the paper ran it: capacity 1,000,000, sampling exponent 0.6, eviction
+    exponent -0.4; add rounds of 64 x 50, batch 512, eviction every 10 rounds."""
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["control"]
+    g = apex.PeReplay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    o = oracle.PrioritizedEvictionReplay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes, payload=False)
+    prio = synth.priorities("lognormal1", w.seed, 0, w.capacity, tag="bulk")
+    assert o.add(prio)[0] == 0 and g.add(dev(prio)) == 0
+    check(g, o)
+    rounds = 5
+    for step in range(60):
+        p_new = synth.priorities("lognormal1", w.seed, step + 1, w.add_count, tag="bulk")
+        assert o.add(p_new)[0] == 0 and g.add(dev(p_new)) == 0
+        rnd = synth.uniforms(w.seed, step, 1, w.k).reshape(-1)
+        rco, oo = o.sample(1, w.k, w.beta, rnd, payload=False)
+        rcg, go = g.sample(1, w.k, w.beta, dev(rnd))
+        torch.cuda.synchronize()
+        assert_sample_equal(go, oo, payload=False)
+        newp = synth.priorities(w.td_dist, w.seed, step, w.k)
+        assert o.update_priorities(oo["key"], newp) == 0 and g.update_priorities(go["key"], dev(newp)) == 0
+        if (step + 1) % 10 == 0:
+            e = o.size - w.capacity
+            rnd_e = np.random.default_rng(step).integers(0, U64, (rounds, e), dtype=np.uint64)
+            assert g.evict(rounds, dev(rnd_e)) == o.evict(rounds, rnd_e) == (0, e)
+            check(g, o)
+    check(g, o)
