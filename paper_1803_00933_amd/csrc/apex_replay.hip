@@ -39,12 +39,14 @@ uint32_t ceil_log2(uint64_t v)
 
 uint64_t qmax_for(uint64_t max_slots) { return max_slots ? 1ull << (62 - ceil_log2(max_slots)) : 1ull << 62; }
 
+constexpr uint32_t kStepSets = 64;  // buffer sets a sequence of fused steps can cycle through
+
 struct Geometry {
   uint64_t obs_off, act_off, ret_off, gacc_off, storage_bytes;
   uint32_t nlev;
   uint64_t level_off[kMaxLevels], level_size[kMaxLevels], tree_words;
-  // scratch: DeviceState | mass | claim
-  uint64_t state_off, mass_off, claim_off, scratch_bytes;
+  // scratch: DeviceState | mass | claim | new masses of the batches of fused steps
+  uint64_t state_off, mass_off, claim_off, stepq_off, scratch_bytes;
 };
 
 int validate(const apex_replay_config_t *c)
@@ -82,7 +84,8 @@ int geometry(const apex_replay_config_t *c, Geometry *g)
   g->state_off = 0;
   g->mass_off = 256;
   g->claim_off = g->mass_off + (uint64_t)APEX_MAX_SAMPLES_PER_CALL * 8;
-  g->scratch_bytes = g->claim_off + round_up(P * 4, 256);
+  g->stepq_off = g->claim_off + round_up(P * 4, 256);
+  g->scratch_bytes = g->stepq_off + (uint64_t)kStepSets * kStepMaxK * 8;
   return APEX_OK;
 }
 
@@ -97,10 +100,16 @@ struct apex_replay {
   uint64_t head, tail;  // host mirror of the device state
   QuantParams qp;
   TreeView tv;
+  // Second copy of the tree, behind the first in the tree region: used by sequences of fused learner
+  // steps only.  It equals the first while tree_version == second_version; every entry point that
+  // changes the first copy moves tree_version on.
+  TreeView tv2;
+  uint64_t tree_version = 1, second_version = 0;
 
   DeviceState *state() const { return reinterpret_cast<DeviceState *>(scratch + geo.state_off); }
   uint64_t *mass() const { return reinterpret_cast<uint64_t *>(scratch + geo.mass_off); }
   uint32_t *claim() const { return reinterpret_cast<uint32_t *>(scratch + geo.claim_off); }
+  uint64_t *stepq(uint32_t set) const { return reinterpret_cast<uint64_t *>(scratch + geo.stepq_off) + (uint64_t)set * kStepMaxK; }
   uint8_t *obs() const { return storage + geo.obs_off; }
   uint8_t *act() const { return storage + geo.act_off; }
   float *ret() const { return reinterpret_cast<float *>(storage + geo.ret_off); }
@@ -188,7 +197,7 @@ int apex_replay_workspace_bytes(const apex_replay_config_t *cfg, size_t *storage
   rc = geometry(cfg, &g);
   if (rc != APEX_OK) return rc;
   if (storage_bytes) *storage_bytes = g.storage_bytes;
-  if (tree_bytes) *tree_bytes = g.tree_words * 8;
+  if (tree_bytes) *tree_bytes = 2 * g.tree_words * 8;  // two copies, see learner_step_kernel
   if (scratch_bytes) *scratch_bytes = g.scratch_bytes;
   return APEX_OK;
 }
@@ -217,8 +226,10 @@ int apex_replay_create(const apex_replay_config_t *cfg, void *d_storage, void *d
   r->tv.n_top = (uint32_t)r->geo.level_size[r->geo.nlev - 1];
   r->tv.P = cfg->max_slots;
   for (uint32_t l = 0; l < kMaxLevels; ++l) r->tv.level[l] = l < r->geo.nlev ? r->tree + r->geo.level_off[l] : nullptr;
+  r->tv2 = r->tv;
+  for (uint32_t l = 0; l < r->geo.nlev; ++l) r->tv2.level[l] = r->tv.level[l] + r->geo.tree_words;
 
-  fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(r->tree, r->geo.tree_words);
+  fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(r->tree, 2 * r->geo.tree_words);
   fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(reinterpret_cast<uint64_t *>(r->scratch),
                                                           r->geo.scratch_bytes / 8);
   if (hip_failed(hipGetLastError()) || hip_failed(hipDeviceSynchronize())) {
@@ -295,6 +306,7 @@ int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio,
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
   if (count) {
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    ++r->tree_version;
     add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), count, prio, r->qp);
     advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), 0, count);
     APEX_HIP(hipGetLastError());
@@ -353,6 +365,7 @@ namespace {
 int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *prio, hipStream_t stream,
                   const QSource &qs = QSource{})
 {
+  ++r->tree_version;
   if (m <= 1024) {
     const UpdateArgs ua{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, nullptr, nullptr, qs};
     update_small_kernel<<<dim3(1), dim3((uint32_t)round_up(m, kWave)), 0, stream>>>(ua);
@@ -374,6 +387,7 @@ int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, co
   SideJobs jobs;
   jobs.wa = WeightArgs{mass, weight_out, k, beta};
   const bool hint = same_batch && mass && m == (uint64_t)num_batches * k;
+  if (m) ++r->tree_version;
   if (m && (m <= 1024 || hint)) {
     jobs.ua = UpdateArgs{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, hint ? slot : nullptr, hint ? mass : nullptr,
                          QSource{}};
@@ -389,6 +403,96 @@ int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, co
     APEX_HIP(hipGetLastError());
   }
   if (m && (jobs.ua.m || !(m <= 1024 || hint))) return launch_update(r, m, key, prio, stream);
+  return APEX_OK;
+}
+
+// n learner steps of one batch of k each, in strict order (draw i, write-back i, draw i+1, ...), as
+// one standalone draw, one launch per step, and one small launch at the end: see
+// learner_step_kernel.  Batch i goes to sets[(first_set + i) % depth]; kernel i reads the sets of
+// batches i-1 and i and writes that of batch i+1, hence depth >= 3.
+// Returns APEX_ERR_NOT_READY - with nothing enqueued - when the shapes do not fit the fused launch.
+bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uint32_t depth,
+                     const apex_batch_buffers_t *sets)
+{
+  const uint64_t row_bytes = r->cfg.obs_bytes;
+  const uint64_t vpr = row_bytes / sizeof(u32x4);
+  if (num_batches != 1 || k > kStepMaxK || depth < 3 || depth > kStepSets || r->tv.n_top > kStepMaxTop) return false;
+  if (row_bytes % sizeof(u32x4) || vpr <= 256 || vpr > (uint64_t)kLongCopyThreads * kLongCopyUnroll) return false;
+  if ((uintptr_t)r->obs() & 15) return false;
+  for (uint32_t i = 0; i < depth; ++i)
+    if ((uintptr_t)sets[i].obs & 15) return false;
+  return true;
+}
+
+int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64_t *rnd, const float *new_prio,
+                const apex_batch_buffers_t *sets, uint32_t depth, uint32_t first_set, bool always_copy,
+                hipStream_t stream)
+{
+  const auto idx = [&](uint32_t i) { return (first_set + i) % depth; };
+  const auto set = [&](uint32_t i) -> const apex_batch_buffers_t & { return sets[idx(i)]; };
+  const apex_batch_buffers_t &b0 = set(0);
+  int rc = apex_replay_sample_begin(r, 1, k, rnd, b0.key, b0.slot, b0.mass, b0.act, b0.ret, b0.gacc, stream);
+  if (rc != APEX_OK) return rc;
+  if (new_prio) {
+    if (always_copy || r->second_version != r->tree_version)
+      copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
+    first_deltas_kernel<<<dim3(blocks_for(k, 256)), dim3(256), 0, stream>>>(new_prio, b0.mass, r->stepq(idx(0)), k,
+                                                                            r->qp, r->state());
+    APEX_HIP(hipGetLastError());
+  }
+  const size_t lds = ((size_t)r->tv.n_top + k + kFanout) * 8 + (size_t)k * 4;
+  for (uint32_t i = 0; i < n; ++i) {
+    const apex_batch_buffers_t &b = set(i);
+    const TreeView &rd = (new_prio && (i & 1)) ? r->tv2 : r->tv;
+    const TreeView &wr = (new_prio && (i & 1)) ? r->tv : r->tv2;
+    StepArgs a{};
+    a.src = r->obs();
+    a.dst = static_cast<uint8_t *>(b.obs);
+    a.row_bytes = r->cfg.obs_bytes;
+    a.vecs_per_row = (uint32_t)(a.row_bytes / sizeof(u32x4));
+    a.k = k;
+    a.act = r->act();
+    a.act_bytes = r->cfg.act_bytes;
+    a.ret = r->ret();
+    a.gacc = r->gacc();
+    a.act_out = static_cast<uint8_t *>(b.act);
+    a.ret_out = b.ret;
+    a.gacc_out = b.gacc;
+    a.slot = b.slot;
+    a.dq = new_prio ? r->stepq(idx(i)) : nullptr;
+    if (new_prio && i > 0) {
+      a.prev_slot = set(i - 1).slot;
+      a.prev_dq = r->stepq(idx(i - 1));
+    }
+    a.qp = r->qp;
+    a.wr = wr;
+    a.st = r->state();
+    a.wa = WeightArgs{b.mass, b.weight, k, beta};
+    a.next.tv = rd;
+    a.next.st = r->state();
+    a.next.k = k;
+    if (i + 1 < n) {
+      const apex_batch_buffers_t &nb = set(i + 1);
+      a.next.rnd = rnd + (uint64_t)(i + 1) * k;
+      a.next.key_out = nb.key;
+      a.next.slot_out = nb.slot;
+      a.next.mass = nb.mass;
+      // the small columns of batch i+1 are gathered by the launch that copies its rows
+      if (new_prio) {
+        a.next_prio = new_prio + (uint64_t)(i + 1) * k;
+        a.next_dq = r->stepq(idx(i + 1));
+      }
+    }
+    learner_step_kernel<u32x4, kLongCopyUnroll><<<dim3(k), dim3(kLongCopyThreads), lds, stream>>>(a);
+  }
+  if (new_prio) {
+    // the copy read by the last launch is one batch behind
+    const TreeView &behind = ((n - 1) & 1) ? r->tv2 : r->tv;
+    const apex_batch_buffers_t &b = set(n - 1);
+    apply_deltas_kernel<<<dim3(blocks_for(k, 256)), dim3(256), 0, stream>>>(behind, b.slot, r->stepq(idx(n - 1)), k);
+    r->second_version = ++r->tree_version;
+  }
+  APEX_HIP(hipGetLastError());
   return APEX_OK;
 }
 
@@ -493,6 +597,7 @@ int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream)
   if (evicted_out) *evicted_out = e;
   if (e == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  ++r->tree_version;
   evict_leaves_kernel<<<dim3(blocks_for(e, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), e);
   advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), e, 0);
   APEX_HIP(hipGetLastError());

@@ -518,35 +518,27 @@ struct SampleArgs {
   float *ret_out, *gacc_out;
 };
 
-// Dynamic LDS: n_top uint64 (exclusive prefix sums of the top level) + blockDim/64 words.
-__global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
-{
-  extern __shared__ uint64_t lds[];
-  const TreeView &tv = a.tv;
-  const uint32_t n_top = tv.n_top;
-  uint64_t *pre = lds;
-  uint64_t *wave_total = lds + n_top;
-  const uint32_t tid = threadIdx.x, nthr = blockDim.x, nwave = nthr / kWave;
-  const uint32_t wave = tid / kWave;
-  const int lane = lane_id();
-  const uint32_t b = blockIdx.y;
-  const uint32_t j = blockIdx.x * nwave + wave;
-  const uint32_t k = a.k_dev ? (uint32_t)*a.k_dev : a.k;
-  const uint64_t o = (uint64_t)b * k + j;
-  // issued ahead of the LDS work below, which does not depend on them
-  const uint64_t u = j < k ? a.rnd[o] : 0;
-  const uint64_t head = a.st->head;
+// Pending changes of leaf masses that the tree in memory does not hold yet (LDS): a descent adds
+// them to every row of children it reads.  count == 0: none.
+struct PendingDeltas {
+  const uint32_t *slot;   // [count]
+  const uint64_t *delta;  // [count], mod 2^64; 0: nothing to add
+  uint32_t count;
+  uint64_t *row;          // 64 words of scratch, private to the wave that descends
+};
 
-  // ---- top level -> LDS, exclusive prefix sums in place
-  const uint64_t *top = tv.level[tv.nlev - 1];
-  for (uint32_t i = tid; i < n_top; i += nthr) pre[i] = top[i];
-  __syncthreads();
+// Turns pre[0, n_top) (LDS, the top level's masses, complete and visible) into exclusive prefix sums in
+// place and returns their total.  wave_total: blockDim/64 words of LDS.  Called by every thread
+// of the workgroup; ends with a barrier.
+__device__ __forceinline__ uint64_t top_prefix_sums(uint64_t *pre, uint64_t *wave_total, uint32_t n_top)
+{
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x, nwave = nthr / kWave, wave = tid / kWave;
   const uint32_t per = (n_top + nthr - 1) / nthr;
   const uint32_t lo = min(tid * per, n_top), hi = min(lo + per, n_top);
   uint64_t mine = 0;
   for (uint32_t i = lo; i < hi; ++i) mine += pre[i];
   const uint64_t incl = wave_inclusive_scan(mine);
-  if (lane == kWave - 1) wave_total[wave] = incl;
+  if (lane_id() == kWave - 1) wave_total[wave] = incl;
   __syncthreads();
   uint64_t before = 0, total = 0;
   for (uint32_t w = 0; w < nwave; ++w) {
@@ -561,53 +553,405 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
     run += v;
   }
   __syncthreads();
+  return total;
+}
+
+struct Drawn {
+  uint64_t slot, mass;
+};
+
+// One wavefront walks from the top level (exclusive prefix sums `pre` in LDS) down to the slot
+// whose cumulative-mass interval holds x.  Called by all 64 lanes.
+template <bool kPending>
+__device__ __forceinline__ Drawn wave_descend(const TreeView &tv, const uint64_t *pre, uint64_t total, uint64_t x,
+                                              const PendingDeltas &pd)
+{
+  const int lane = lane_id();
+  const uint32_t n_top = tv.n_top;
+  // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
+  const uint32_t stride = (n_top + kWave - 1) / kWave;
+  uint32_t p0 = lane * stride;
+  uint32_t cnt = __popcll(__ballot(p0 < n_top && pre[p0] <= x));
+  const uint32_t base = (cnt - 1) * stride;  // pre[0] = 0 <= x, so cnt >= 1
+  cnt = 0;
+  for (uint32_t off = 0; off < stride; off += kWave) {
+    const uint32_t p1 = base + off + lane;
+    cnt += __popcll(__ballot(off + lane < stride && p1 < n_top && pre[p1] <= x));
+  }
+  uint64_t idx = base + cnt - 1;
+  uint64_t mass = ((idx + 1 < n_top) ? pre[idx + 1] : total) - pre[idx];
+  x -= pre[idx];
+
+  // lower levels: 64 children per step, prefix sum across the wave, first child whose
+  // running sum exceeds the remainder
+  for (int l = (int)tv.nlev - 2; l >= 0; --l) {
+    uint64_t c = tv.level[l][idx * kFanout + lane];
+    if (kPending && pd.count) {
+      // the pending deltas that fall under node idx, summed per child in LDS
+      pd.row[lane] = 0;
+      __builtin_amdgcn_wave_barrier();
+      const uint32_t sh = kFanoutLog2 * (uint32_t)l;
+      // (the loads of a group of eight entries per lane go out together)
+      for (uint32_t e0 = 0; e0 < pd.count; e0 += 8 * kWave) {
+        uint32_t es[8];
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          const uint32_t e = e0 + t * kWave + lane;
+          es[t] = e < pd.count ? pd.slot[e] : 0xffffffffu;  // no node has this prefix: slots are below 2^31
+        }
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          if (((uint64_t)es[t] >> (sh + kFanoutLog2)) == idx) {
+            const uint64_t dv = pd.delta[e0 + t * kWave + lane];
+            if (dv) atomicAdd(reinterpret_cast<unsigned long long *>(pd.row + ((es[t] >> sh) & (kFanout - 1))),
+                              (unsigned long long)dv);
+          }
+        }
+      }
+      __builtin_amdgcn_wave_barrier();
+      c += pd.row[lane];
+      __builtin_amdgcn_wave_barrier();
+    }
+    const uint64_t sc = wave_inclusive_scan(c);
+    const uint64_t hit = __ballot(sc > x);
+    const int sel = hit ? __ffsll((unsigned long long)hit) - 1 : kWave - 1;
+    const uint64_t c_sel = __shfl(c, sel, kWave);
+    const uint64_t s_sel = __shfl(sc, sel, kWave);
+    x -= s_sel - c_sel;
+    idx = idx * kFanout + sel;
+    mass = c_sel;
+  }
+  return Drawn{idx, mass};
+}
+
+// What a draw writes for sample o (called by all 64 lanes of the wave that drew it).
+__device__ __forceinline__ void write_drawn(const SampleArgs &a, uint64_t o, Drawn d, uint64_t head)
+{
+  const TreeView &tv = a.tv;
+  const int lane = lane_id();
+  const uint64_t slot = d.slot;
+  if (lane == 0) {
+    a.slot_out[o] = (uint32_t)slot;
+    if (a.key_out)
+      a.key_out[o] = a.gen ? ((uint64_t)a.gen[slot] << 32) | slot : head + ((slot + tv.P - head % tv.P) % tv.P);
+    a.mass[o] = d.mass;
+    if (a.ret_out) a.ret_out[o] = a.ret[slot];
+    if (a.gacc_out) a.gacc_out[o] = a.gacc[slot];
+  }
+  if (a.act_out)
+    for (uint32_t by = lane; by < a.act_bytes; by += kWave)
+      a.act_out[o * a.act_bytes + by] = a.act[slot * a.act_bytes + by];
+}
+
+// Dynamic LDS: n_top uint64 (exclusive prefix sums of the top level) + blockDim/64 words.
+__global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
+{
+  extern __shared__ uint64_t lds[];
+  const TreeView &tv = a.tv;
+  const uint32_t n_top = tv.n_top;
+  uint64_t *pre = lds;
+  uint64_t *wave_total = lds + n_top;
+  const uint32_t tid = threadIdx.x, nthr = blockDim.x, nwave = nthr / kWave;
+  const uint32_t wave = tid / kWave;
+  const uint32_t b = blockIdx.y;
+  const uint32_t j = blockIdx.x * nwave + wave;
+  const uint32_t k = a.k_dev ? (uint32_t)*a.k_dev : a.k;
+  const uint64_t o = (uint64_t)b * k + j;
+  // issued ahead of the LDS work below, which does not depend on them
+  const uint64_t u = j < k ? a.rnd[o] : 0;
+  const uint64_t head = a.st->head;
+
+  // ---- top level -> LDS, exclusive prefix sums in place
+  const uint64_t *top = tv.level[tv.nlev - 1];
+  for (uint32_t i = tid; i < n_top; i += nthr) pre[i] = top[i];
+  __syncthreads();
+  const uint64_t total = top_prefix_sums(pre, wave_total, n_top);
 
   // ---- one sample per wavefront
   if (j < k) {
-    const uint64_t w = total / k;                   // stratum width
-    uint64_t x = (uint64_t)j * w + __umul64hi(u, w);  // point inside stratum j
+    const uint64_t w = total / k;                           // stratum width
+    const uint64_t x = (uint64_t)j * w + __umul64hi(u, w);  // point inside stratum j
+    write_drawn(a, o, wave_descend<false>(tv, pre, total, x, PendingDeltas{}), head);
+  }
+}
 
-    // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
-    const uint32_t stride = (n_top + kWave - 1) / kWave;
-    uint32_t p0 = lane * stride;
-    uint32_t cnt = __popcll(__ballot(p0 < n_top && pre[p0] <= x));
-    const uint32_t base = (cnt - 1) * stride;  // pre[0] = 0 <= x, so cnt >= 1
-    cnt = 0;
-    for (uint32_t off = 0; off < stride; off += kWave) {
-      const uint32_t p1 = base + off + lane;
-      cnt += __popcll(__ballot(off + lane < stride && p1 < n_top && pre[p1] <= x));
-    }
-    uint64_t idx = base + cnt - 1;
-    uint64_t mass = ((idx + 1 < n_top) ? pre[idx + 1] : total) - pre[idx];
-    x -= pre[idx];
+// --------------------------------------------------------------------------------------------
+// One launch per learner step (Algorithm 2: replay.Sample, replay.SetPriority in strict order):
+// the gather of batch i, its importance weights, the write-back of its new priorities, and the
+// draw of batch i+1 as it follows that write-back.
+//
+// A draw may not read a tree that other workgroups of the same launch are writing, so the memory
+// keeps two copies of the sum tree.  The launch reads one of them, which holds every write-back
+// up to batch i-1, and each workgroup adds the changes of batch i to what it reads from it: the
+// k pairs (slot, new mass - old mass) are worked out by every workgroup and held in LDS.  The
+// same changes, and those of batch i-1 which the other copy still lacks, go into the other copy
+// with atomics, one pair per workgroup; the next launch reads that copy.  The two copies swap
+// roles from launch to launch, and the last launch of a sequence is followed by
+// apply_deltas_kernel on the copy that is one batch behind.
+//
+// Within a batch the drawn slots do not decrease (the strata are ordered), so the pairs that
+// share a slot are neighbours and the last of them is the one that counts.
+// --------------------------------------------------------------------------------------------
+__device__ __forceinline__ void add_delta(const TreeView &tv, uint32_t slot, uint64_t delta)
+{
+  if (!delta) return;
+  atomic_add_u64(tv.level[0] + slot, delta);
+  add_to_ancestors(tv, slot, delta);
+}
 
-    // lower levels: 64 children per step, prefix sum across the wave, first child whose
-    // running sum exceeds the remainder
-    for (int l = (int)tv.nlev - 2; l >= 0; --l) {
-      const uint64_t c = tv.level[l][idx * kFanout + lane];
-      const uint64_t sc = wave_inclusive_scan(c);
-      const uint64_t hit = __ballot(sc > x);
-      const int sel = hit ? __ffsll((unsigned long long)hit) - 1 : kWave - 1;
-      const uint64_t c_sel = __shfl(c, sel, kWave);
-      const uint64_t s_sel = __shfl(sc, sel, kWave);
-      x -= s_sel - c_sel;
-      idx = idx * kFanout + sel;
-      mass = c_sel;
+// Orders the LDS accesses of one wavefront among its lanes (the hardware runs them in order; this
+// keeps the compiler from moving them).
+__device__ __forceinline__ void wave_lds_sync()
+{
+  __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+constexpr uint32_t kStepMaxK = 1024;    // pairs per batch that the fused step handles
+constexpr uint32_t kStepMaxTop = 1024;  // top-level nodes that its single drawing wave stages
+
+struct StepArgs {
+  // gather of batch i: row j of dst = row slot[j] of src; the small columns likewise
+  const uint8_t *src;
+  uint8_t *dst;
+  uint32_t vecs_per_row;  // <= kLongCopyUnroll * blockDim
+  uint64_t row_bytes;
+  const uint8_t *act;
+  uint32_t act_bytes;
+  const float *ret, *gacc;
+  uint8_t *act_out;
+  float *ret_out, *gacc_out;
+  uint32_t k;             // <= kStepMaxK
+  const uint32_t *slot;   // [k] batch i as it was drawn
+  const uint64_t *dq;     // [k] new mass - mass as drawn; null: nothing is written back in this sequence
+  const uint32_t *prev_slot;  // batch i-1, which the written copy still lacks; null: none
+  const uint64_t *prev_dq;
+  TreeView wr;            // the copy that is written
+  WeightArgs wa;          // weights of batch i
+  SampleArgs next;        // draw of batch i+1 from next.tv, the copy that is read; next.rnd == null: none
+  const float *next_prio; // [k] new priorities of batch i+1 (null: none) ...
+  uint64_t *next_dq;      // ... their mass differences, written by the wave that draws the sample
+  QuantParams qp;
+  DeviceState *st;
+};
+
+// The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier:
+// pending changes and the top level into LDS, the changes added to the top level, prefix sums,
+// descent.  LDS, in words of 8 bytes: n_top + k + 64, then k words of 4 bytes.
+__device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *lds)
+{
+  const TreeView &rd = a.next.tv;
+  const uint32_t n_top = rd.n_top, lane = lane_id();
+  const uint32_t kp = a.dq ? a.k : 0;
+  uint64_t *pre = lds;
+  uint64_t *p_delta = pre + n_top;
+  uint64_t *p_row = p_delta + a.k;
+  uint32_t *p_slot = reinterpret_cast<uint32_t *>(p_row + kFanout);
+  __builtin_amdgcn_s_setprio(2);
+
+  const uint64_t un = a.next.rnd[row];
+  const float prio_next = a.next_prio ? a.next_prio[row] : 0.0f;
+  const uint64_t head = a.next.st->head;
+  // pending changes: a pair counts unless the next pair has the same slot (eight pairs per lane in flight)
+  for (uint32_t j0 = 0; j0 < kp; j0 += 8 * kWave) {
+    uint32_t sj[8], sn[8];
+    uint64_t dj[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const uint32_t j = j0 + t * kWave + lane;
+      sj[t] = j < kp ? a.slot[j] : 0xffffffffu;
+      sn[t] = j + 1 < kp ? a.slot[j + 1] : 0xfffffffeu;
+      dj[t] = j < kp ? a.dq[j] : 0;
     }
-    const uint64_t slot = idx;
-    if (lane == 0) {
-      a.slot_out[o] = (uint32_t)slot;
-      if (a.key_out)
-        a.key_out[o] = a.gen ? ((uint64_t)a.gen[slot] << 32) | slot : head + ((slot + tv.P - head % tv.P) % tv.P);
-      a.mass[o] = mass;
-      if (a.ret_out) a.ret_out[o] = a.ret[slot];
-      if (a.gacc_out) a.gacc_out[o] = a.gacc[slot];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const uint32_t j = j0 + t * kWave + lane;
+      if (j < kp) {
+        p_slot[j] = sj[t];
+        p_delta[j] = sn[t] != sj[t] ? dj[t] : 0;
+      }
     }
-    if (a.act_out)
-      for (uint32_t by = lane; by < a.act_bytes; by += kWave)
-        a.act_out[o * a.act_bytes + by] = a.act[slot * a.act_bytes + by];
+  }
+  const uint64_t *top = rd.level[rd.nlev - 1];
+  for (uint32_t i0 = 0; i0 < n_top; i0 += 8 * kWave) {
+    uint64_t v[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const uint32_t i = i0 + t * kWave + lane;
+      v[t] = i < n_top ? top[i] : 0;
+    }
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const uint32_t i = i0 + t * kWave + lane;
+      if (i < n_top) pre[i] = v[t];
+    }
+  }
+  bool clamped = false;
+  const uint64_t q_next = a.next_prio ? quantise_priority(prio_next, a.qp, &clamped) : 0;
+  wave_lds_sync();
+  const uint32_t sh_top = kFanoutLog2 * (rd.nlev - 1);
+  for (uint32_t j = lane; j < kp; j += kWave) {
+    const uint64_t dv = p_delta[j];
+    if (dv) atomicAdd(reinterpret_cast<unsigned long long *>(pre + (p_slot[j] >> sh_top)), (unsigned long long)dv);
+  }
+  wave_lds_sync();
+  // exclusive prefix sums in place: a contiguous run of `per` nodes per lane
+  const uint32_t per = (n_top + kWave - 1) / kWave;
+  const uint32_t lo = min(lane * per, n_top), hi = min(lo + per, n_top);
+  uint64_t mine = 0;
+  for (uint32_t i = lo; i < hi; ++i) mine += pre[i];
+  const uint64_t incl = wave_inclusive_scan(mine);
+  const uint64_t total = __shfl(incl, kWave - 1, kWave);
+  uint64_t run = incl - mine;
+  for (uint32_t i = lo; i < hi; ++i) {
+    const uint64_t v = pre[i];
+    pre[i] = run;
+    run += v;
+  }
+  wave_lds_sync();
+
+  const uint64_t w = total / a.next.k;
+  const uint64_t x = (uint64_t)row * w + __umul64hi(un, w);
+  const PendingDeltas pd{p_slot, p_delta, rd.nlev > 1 ? kp : 0, p_row};
+  const Drawn dr = wave_descend<true>(rd, pre, total, x, pd);
+  write_drawn(a.next, row, dr, head);
+  if (a.next_prio && lane == 0) {
+    a.next_dq[row] = q_next - dr.mass;
+    if (clamped) atomic_add_u64(&a.st->n_clamped, 1);
+  }
+  __builtin_amdgcn_s_setprio(0);
+}
+
+// No barrier anywhere: the waves of a workgroup run independently.
+//   wave 0       draws sample `row` of the next batch; copies too only when the other waves cannot
+//                hold the whole row (its dependent loads would queue behind the row loads)
+//   wave 1       lane 0 carries pair `row` of this batch and of the batch before into the written
+//                copy; lanes 1, 2 gather ret and gacc of the row
+//   wave 2       gathers the action bytes of the row
+//   wave 3       in the first ceil(k / 64) workgroups: importance weights of 64 samples
+// Dynamic LDS: see draw_in_first_wave.
+template <typename Vec, int kUnroll>
+__global__ __launch_bounds__(kLongCopyThreads) void learner_step_kernel(StepArgs a)
+{
+  extern __shared__ uint64_t lds[];
+  const uint32_t row = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
+  const uint32_t wave = tid / kWave, lane = lane_id();
+  const bool write_back = a.dq != nullptr, draw = a.next.rnd != nullptr;
+  const uint32_t first = (draw && a.vecs_per_row <= (nthr - kWave) * kUnroll) ? kWave : 0;
+  if (draw && wave == 0) {
+    draw_in_first_wave(a, row, lds);
+    if (first) return;
+  }
+  const uint32_t my_slot = a.slot[row];
+
+  // ---- small loads first, so that nothing that uses them waits for the row
+  const bool carrier = write_back && tid == kWave;
+  uint32_t pc_next = 0xfffffffeu, pp_slot = 0, pp_next = 0xfffffffeu;
+  uint64_t pc_dq = 0, pp_dq = 0;
+  if (carrier) {
+    if (row + 1 < a.k) pc_next = a.slot[row + 1];
+    pc_dq = a.dq[row];
+    if (a.prev_dq) {
+      pp_slot = a.prev_slot[row];
+      if (row + 1 < a.k) pp_next = a.prev_slot[row + 1];
+      pp_dq = a.prev_dq[row];
+    }
+  }
+  float small = 0.0f;
+  if (tid == kWave + 1 && a.ret_out) small = a.ret[my_slot];
+  if (tid == kWave + 2 && a.gacc_out) small = a.gacc[my_slot];
+  const bool weigher = wave == 3 && a.wa.weight_out && row * kWave < a.k;
+  uint64_t mass_min = ~0ull, mass_mine = 1;
+  if (weigher) {  // smallest mass of the batch, eight loads per lane in flight
+    for (uint32_t j0 = 0; j0 < a.k; j0 += 8 * kWave) {
+      uint64_t wm[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const uint32_t j = j0 + t * kWave + lane;
+        wm[t] = j < a.k ? a.wa.mass[j] : ~0ull;
+      }
+#pragma unroll
+      for (int t = 0; t < 8; ++t) mass_min = wm[t] < mass_min ? wm[t] : mass_min;
+    }
+    if (row * kWave + lane < a.k) mass_mine = a.wa.mass[row * kWave + lane];
+  }
+  uint8_t act_byte[4] = {0, 0, 0, 0};
+  const bool act_early = wave == 2 && a.act_out && a.act_bytes <= 4 * kWave;
+  if (act_early) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const uint32_t by = t * kWave + lane;
+      if (by < a.act_bytes) act_byte[t] = a.act[(uint64_t)my_slot * a.act_bytes + by];
+    }
   }
 
+  // ---- the row
+  const uint32_t copiers = nthr - first;
+  const Vec *s = reinterpret_cast<const Vec *>(a.src + (uint64_t)my_slot * a.row_bytes);
+  Vec *d = reinterpret_cast<Vec *>(a.dst + (uint64_t)row * a.row_bytes);
+  Vec tmp[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t v = tid - first + u * copiers;
+    if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+  }
+
+  if (carrier) {
+    if (pc_next != my_slot) add_delta(a.wr, my_slot, pc_dq);
+    if (pp_next != pp_slot) add_delta(a.wr, pp_slot, pp_dq);  // pp_dq = 0 without a batch before
+  }
+  if (tid == kWave + 1 && a.ret_out) a.ret_out[row] = small;
+  if (tid == kWave + 2 && a.gacc_out) a.gacc_out[row] = small;
+  if (act_early) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+      const uint32_t by = t * kWave + lane;
+      if (by < a.act_bytes) a.act_out[(uint64_t)row * a.act_bytes + by] = act_byte[t];
+    }
+  }
+  if (weigher) {
+    const float fmn = (float)wave_min(mass_min);
+    const uint32_t j = row * kWave + lane;
+    if (j < a.k) a.wa.weight_out[j] = pow_fixed_sequence(fmn / (float)mass_mine, a.wa.beta);
+  }
+
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t v = tid - first + u * copiers;
+    if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+  }
+  if (wave == 2 && a.act_out && !act_early)  // long action rows: after the row, which they would hold up
+    for (uint32_t by = lane; by < a.act_bytes; by += kWave)
+      a.act_out[(uint64_t)row * a.act_bytes + by] = a.act[(uint64_t)my_slot * a.act_bytes + by];
+}
+
+// Mass differences of the first batch of a sequence of fused steps: Q(prio) - mass as drawn.
+__global__ __launch_bounds__(256) void first_deltas_kernel(const float *prio, const uint64_t *mass, uint64_t *dq,
+                                                           uint32_t k, QuantParams qp, DeviceState *st)
+{
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  bool clamped = false;
+  if (j < k) dq[j] = quantise_priority(prio[j], qp, &clamped) - mass[j];
+  const uint64_t nc = __popcll(__ballot(clamped));
+  if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
+}
+
+// Adds the changes of one batch (see learner_step_kernel) to a copy of the tree.
+__global__ __launch_bounds__(256) void apply_deltas_kernel(TreeView tv, const uint32_t *slot, const uint64_t *dq,
+                                                           uint32_t k)
+{
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= k) return;
+  const uint32_t sj = slot[j];
+  if (j + 1 == k || slot[j + 1] != sj) add_delta(tv, sj, dq[j]);
+}
+
+// dst[i] = src[i]: brings the second copy of the tree up to date
+__global__ __launch_bounds__(256) void copy_words_kernel(uint64_t *__restrict__ dst, const uint64_t *__restrict__ src,
+                                                         uint64_t n)
+{
+  for (uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (uint64_t)gridDim.x * blockDim.x)
+    dst[i] = src[i];
 }
 
 // zero fill (hipMemset is avoided so that the library's launches stay replayable)

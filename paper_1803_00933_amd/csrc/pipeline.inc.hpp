@@ -1,6 +1,9 @@
 // apex_pipeline_*: the replay verbs issued on two internal streams ordered by events (learner
 // steps on one, the payload copies of add rounds on the other), and the same sequence captured
 // once as a HIP graph and replayed.
+// A step that draws several batches at once (the learner's prefetch, Section 4.1) is long enough
+// to pay for two more events: its gather then runs on the copy stream, beside the write-back of
+// its priorities and the next draw, which are all that the next step has to wait for.
 // Included by apex_replay.hip (one translation unit), after the plain entry points.
 
 struct apex_pipeline {
@@ -16,6 +19,11 @@ struct apex_pipeline {
     hipEvent_t cur = nullptr;  // what a wait has to wait for; null: nothing to wait for
   };
   Mark payload_done, tail_ready;
+  // wide steps only: the draw of a step (the copy stream's gather waits for it), and per buffer
+  // set the gather that last read it (the next draw into that set waits for it)
+  bool wide = false;
+  Mark drawn;
+  std::vector<Mark> gathered;
   hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   std::vector<hipEvent_t> capture_events;
 
@@ -33,6 +41,12 @@ struct apex_pipeline {
 };
 
 namespace {
+
+// From this many steps per call on, steps of one batch each are issued as one launch per step.
+constexpr uint32_t kFusedStepsMin = 3;
+
+// From this many samples per step on, a step's gather goes to the copy stream.
+constexpr uint64_t kWideStepSamples = 2048;
 
 bool new_event(hipEvent_t *e) { return !hip_failed(hipEventCreateWithFlags(e, hipEventDisableTiming)); }
 
@@ -56,7 +70,8 @@ int mark_wait(apex_pipeline::Mark &m, hipStream_t s)
 
 void forget_marks(apex_pipeline *p)
 {
-  p->payload_done.cur = p->tail_ready.cur = nullptr;
+  p->payload_done.cur = p->tail_ready.cur = p->drawn.cur = nullptr;
+  for (apex_pipeline::Mark &m : p->gathered) m.cur = nullptr;
   p->first_step = p->step;
 }
 
@@ -73,8 +88,10 @@ void drop_graph(apex_pipeline *p)
 void pipeline_free(apex_pipeline *p)
 {
   drop_graph(p);
-  for (hipEvent_t e : {p->payload_done.own, p->tail_ready.own, p->fork_ev, p->join_ev})
+  for (hipEvent_t e : {p->payload_done.own, p->tail_ready.own, p->drawn.own, p->fork_ev, p->join_ev})
     if (e) (void)hipEventDestroy(e);
+  for (apex_pipeline::Mark &m : p->gathered)
+    if (m.own) (void)hipEventDestroy(m.own);
   for (int i = 0; i < 2; ++i)
     if (p->streams(i)) (void)hipStreamDestroy(p->streams(i));
   delete p;
@@ -112,7 +129,12 @@ int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buff
   for (hipStream_t *s : {&p->tree, &p->add})
     ok = ok && !hip_failed(hipStreamCreateWithFlags(s, hipStreamNonBlocking));  // default priority
   ok = ok && new_event(&p->payload_done.own) && new_event(&p->tail_ready.own) && new_event(&p->fork_ev) &&
-       new_event(&p->join_ev);
+       new_event(&p->join_ev) && new_event(&p->drawn.own);
+  p->wide = (uint64_t)num_batches * k >= kWideStepSamples && depth >= 2;
+  if (p->wide) {
+    p->gathered.resize(depth);
+    for (apex_pipeline::Mark &m : p->gathered) ok = ok && new_event(&m.own);
+  }
   if (!ok) {
     pipeline_free(p);
     return APEX_ERR_HIP;
@@ -153,8 +175,27 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
   if (!p || (n && !rnd) || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
   if (first_set_out) *first_set_out = (uint32_t)(p->step % p->depth);
   const uint64_t per = (uint64_t)p->nb * p->k;
+  if (n >= kFusedStepsMin && fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) {
+    APEX_TRY(fused_steps(p->r, n, p->k, beta, rnd, new_prio, p->sets.data(), p->depth,
+                         (uint32_t)(p->step % p->depth), p->capturing, p->tree));
+    p->step += n;
+    return APEX_OK;
+  }
   for (uint32_t i = 0; i < n; ++i) {
-    const apex_batch_buffers_t &b = p->sets[p->step % p->depth];
+    const uint32_t set = (uint32_t)(p->step % p->depth);
+    const apex_batch_buffers_t &b = p->sets[set];
+    if (p->wide) {
+      APEX_TRY(mark_wait(p->gathered[set], p->tree));  // the set's last gather has read slot and mass
+      APEX_TRY(apex_replay_sample_begin(p->r, p->nb, p->k, rnd + i * per, b.key, b.slot, b.mass, b.act, b.ret, b.gacc,
+                                        p->tree));
+      APEX_TRY(mark_record(p, p->drawn, p->tree));
+      APEX_TRY(mark_wait(p->drawn, p->add));
+      APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs, p->add));
+      APEX_TRY(mark_record(p, p->gathered[set], p->add));
+      if (new_prio) APEX_TRY(apex_replay_update_priorities(p->r, per, b.key, new_prio + i * per, p->tree));
+      ++p->step;
+      continue;
+    }
     APEX_TRY(apex_replay_sample_begin(p->r, p->nb, p->k, rnd + i * per, b.key, b.slot, b.mass, b.act, b.ret, b.gacc,
                                       p->tree));
     // the gather of this batch, its weights, and the write-back of its priorities: one launch
@@ -226,6 +267,7 @@ int apex_pipeline_capture_end(apex_pipeline_t *p)
   const bool failed = hip_failed(hipStreamEndCapture(p->tree, &g));
   p->capturing = false;
   forget_marks(p);
+  p->r->second_version = 0;  // what was recorded has not run
   if (failed || rc != APEX_OK || !g) {
     if (g) (void)hipGraphDestroy(g);
     return rc != APEX_OK ? rc : APEX_ERR_HIP;
@@ -239,6 +281,7 @@ int apex_pipeline_replay(apex_pipeline_t *p, uint32_t times)
 {
   if (!p || p->capturing || !p->graph_exec) return APEX_ERR_INVALID_ARG;
   for (uint32_t i = 0; i < times; ++i) APEX_HIP(hipGraphLaunch(p->graph_exec, p->tree));
+  if (times) ++p->r->tree_version;
   return APEX_OK;
 }
 

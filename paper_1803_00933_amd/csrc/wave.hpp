@@ -10,15 +10,26 @@ constexpr int kWave = 64;
 
 __device__ __forceinline__ int lane_id() { return threadIdx.x & (kWave - 1); }
 
-// Inclusive prefix sum of one uint64 per lane.
+// One step of a prefix sum with data-parallel primitives (no LDS traffic): every lane adds the
+// value that the DPP control word routes to it, and 0 where it routes none.
+template <int kCtrl, int kRowMask>
+__device__ __forceinline__ uint64_t dpp_add_step(uint64_t v)
+{
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)v, kCtrl, kRowMask, 0xf, false);
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)(uint32_t)(v >> 32), kCtrl, kRowMask, 0xf, false);
+  return v + (((uint64_t)hi << 32) | lo);
+}
+
+// Inclusive prefix sum of one uint64 per lane: shifts by 1, 2, 4, 8 lanes inside each row of 16
+// lanes, then the last lane of row 0 (2) is added to row 1 (3), then lane 31 to rows 2 and 3.
 __device__ __forceinline__ uint64_t wave_inclusive_scan(uint64_t v)
 {
-  const int lane = lane_id();
-#pragma unroll
-  for (int d = 1; d < kWave; d <<= 1) {
-    uint64_t t = __shfl_up(v, d, kWave);
-    if (lane >= d) v += t;
-  }
+  v = dpp_add_step<0x111, 0xf>(v);  // row_shr:1
+  v = dpp_add_step<0x112, 0xf>(v);  // row_shr:2
+  v = dpp_add_step<0x114, 0xf>(v);  // row_shr:4
+  v = dpp_add_step<0x118, 0xf>(v);  // row_shr:8
+  v = dpp_add_step<0x142, 0xa>(v);  // row_bcast:15 into rows 1 and 3
+  v = dpp_add_step<0x143, 0xc>(v);  // row_bcast:31 into rows 2 and 3
   return v;
 }
 

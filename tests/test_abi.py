@@ -46,7 +46,7 @@ def test_workspace_sizes_and_argument_checks_need_no_gpu():
     assert rc == apex.OK
     P = 1 << 21
     assert storage == P * 28224 + P * 4 * 3
-    assert tree == 8 * (P + P // 64 + P // 4096)          # three levels: 2^21, 2^15, 2^9 nodes
+    assert tree == 2 * 8 * (P + P // 64 + P // 4096)      # three levels: 2^21, 2^15, 2^9 nodes; two copies
     assert scratch >= P * 4
     for bad in (apex.Config(0, 8, 4, 4, 0.6, 0, 24, 0, 0), apex.Config(9, 8, 4, 4, 0.6, 0, 24, 0, 0),
                 apex.Config(8, 8, 0, 4, 0.6, 0, 24, 0, 0), apex.Config(8, 8, 4, 4, 1.5, 0, 24, 0, 0),

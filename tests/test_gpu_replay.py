@@ -300,18 +300,25 @@ def test_captured_launches_replay_correctly():
             assert g.resync() == 0
 
 
-def test_pipeline_matches_the_plain_call_order():
-    """apex_pipeline_*: learner steps with the gathers on a second stream and add rounds whose payload
-    copy runs beside them, against the oracle doing draw, update, [add], [evict] one after the other."""
+# (batches per step, k): one batch per step is two launches on one stream; 8 x 288 samples per step is
+# above the size from which the pipeline sends a step's gather to its copy stream
+PIPELINE_STEP_SHAPES = [(1, 96), (8, 288)]
+
+
+@pytest.mark.parametrize("nb,k", PIPELINE_STEP_SHAPES)
+def test_pipeline_matches_the_plain_call_order(nb, k):
+    """apex_pipeline_*: learner steps (for steps of several batches: with the gathers on the second
+    stream) and add rounds whose payload copy runs beside them, against the oracle doing draw, update,
+    [add], [evict] one after the other."""
     from paper_1803_00933_amd import apex, synth
-    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=96)
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=k)
     rng = np.random.default_rng(14)
     g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
     add_both(g, o, rng, w.capacity)
     depth, n_steps, per_round = 3, 24, 6
-    pipe = apex.Pipeline(g, depth, 1, w.k)
-    rnd = rng.integers(0, U64, (n_steps, w.k), dtype=np.uint64)
-    newp = rng.lognormal(0, 1, (n_steps, w.k)).astype(F32)
+    pipe = apex.Pipeline(g, depth, nb, w.k)
+    rnd = rng.integers(0, U64, (n_steps, nb * w.k), dtype=np.uint64)
+    newp = rng.lognormal(0, 1, (n_steps, nb * w.k)).astype(F32)
     d_rnd, d_newp = dev(rnd), dev(newp)
     S, T = w.streams, w.chunk
     scratch = [torch.empty(S * T, dtype=torch.float32, device="cuda:0") for _ in range(3)]
@@ -330,7 +337,7 @@ def test_pipeline_matches_the_plain_call_order():
                                   dd["obs"], dd["act"], *scratch) == 0
         rc, first = pipe.steps(1, 0.4, d_rnd[s], d_newp[s])
         assert rc == 0 and first == s % depth
-        rco, oo = o.sample(1, w.k, 0.4, rnd[s])
+        rco, oo = o.sample(nb, w.k, 0.4, rnd[s])
         o.update_priorities(oo["key"], newp[s])
         refs.append(oo)
         if (s + 1) % per_round == 0:
@@ -353,8 +360,8 @@ def test_pipeline_matches_the_plain_call_order():
         assert_sample_equal(out, oo)
     check_gpu_tree(g, o)
     # several steps in one call, no synchronisation in between; the last `depth` sets are checked
-    rnd2 = rng.integers(0, U64, (7, w.k), dtype=np.uint64)
-    newp2 = rng.lognormal(0, 1, (7, w.k)).astype(F32)
+    rnd2 = rng.integers(0, U64, (7, nb * w.k), dtype=np.uint64)
+    newp2 = rng.lognormal(0, 1, (7, nb * w.k)).astype(F32)
     d2 = (dev(rnd2), dev(newp2))
     torch.cuda.synchronize()
     assert pipe.fork() == 0
@@ -364,7 +371,7 @@ def test_pipeline_matches_the_plain_call_order():
     torch.cuda.synchronize()
     refs2 = []
     for s in range(7):
-        rco, oo = o.sample(1, w.k, 0.4, rnd2[s])
+        rco, oo = o.sample(nb, w.k, 0.4, rnd2[s])
         o.update_priorities(oo["key"], newp2[s])
         refs2.append(oo)
     for s in range(7 - depth, 7):
@@ -373,18 +380,19 @@ def test_pipeline_matches_the_plain_call_order():
     pipe.close()
 
 
-def test_pipeline_graph_replays():
+@pytest.mark.parametrize("nb,k", PIPELINE_STEP_SHAPES)
+def test_pipeline_graph_replays(nb, k):
     """One cycle (an add round beside six learner steps, then eviction) captured as a HIP graph by the
     pipeline and replayed; every replay is checked against the oracle, with eager work in between."""
     from paper_1803_00933_amd import apex, synth
-    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=96)
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=k)
     rng = np.random.default_rng(15)
     g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
     add_both(g, o, rng, w.capacity)
     depth, n_steps = 3, 6
-    pipe = apex.Pipeline(g, depth, 1, w.k)
-    rnd = rng.integers(0, U64, (n_steps, w.k), dtype=np.uint64)
-    newp = rng.lognormal(0, 1, (n_steps, w.k)).astype(F32)
+    pipe = apex.Pipeline(g, depth, nb, w.k)
+    rnd = rng.integers(0, U64, (n_steps, nb * w.k), dtype=np.uint64)
+    newp = rng.lognormal(0, 1, (n_steps, nb * w.k)).astype(F32)
     d_rnd, d_newp = dev(rnd), dev(newp)
     S, T = w.streams, w.chunk
     scratch = [torch.empty(S * T, dtype=torch.float32, device="cuda:0") for _ in range(3)]
@@ -403,7 +411,7 @@ def test_pipeline_graph_replays():
     def oracle_cycle():
         res = []
         for s in range(n_steps):
-            res.append(o.sample(1, w.k, 0.4, rnd[s])[1])
+            res.append(o.sample(nb, w.k, 0.4, rnd[s])[1])
             o.update_priorities(res[-1]["key"], newp[s])
         ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
                                       w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
@@ -439,6 +447,61 @@ def test_pipeline_graph_replays():
         assert_sample_equal(pipe.sets[s % depth], res[s])
     assert g.resync() == 0
     check_gpu_tree(g, o)
+    pipe.close()
+
+
+@pytest.mark.parametrize("P,C,k,ob", [
+    (4096, 3000, 96, 4224),          # one tree level
+    (40_000, 30_000, 200, 4112),     # two levels, ragged tails, partial last vector chunk
+    (400_000, 300_000, 512, 4224),   # three levels
+    (5000, 4000, 1024, 32768),       # as many samples as a workgroup has lanes, largest fused row
+    (5000, 4000, 1, 4224),           # batches of one
+])
+def test_one_launch_per_learner_step(P, C, k, ob):
+    """Sequences of learner steps issued as one launch per step (draw of the next batch inside the launch
+    that gathers and writes back the current one, two copies of the tree): every batch of every sequence
+    against the oracle doing draw, update, draw, update, with other operations between the sequences.
+    Priorities are heavy-tailed so that batches draw the same slot several times."""
+    from paper_1803_00933_amd import apex
+    rng = np.random.default_rng(P + k)
+    g, o = make_pair(C, P, ob, 4)
+    heavy = lambda rng, n: (rng.pareto(0.4, n) + 1e-3)
+    while o.size < C:
+        assert add_both(g, o, rng, min(20_000, C - o.size), heavy) == 0
+    depth, n = 9, 8
+    pipe = apex.Pipeline(g, depth, 1, k)
+    for seq in range(6):
+        rnd = rng.integers(0, U64, (n, k), dtype=np.uint64)
+        newp = heavy(rng, (n, k)).astype(F32)
+        newp[rng.random((n, k)) < 0.1] = 0.0
+        with_update = seq != 3
+        d_rnd, d_newp = dev(rnd), dev(newp)
+        torch.cuda.synchronize()
+        assert pipe.fork() == 0
+        rc, first = pipe.steps(n, 0.5, d_rnd, d_newp if with_update else None)
+        assert rc == 0
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        dup = 0
+        for i in range(n):
+            rco, oo = o.sample(1, k, 0.5, rnd[i])
+            assert rco == 0
+            dup += k - len(np.unique(oo["slot"]))
+            if with_update:
+                assert o.update_priorities(oo["key"], newp[i]) == 0
+            assert_sample_equal(pipe.sets[(first + i) % depth], oo)
+        assert k < 64 or dup > 0          # the case the test is about occurs
+        check_gpu_tree(g, o)
+        # other operations between the sequences: they change the first copy of the tree only
+        if seq % 2 == 0:
+            assert add_both(g, o, rng, min(500, P - o.size), heavy) == 0
+            assert g.evict() == o.evict()
+        else:
+            oo = sample_both(g, o, rng, 1, min(k, 64))
+            pr = heavy(rng, len(oo["key"])).astype(F32)
+            assert g.update_priorities(dev(oo["key"]), dev(pr)) == o.update_priorities(oo["key"], pr) == 0
+    st = g.stats()
+    assert (st["n_clamped"], st["n_stale_dropped"]) == (o.n_clamped, o.n_stale)
     pipe.close()
 
 
