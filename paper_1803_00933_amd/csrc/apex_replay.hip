@@ -306,8 +306,11 @@ int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio,
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
   if (count) {
     hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+    const bool both = r->second_version == r->tree_version;
     ++r->tree_version;
-    add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), count, prio, r->qp);
+    if (both) r->second_version = r->tree_version;
+    add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->tv2, both, r->state(), count,
+                                                                              prio, r->qp);
     advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), 0, count);
     APEX_HIP(hipGetLastError());
   }
@@ -325,9 +328,12 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
   return apex_replay_add_publish(r, count, prio, first_key_out, hip_stream);
 }
 
-int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k, const uint64_t *rnd,
-                             uint64_t *key_out, uint32_t *slot_out, uint64_t *mass_out, void *act_out, float *ret_out,
-                             float *gacc_out, void *hip_stream)
+namespace {
+
+// first_prio, first_dq: see SampleArgs (null for a plain draw).
+int sample_begin_impl(apex_replay *r, uint32_t num_batches, uint32_t k, const uint64_t *rnd, uint64_t *key_out,
+                      uint32_t *slot_out, uint64_t *mass_out, void *act_out, float *ret_out, float *gacc_out,
+                      const float *first_prio, uint64_t *first_dq, hipStream_t stream)
 {
   if (!r || !num_batches || !k || !rnd || !slot_out || !mass_out) return APEX_ERR_INVALID_ARG;
   if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
@@ -335,12 +341,10 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
   const uint64_t size = r->tail - r->head;
   if (size < r->cfg.min_size_to_sample) return APEX_ERR_NOT_READY;
   if (size == 0) return APEX_ERR_EMPTY;
-  SampleArgs a;
+  SampleArgs a{};
   a.tv = r->tv;
   a.st = r->state();
   a.k = k;
-  a.k_dev = nullptr;
-  a.gen = nullptr;
   a.rnd = rnd;
   a.key_out = key_out;
   a.slot_out = slot_out;
@@ -352,12 +356,25 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
   a.act_out = static_cast<uint8_t *>(act_out);
   a.ret_out = ret_out;
   a.gacc_out = gacc_out;
+  a.first_prio = first_prio;
+  a.first_dq = first_dq;
+  a.qp = r->qp;
+  a.counters = r->state();
   const uint32_t waves = 4;
   const size_t lds = ((size_t)r->tv.n_top + waves) * sizeof(uint64_t);
-  sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds,
-                          static_cast<hipStream_t>(hip_stream)>>>(a);
+  sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds, stream>>>(a);
   APEX_HIP(hipGetLastError());
   return APEX_OK;
+}
+
+}  // namespace
+
+int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k, const uint64_t *rnd,
+                             uint64_t *key_out, uint32_t *slot_out, uint64_t *mass_out, void *act_out, float *ret_out,
+                             float *gacc_out, void *hip_stream)
+{
+  return sample_begin_impl(r, num_batches, k, rnd, key_out, slot_out, mass_out, act_out, ret_out, gacc_out, nullptr,
+                           nullptr, static_cast<hipStream_t>(hip_stream));
 }
 
 namespace {
@@ -417,10 +434,10 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
   const uint64_t row_bytes = r->cfg.obs_bytes;
   const uint64_t vpr = row_bytes / sizeof(u32x4);
   if (num_batches != 1 || k > kStepMaxK || depth < 3 || depth > kStepSets || r->tv.n_top > kStepMaxTop) return false;
-  if (row_bytes % sizeof(u32x4) || vpr <= 256 || vpr > (uint64_t)kLongCopyThreads * kLongCopyUnroll) return false;
+  if (row_bytes % sizeof(u32x4) || vpr <= 256 || vpr > (uint64_t)kStepThreads * kStepUnroll) return false;
   if ((uintptr_t)r->obs() & 15) return false;
   for (uint32_t i = 0; i < depth; ++i)
-    if ((uintptr_t)sets[i].obs & 15) return false;
+    if (((uintptr_t)sets[i].obs | (uintptr_t)sets[i].slot) & 15) return false;
   return true;
 }
 
@@ -431,16 +448,15 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
   const auto idx = [&](uint32_t i) { return (first_set + i) % depth; };
   const auto set = [&](uint32_t i) -> const apex_batch_buffers_t & { return sets[idx(i)]; };
   const apex_batch_buffers_t &b0 = set(0);
-  int rc = apex_replay_sample_begin(r, 1, k, rnd, b0.key, b0.slot, b0.mass, b0.act, b0.ret, b0.gacc, stream);
+  int rc = sample_begin_impl(r, 1, k, rnd, b0.key, b0.slot, b0.mass, b0.act, b0.ret, b0.gacc, new_prio,
+                             new_prio ? r->stepq(idx(0)) : nullptr, stream);
   if (rc != APEX_OK) return rc;
-  if (new_prio) {
-    if (always_copy || r->second_version != r->tree_version)
-      copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
-    first_deltas_kernel<<<dim3(blocks_for(k, 256)), dim3(256), 0, stream>>>(new_prio, b0.mass, r->stepq(idx(0)), k,
-                                                                            r->qp, r->state());
+  if (new_prio && (always_copy || r->second_version != r->tree_version)) {
+    copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
     APEX_HIP(hipGetLastError());
   }
-  const size_t lds = ((size_t)r->tv.n_top + k + kFanout) * 8 + (size_t)k * 4;
+  const size_t k_pad = round_up(k, 8);
+  const size_t lds = (round_up(r->tv.n_top, kFanout) + k_pad + kFanout) * 8 + k_pad * 4;
   for (uint32_t i = 0; i < n; ++i) {
     const apex_batch_buffers_t &b = set(i);
     const TreeView &rd = (new_prio && (i & 1)) ? r->tv2 : r->tv;
@@ -483,15 +499,10 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
         a.next_dq = r->stepq(idx(i + 1));
       }
     }
-    learner_step_kernel<u32x4, kLongCopyUnroll><<<dim3(k), dim3(kLongCopyThreads), lds, stream>>>(a);
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll><<<dim3(k), dim3(kStepThreads), lds, stream>>>(a);
   }
-  if (new_prio) {
-    // the copy read by the last launch is one batch behind
-    const TreeView &behind = ((n - 1) & 1) ? r->tv2 : r->tv;
-    const apex_batch_buffers_t &b = set(n - 1);
-    apply_deltas_kernel<<<dim3(blocks_for(k, 256)), dim3(256), 0, stream>>>(behind, b.slot, r->stepq(idx(n - 1)), k);
-    r->second_version = ++r->tree_version;
-  }
+  // (the last launch draws nothing and has brought both copies up to date)
+  if (new_prio) r->second_version = ++r->tree_version;
   APEX_HIP(hipGetLastError());
   return APEX_OK;
 }
@@ -597,8 +608,10 @@ int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream)
   if (evicted_out) *evicted_out = e;
   if (e == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  const bool both = r->second_version == r->tree_version;
   ++r->tree_version;
-  evict_leaves_kernel<<<dim3(blocks_for(e, 256)), dim3(256), 0, stream>>>(r->tv, r->state(), e);
+  if (both) r->second_version = r->tree_version;
+  evict_leaves_kernel<<<dim3(blocks_for(e, 256)), dim3(256), 0, stream>>>(r->tv, r->tv2, both, r->state(), e);
   advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), e, 0);
   APEX_HIP(hipGetLastError());
   r->head += e;

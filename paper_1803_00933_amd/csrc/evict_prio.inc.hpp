@@ -397,7 +397,7 @@ int apex_pe_sample(apex_pe_replay_t *r, uint32_t num_batches, uint32_t k, float 
     return APEX_ERR_TOO_LARGE;
   if (r->size() == 0) return APEX_ERR_EMPTY;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  SampleArgs a;
+  SampleArgs a{};
   a.tv = r->v.ts;
   a.st = &r->state()->base;
   a.k = k;
@@ -459,7 +459,7 @@ int apex_pe_evict(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uin
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   PeState *st = r->state();
   pe_begin_evict_kernel<<<dim3(1), dim3(64), 0, stream>>>(st, e);
-  SampleArgs a;
+  SampleArgs a{};
   a.tv = r->v.te;
   a.st = &st->base;
   a.k = 0;

@@ -48,7 +48,9 @@ __device__ __forceinline__ void add_to_ancestors(const TreeView &tv, uint64_t sl
 // Same, for a wave whose active lanes hold neighbouring slots (adds, evictions): lanes under one
 // level-1 node are summed first, so each node receives one atomic per wave instead of up to 64.
 // Must be called by all 64 lanes; `active` marks the lanes that carry a delta.
-__device__ __forceinline__ void add_to_ancestors_grouped(const TreeView &tv, bool active, uint64_t slot, uint64_t delta)
+// second: another copy of the same tree that receives the same sums, or null.
+__device__ __forceinline__ void add_to_ancestors_grouped(const TreeView &tv, bool active, uint64_t slot, uint64_t delta,
+                                                         const TreeView *second = nullptr)
 {
   const int lane = lane_id();
   const uint64_t node1 = slot >> kFanoutLog2;
@@ -62,6 +64,7 @@ __device__ __forceinline__ void add_to_ancestors_grouped(const TreeView &tv, boo
       uint64_t idx = node;
       for (uint32_t l = 1; l < tv.nlev; ++l) {
         atomic_add_u64(tv.level[l] + idx, sum);
+        if (second) atomic_add_u64(second->level[l] + idx, sum);
         idx >>= kFanoutLog2;
       }
     }
@@ -405,7 +408,9 @@ __global__ __launch_bounds__(256) void copy_rows_short_kernel(const uint8_t *__r
 // --------------------------------------------------------------------------------------------
 // add: masses of the new keys, and their sums into the upper levels
 // --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, DeviceState *__restrict__ st, uint64_t count,
+// both: the second copy of the tree (tv2) is in step with the first and is kept so.
+__global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, TreeView tv2, bool both,
+                                                         DeviceState *__restrict__ st, uint64_t count,
                                                          const float *__restrict__ prio, QuantParams qp)
 {
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -416,14 +421,16 @@ __global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, DeviceStat
     slot = (st->tail + i) % tv.P;
     q = quantise_priority(prio[i], qp, &clamped);
     tv.level[0][slot] = q;  // the slot was empty (mass 0): the ring is never over-filled
+    if (both) tv2.level[0][slot] = q;
   }
-  add_to_ancestors_grouped(tv, active, slot, q);
+  add_to_ancestors_grouped(tv, active, slot, q, both ? &tv2 : nullptr);
   const uint64_t nc = __popcll(__ballot(clamped));
   if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
 }
 
 // evict: zero the masses of the e oldest keys and take them out of the upper levels
-__global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, const DeviceState *__restrict__ st, uint64_t e)
+__global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, TreeView tv2, bool both,
+                                                           const DeviceState *__restrict__ st, uint64_t e)
 {
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const bool active = i < e;
@@ -432,8 +439,9 @@ __global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, const De
     slot = (st->head + i) % tv.P;
     old = tv.level[0][slot];
     tv.level[0][slot] = 0;
+    if (both) tv2.level[0][slot] = 0;
   }
-  add_to_ancestors_grouped(tv, active, slot, 0 - old);
+  add_to_ancestors_grouped(tv, active, slot, 0 - old, both ? &tv2 : nullptr);
 }
 
 // One thread, after the kernels that needed the old values.
@@ -516,6 +524,12 @@ struct SampleArgs {
   const float *ret, *gacc;
   uint8_t *act_out;
   float *ret_out, *gacc_out;
+  // not null (one batch only): the new priorities of the batch being drawn; their mass differences
+  // Q(prio) - mass as drawn go to first_dq, for a sequence of fused learner steps
+  const float *first_prio;
+  uint64_t *first_dq;
+  QuantParams qp;
+  DeviceState *counters;
 };
 
 // Pending changes of leaf masses that the tree in memory does not hold yet (LDS): a descent adds
@@ -671,7 +685,16 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
   if (j < k) {
     const uint64_t w = total / k;                           // stratum width
     const uint64_t x = (uint64_t)j * w + __umul64hi(u, w);  // point inside stratum j
-    write_drawn(a, o, wave_descend<false>(tv, pre, total, x, PendingDeltas{}), head);
+    const Drawn dr = wave_descend<false>(tv, pre, total, x, PendingDeltas{});
+    write_drawn(a, o, dr, head);
+    if (a.first_prio) {
+      bool clamped;
+      const uint64_t q = quantise_priority(a.first_prio[o], a.qp, &clamped);
+      if (lane_id() == 0) {
+        a.first_dq[o] = q - dr.mass;
+        if (clamped) atomic_add_u64(&a.counters->n_clamped, 1);
+      }
+    }
   }
 }
 
@@ -683,11 +706,12 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
 // A draw may not read a tree that other workgroups of the same launch are writing, so the memory
 // keeps two copies of the sum tree.  The launch reads one of them, which holds every write-back
 // up to batch i-1, and each workgroup adds the changes of batch i to what it reads from it: the
-// k pairs (slot, new mass - old mass) are worked out by every workgroup and held in LDS.  The
-// same changes, and those of batch i-1 which the other copy still lacks, go into the other copy
-// with atomics, one pair per workgroup; the next launch reads that copy.  The two copies swap
-// roles from launch to launch, and the last launch of a sequence is followed by
-// apply_deltas_kernel on the copy that is one batch behind.
+// k pairs (slot, new mass - old mass) are loaded by every workgroup and held in LDS (the new
+// mass of a pair is worked out once, by the wave that draws it).  The same changes, and those of
+// batch i-1 which the other copy still lacks, go into the other copy with atomics, one pair per
+// workgroup; the next launch reads that copy.  The two copies swap roles from launch to launch.
+// The last launch of a sequence draws nothing, so nothing reads a tree in it, and it brings
+// both copies up to date.
 //
 // Within a batch the drawn slots do not decrease (the strata are ordered), so the pairs that
 // share a slot are neighbours and the last of them is the one that counts.
@@ -707,6 +731,11 @@ __device__ __forceinline__ void wave_lds_sync()
   __builtin_amdgcn_wave_barrier();
 }
 
+// Workgroups of 8 waves, 4 vectors per lane: as fast as 16 waves x 2 when the kernel runs alone, and the
+// chip then holds the whole batch in half of its wave slots, which leaves room for the workgroups of
+// an add round's payload copy on the other stream (measured: 16.9 instead of 18.4 us per step there).
+constexpr int kStepThreads = 512;
+constexpr int kStepUnroll = 4;
 constexpr uint32_t kStepMaxK = 1024;    // pairs per batch that the fused step handles
 constexpr uint32_t kStepMaxTop = 1024;  // top-level nodes that its single drawing wave stages
 
@@ -714,7 +743,7 @@ struct StepArgs {
   // gather of batch i: row j of dst = row slot[j] of src; the small columns likewise
   const uint8_t *src;
   uint8_t *dst;
-  uint32_t vecs_per_row;  // <= kLongCopyUnroll * blockDim
+  uint32_t vecs_per_row;  // <= kStepUnroll * kStepThreads
   uint64_t row_bytes;
   const uint8_t *act;
   uint32_t act_bytes;
@@ -735,79 +764,134 @@ struct StepArgs {
   DeviceState *st;
 };
 
+typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
+
 // The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier:
 // pending changes and the top level into LDS, the changes added to the top level, prefix sums,
-// descent.  LDS, in words of 8 bytes: n_top + k + 64, then k words of 4 bytes.
+// descent.  Every lane takes eight consecutive pairs and eight consecutive top-level nodes per
+// pass, with 16-byte loads.
+// LDS, in words of 8 bytes: round_up(n_top, 64) + round_up(k, 8) + 64, then round_up(k, 8) words of 4 bytes.
 __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *lds)
 {
   const TreeView &rd = a.next.tv;
   const uint32_t n_top = rd.n_top, lane = lane_id();
-  const uint32_t kp = a.dq ? a.k : 0;
+  const uint32_t n_top_pad = (n_top + kFanout - 1) & ~(kFanout - 1);  // the level is zero-padded to this in memory
+  const uint32_t kp = a.dq ? a.k : 0, k_pad = (a.k + 7) & ~7u;
   uint64_t *pre = lds;
-  uint64_t *p_delta = pre + n_top;
-  uint64_t *p_row = p_delta + a.k;
+  uint64_t *p_delta = pre + n_top_pad;
+  uint64_t *p_row = p_delta + k_pad;
   uint32_t *p_slot = reinterpret_cast<uint32_t *>(p_row + kFanout);
   __builtin_amdgcn_s_setprio(2);
 
   const uint64_t un = a.next.rnd[row];
   const float prio_next = a.next_prio ? a.next_prio[row] : 0.0f;
   const uint64_t head = a.next.st->head;
-  // pending changes: a pair counts unless the next pair has the same slot (eight pairs per lane in flight)
-  for (uint32_t j0 = 0; j0 < kp; j0 += 8 * kWave) {
-    uint32_t sj[8], sn[8];
-    uint64_t dj[8];
+  const uint32_t sh_top = kFanoutLog2 * (rd.nlev - 1);
+  const uint64_t *top = rd.level[rd.nlev - 1];
+
+  // the first 512 nodes of the top level are requested before anything else
+  uint64_t v_top[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (8 * lane < n_top_pad) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const uint32_t j = j0 + t * kWave + lane;
-      sj[t] = j < kp ? a.slot[j] : 0xffffffffu;
-      sn[t] = j + 1 < kp ? a.slot[j + 1] : 0xfffffffeu;
-      dj[t] = j < kp ? a.dq[j] : 0;
-    }
-#pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const uint32_t j = j0 + t * kWave + lane;
-      if (j < kp) {
-        p_slot[j] = sj[t];
-        p_delta[j] = sn[t] != sj[t] ? dj[t] : 0;
-      }
+    for (int t = 0; t < 8; t += 2) {
+      const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + 8 * lane + t);
+      v_top[t] = v2.x, v_top[t + 1] = v2.y;
     }
   }
-  const uint64_t *top = rd.level[rd.nlev - 1];
-  for (uint32_t i0 = 0; i0 < n_top; i0 += 8 * kWave) {
-    uint64_t v[8];
+
+  // ---- pending changes of this batch -> LDS; a pair counts unless the next pair has the same slot
+  for (uint32_t c0 = 0; c0 < kp; c0 += 8 * kWave) {
+    const uint32_t j0 = c0 + 8 * lane;
+    uint32_t sj[9];
+    uint64_t dj[8];
+    if (j0 + 8 <= kp) {
+      const u32x4 s0 = *reinterpret_cast<const u32x4 *>(a.slot + j0), s1 = *reinterpret_cast<const u32x4 *>(a.slot + j0 + 4);
+      sj[0] = s0.x, sj[1] = s0.y, sj[2] = s0.z, sj[3] = s0.w, sj[4] = s1.x, sj[5] = s1.y, sj[6] = s1.z, sj[7] = s1.w;
+      sj[8] = j0 + 8 < kp ? a.slot[j0 + 8] : 0xfffffffeu;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const uint32_t i = i0 + t * kWave + lane;
-      v[t] = i < n_top ? top[i] : 0;
+      for (int t = 0; t < 8; t += 2) {
+        const u64x2 d2 = *reinterpret_cast<const u64x2 *>(a.dq + j0 + t);
+        dj[t] = d2.x, dj[t + 1] = d2.y;
+      }
+    } else {
+#pragma unroll
+      for (int t = 0; t < 9; ++t) sj[t] = j0 + t < kp ? a.slot[j0 + t] : 0xfffffffeu - (t & 1);
+#pragma unroll
+      for (int t = 0; t < 8; ++t) dj[t] = j0 + t < kp ? a.dq[j0 + t] : 0;
     }
+    if (j0 < k_pad) {
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      const uint32_t i = i0 + t * kWave + lane;
-      if (i < n_top) pre[i] = v[t];
+      for (int t = 0; t < 8; ++t) {
+        p_slot[j0 + t] = j0 + t < kp ? sj[t] : 0xffffffffu;
+        p_delta[j0 + t] = (j0 + t < kp && sj[t + 1] != sj[t]) ? dj[t] : 0;
+      }
     }
   }
   bool clamped = false;
   const uint64_t q_next = a.next_prio ? quantise_priority(prio_next, a.qp, &clamped) : 0;
-  wave_lds_sync();
-  const uint32_t sh_top = kFanoutLog2 * (rd.nlev - 1);
-  for (uint32_t j = lane; j < kp; j += kWave) {
-    const uint64_t dv = p_delta[j];
-    if (dv) atomicAdd(reinterpret_cast<unsigned long long *>(pre + (p_slot[j] >> sh_top)), (unsigned long long)dv);
+
+  // ---- top level: exclusive prefix sums of (masses + pending changes) -> LDS
+  if (kp) {  // the changes land on nodes of other lanes: add them in LDS
+    if (8 * lane < n_top_pad) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) pre[8 * lane + t] = v_top[t];
+    }
+    for (uint32_t i0 = 8 * (kWave + lane); i0 < n_top_pad; i0 += 8 * kWave) {
+#pragma unroll
+      for (int t = 0; t < 8; t += 2) {
+        const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + i0 + t);
+        pre[i0 + t] = v2.x, pre[i0 + t + 1] = v2.y;
+      }
+    }
+    wave_lds_sync();
+    for (uint32_t j0 = 0; j0 < kp; j0 += 8 * kWave) {
+      uint64_t dv[8];
+      uint32_t ss[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        const uint32_t j = j0 + t * kWave + lane;
+        dv[t] = j < kp ? p_delta[j] : 0;
+        ss[t] = j < kp ? p_slot[j] : 0;
+      }
+#pragma unroll
+      for (int t = 0; t < 8; ++t)
+        if (dv[t]) atomicAdd(reinterpret_cast<unsigned long long *>(pre + (ss[t] >> sh_top)), (unsigned long long)dv[t]);
+    }
+    wave_lds_sync();
   }
-  wave_lds_sync();
-  // exclusive prefix sums in place: a contiguous run of `per` nodes per lane
-  const uint32_t per = (n_top + kWave - 1) / kWave;
-  const uint32_t lo = min(lane * per, n_top), hi = min(lo + per, n_top);
-  uint64_t mine = 0;
-  for (uint32_t i = lo; i < hi; ++i) mine += pre[i];
-  const uint64_t incl = wave_inclusive_scan(mine);
-  const uint64_t total = __shfl(incl, kWave - 1, kWave);
-  uint64_t run = incl - mine;
-  for (uint32_t i = lo; i < hi; ++i) {
-    const uint64_t v = pre[i];
-    pre[i] = run;
-    run += v;
+  uint64_t carry = 0;
+  for (uint32_t c0 = 0; c0 < n_top_pad; c0 += 8 * kWave) {
+    const uint32_t i0 = c0 + 8 * lane;
+    const bool have = i0 < n_top_pad;
+    uint64_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    if (have && kp) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = pre[i0 + t];
+    } else if (have && c0 == 0) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[t] = v_top[t];
+    } else if (have) {
+#pragma unroll
+      for (int t = 0; t < 8; t += 2) {
+        const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + i0 + t);
+        v[t] = v2.x, v[t + 1] = v2.y;
+      }
+    }
+    uint64_t mine = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) mine += v[t];
+    const uint64_t incl = wave_inclusive_scan(mine);
+    uint64_t run = carry + incl - mine;
+    if (have) {
+#pragma unroll
+      for (int t = 0; t < 8; ++t) {
+        pre[i0 + t] = run;
+        run += v[t];
+      }
+    }
+    carry += __shfl(incl, kWave - 1, kWave);
   }
+  const uint64_t total = carry;
   wave_lds_sync();
 
   const uint64_t w = total / a.next.k;
@@ -830,8 +914,8 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
 //   wave 2       gathers the action bytes of the row
 //   wave 3       in the first ceil(k / 64) workgroups: importance weights of 64 samples
 // Dynamic LDS: see draw_in_first_wave.
-template <typename Vec, int kUnroll>
-__global__ __launch_bounds__(kLongCopyThreads) void learner_step_kernel(StepArgs a)
+template <typename Vec, int kThreads, int kUnroll>
+__global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
 {
   extern __shared__ uint64_t lds[];
   const uint32_t row = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
@@ -843,6 +927,10 @@ __global__ __launch_bounds__(kLongCopyThreads) void learner_step_kernel(StepArgs
     if (first) return;
   }
   const uint32_t my_slot = a.slot[row];
+  // The drawing wave's first loads are to reach the memory pipeline ahead of the row loads: the
+  // other waves wait a few hundred cycles (longer when the pending changes are loaded as well).
+  if (draw && write_back) __builtin_amdgcn_s_sleep(12);
+  else if (draw) __builtin_amdgcn_s_sleep(4);
 
   // ---- small loads first, so that nothing that uses them waits for the row
   const bool carrier = write_back && tid == kWave;
@@ -897,7 +985,10 @@ __global__ __launch_bounds__(kLongCopyThreads) void learner_step_kernel(StepArgs
   }
 
   if (carrier) {
-    if (pc_next != my_slot) add_delta(a.wr, my_slot, pc_dq);
+    if (pc_next != my_slot) {
+      add_delta(a.wr, my_slot, pc_dq);
+      if (!draw) add_delta(a.next.tv, my_slot, pc_dq);  // last launch of a sequence: nothing reads the other copy
+    }
     if (pp_next != pp_slot) add_delta(a.wr, pp_slot, pp_dq);  // pp_dq = 0 without a batch before
   }
   if (tid == kWave + 1 && a.ret_out) a.ret_out[row] = small;
@@ -923,27 +1014,6 @@ __global__ __launch_bounds__(kLongCopyThreads) void learner_step_kernel(StepArgs
   if (wave == 2 && a.act_out && !act_early)  // long action rows: after the row, which they would hold up
     for (uint32_t by = lane; by < a.act_bytes; by += kWave)
       a.act_out[(uint64_t)row * a.act_bytes + by] = a.act[(uint64_t)my_slot * a.act_bytes + by];
-}
-
-// Mass differences of the first batch of a sequence of fused steps: Q(prio) - mass as drawn.
-__global__ __launch_bounds__(256) void first_deltas_kernel(const float *prio, const uint64_t *mass, uint64_t *dq,
-                                                           uint32_t k, QuantParams qp, DeviceState *st)
-{
-  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  bool clamped = false;
-  if (j < k) dq[j] = quantise_priority(prio[j], qp, &clamped) - mass[j];
-  const uint64_t nc = __popcll(__ballot(clamped));
-  if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
-}
-
-// Adds the changes of one batch (see learner_step_kernel) to a copy of the tree.
-__global__ __launch_bounds__(256) void apply_deltas_kernel(TreeView tv, const uint32_t *slot, const uint64_t *dq,
-                                                           uint32_t k)
-{
-  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= k) return;
-  const uint32_t sj = slot[j];
-  if (j + 1 == k || slot[j + 1] != sj) add_delta(tv, sj, dq[j]);
 }
 
 // dst[i] = src[i]: brings the second copy of the tree up to date
