@@ -27,12 +27,13 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 ADD_EVERY, EVICT_EVERY = 25, 100
 
-# HBM bytes per launch of the gather(+weights+update) kernel, from two rocprofv3 --pmc runs of this
-# script (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads
-# for a plain 508,032,000-byte copy in the same run (FETCH_SIZE reads half the bytes, WRITE_SIZE all):
-#   (7178.3 * 1.99982 + 14264.7 * 1.0) KiB.   See profiles/gather_atari_hbm_traffic.txt.
-MEASURED_GATHER_TRAFFIC_BYTES = int((7178.3 * 496125.0 / 248084.9 + 14264.7) * 1024)
-
+# HBM bytes per launch of the learner-step kernel, from two rocprofv3 --pmc runs of this script
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads for a
+# plain 508,032,000-byte copy in the same run (FETCH_SIZE reads half the bytes, WRITE_SIZE all).
+# See profiles/learner_step_atari_hbm_traffic.txt.
+MEASURED_STEP_TRAFFIC_BYTES = None
+STEP_ALGORITHMIC_BYTES = 512 * 57030   # per learner step of batch 512: gather read + write, sample outputs,
+                                       # descent reads, update read-modify-writes (57,030 B per transition)
 
 def dev(a):
     import torch
@@ -201,35 +202,21 @@ class GpuJob:
         torch.cuda.synchronize()
         return time.perf_counter() - t0, t_host
 
-    def gather_kernel_ms(self, sets=64, replays=8):
-        """Average duration of the dominant kernel as it runs in the timed loop: the launch that gathers the
-        512 frame stacks of one batch, with that batch's importance weights and the write-back of its
-        priorities riding along.  `sets` batches are drawn first, so that every launch reads and writes other
-        rows (nothing is served from the 256 MB memory-side cache); the launches are then captured once and
-        replayed, so that the host's launch rate does not enter the figure; HIP events on the launch stream."""
-        torch, w = self.torch, self.w
-        pipe = self.apex.Pipeline(self.rep, sets, 1, w.k)
-        assert pipe.fork() == 0
-        assert pipe.steps(sets, w.beta, self.rnd[:sets], None)[0] == 0
-        assert pipe.join() == 0
-        s = torch.cuda.Stream()
-        torch.cuda.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=s):
-            for i in range(sets):
-                o = pipe.sets[i]
-                assert self.rep.sample_finish_writeback(1, w.k, w.beta, o, self.td[i]) == 0
-        graph.replay()
+    def step_kernel_us(self, first, count):
+        """Average time per launch of the dominant kernel as it runs in the timed loop: the learner-step launch
+        (gather of the 512 frame stacks of one batch, its importance weights, the write-back of its priorities
+        and the draw of the next batch).  `count` launches back to back on the pipeline's stream, every one
+        with other rows (nothing is served from the 256 MB memory-side cache); HIP events on the stream that
+        the pipeline's stream is forked from and joined to, so the figure contains the gaps between the
+        launches and, once per `count` launches, the standalone first draw."""
+        torch = self.torch
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
-        for _ in range(replays):
-            graph.replay()
+        self.run_pipelined_learner_only(first, count)
         e1.record()
         torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / (sets * replays)
-        pipe.close()
-        return ms
+        return e0.elapsed_time(e1) / count * 1e3
 
 
 def op_timings(job):
@@ -277,7 +264,81 @@ def op_timings(job):
     assert rc == 0 and e == n_add * w.add_count
     out["add_round_18000_incl_nstep"] = ev[0].elapsed_time(ev[1]) / n_add * 1e3
     out["evict_%d" % e] = ev[1].elapsed_time(ev[2]) * 1e3
+    # the payload copy of an add round alone (rows into free ring slots; nothing is published)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for i in range(n_add):
+        assert rep.add_payload(w.add_count, job.obs_stage) == 0
+    ev[1].record()
+    torch.cuda.synchronize()
+    out["add_payload_18000"] = ev[0].elapsed_time(ev[1]) / n_add * 1e3
+    out["add_payload_GBps"] = 2 * w.add_count * w.obs_bytes / (out["add_payload_18000"] * 1e-6) / 1e9
     return out
+
+
+def control_numbers(log, steps=1000):
+    """The continuous-control-shaped workload (Section 4.2, Appendix D): 1,000,000 transitions of fp32[64]
+    observations and fp32[8] actions, n = 5, critic values as the only "action" column; every learner step
+    is preceded by an add round of 64 streams x 50 transitions, the excess is evicted every 10 rounds."""
+    import torch
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["control"]
+    rep = apex.Replay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes, w.alpha, w.eps, w.frac_bits)
+    rounds = [{k: dev(v) for k, v in synth.actor_round(w, i).items()} for i in range(4)]
+    obs = synth.obs_rows_torch(w.seed, 0, w.add_count, w.obs_bytes, "cuda:0")
+    scratch = [torch.empty(w.add_count, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    pipe = apex.Pipeline(rep, 8, 1, w.k)
+
+    def add_begin(i):
+        t = rounds[i % 4]
+        assert pipe.add_begin(t["q_online"], t["q_target"], t["action"], t["reward"], t["discount"], w.n, obs,
+                              t["act"], *scratch) == 0
+
+    assert pipe.fork() == 0
+    for i in range(w.capacity // w.add_count + 1):
+        add_begin(i)
+        assert pipe.add_end(True)[0] == 0
+    assert pipe.join() == 0
+    torch.cuda.synchronize()
+    assert rep.stats()["size"] == w.capacity
+    rnd = dev(np.concatenate([synth.uniforms(w.seed, s, 1, w.k) for s in range(steps)]))
+    td = dev(np.stack([synth.priorities(w.td_dist, w.seed, s, w.k) for s in range(steps)]))
+
+    def timed(fn):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps * 1e6
+
+    def full():
+        assert pipe.fork() == 0
+        for s in range(steps):
+            add_begin(s)
+            assert pipe.steps(1, w.beta, rnd[s:s + 1], td[s:s + 1])[0] == 0
+            assert pipe.add_end((s + 1) % 10 == 0)[0] == 0
+        assert pipe.join() == 0
+
+    def learner_only():
+        assert pipe.fork() == 0
+        assert pipe.steps(steps, w.beta, rnd, td)[0] == 0
+        assert pipe.join() == 0
+
+    full()
+    us_full = min(timed(full) for _ in range(2))
+    learner_only()
+    us_learner = min(timed(learner_only) for _ in range(2))
+    assert rep.stats()["size"] <= w.capacity + 10 * w.add_count
+    pipe.close()
+    log("control shape: %.2f us/step with an add round of %d before every step, %.2f us/step learner only"
+        % (us_full, w.add_count, us_learner))
+    return {"workload": "control: capacity 1,000,000 (ring 2^20) x fp32[64] obs + fp32[8] action, n=5, batch 512; "
+                        "add round of 64x50 before every learner step, FIFO evict every 10 rounds",
+            "us_per_step": us_full, "sampled_transitions_per_s": w.k / (us_full * 1e-6),
+            "adds_per_s": w.add_count / (us_full * 1e-6),
+            "learner_only_us_per_step": us_learner,
+            "learner_only_sampled_transitions_per_s": w.k / (us_learner * 1e-6)}
 
 
 def cpu_baseline(w, budget_steps, log):
@@ -322,6 +383,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--cpu-steps", type=int, default=2000, help="learner steps timed on the CPU oracle (0 = skip)")
+    ap.add_argument("--no-control", action="store_true", help="skip the continuous-control-shaped measurement")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -373,13 +435,16 @@ def main():
     assert st["size"] == w.capacity, st
     log("state after run: %s" % st)
 
-    gather_ms = job.gather_kernel_ms()
+    step_us = job.step_kernel_us(W, K)
     gather_bytes = 2 * w.k * w.obs_bytes                       # read + write of one batch of frame stacks
-    achieved = gather_bytes / (gather_ms * 1e-3) / 1e9
-    log("gather kernel: %.2f us/launch, %.0f GB/s" % (gather_ms * 1e3, achieved))
+    achieved = gather_bytes / (step_us * 1e-6) / 1e9
+    log("learner-step kernel: %.2f us/launch, %.0f GB/s" % (step_us, achieved))
 
     ops = op_timings(job)
     log("other steps alone, us: %s" % {k: round(v, 2) for k, v in ops.items()})
+    del job
+    torch.cuda.empty_cache()
+    control = control_numbers(log) if not args.no_control else None
     cpu = cpu_baseline(w, args.cpu_steps, log) if args.cpu_steps > 0 else None
 
     line = {
@@ -406,11 +471,22 @@ def main():
                                  "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6,
                                  "pipeline_16_batches_per_call_learner_only": us16,
                                  "pipeline_16_batches_per_call": us16_full},
-        "roofline": {"bound": "hbm", "kernel": "copy_rows_long_kernel<u32x4,2,weights,update> (frame-stack gather "
-                                               "of one batch, distinct rows every launch)",
+        "hbm_frac_of_step": {name: STEP_ALGORITHMIC_BYTES / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
+                             for name, us in (("pipeline_learner_only", dt_pipe_learner / K * 1e6),
+                                              ("pipeline_16_batches_per_call_learner_only", us16))},
+        "roofline": {"bound": "hbm", "kernel": "learner_step_kernel<u32x4,512,4> (gather of one batch of frame "
+                                               "stacks + IS weights + priority write-back + draw of the next "
+                                               "batch; distinct rows every launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_GATHER_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,
-                     "us_per_launch": gather_ms * 1e3},
+                     "traffic": MEASURED_STEP_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,
+                     "us_per_launch": step_us},
+        "roofline_add_payload": {"bound": "hbm", "kernel": "copy_rows_long_kernel<u32x4,2> (18,000 frame stacks "
+                                                           "of an add round into the ring)",
+                                 "achieved": ops["add_payload_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                 "frac": ops["add_payload_GBps"] / HBM_PEAK_GBS,
+                                 "bytes_per_launch": 2 * w.add_count * w.obs_bytes,
+                                 "us_per_launch": ops["add_payload_18000"]},
+        "control_workload": control,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)

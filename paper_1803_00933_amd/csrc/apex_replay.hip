@@ -434,7 +434,7 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
   const uint64_t row_bytes = r->cfg.obs_bytes;
   const uint64_t vpr = row_bytes / sizeof(u32x4);
   if (num_batches != 1 || k > kStepMaxK || depth < 3 || depth > kStepSets || r->tv.n_top > kStepMaxTop) return false;
-  if (row_bytes % sizeof(u32x4) || vpr <= 256 || vpr > (uint64_t)kStepThreads * kStepUnroll) return false;
+  if (row_bytes % sizeof(u32x4) || vpr > (uint64_t)kStepThreads * kStepUnroll) return false;
   if ((uintptr_t)r->obs() & 15) return false;
   for (uint32_t i = 0; i < depth; ++i)
     if (((uintptr_t)sets[i].obs | (uintptr_t)sets[i].slot) & 15) return false;

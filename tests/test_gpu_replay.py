@@ -456,6 +456,7 @@ def test_pipeline_graph_replays(nb, k):
     (400_000, 300_000, 512, 4224),   # three levels
     (5000, 4000, 1024, 32768),       # as many samples as a workgroup has lanes, largest fused row
     (5000, 4000, 1, 4224),           # batches of one
+    (70_000, 60_000, 512, 256),      # short rows (feature vectors): a few lanes of each workgroup copy
 ])
 def test_one_launch_per_learner_step(P, C, k, ob):
     """Sequences of learner steps issued as one launch per step (draw of the next batch inside the launch
