@@ -182,6 +182,34 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
 
 inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
 
+// Short observation rows: the whole payload of an add round in one launch.  APEX_ERR_NOT_READY - with
+// nothing enqueued - when the rows are long (the column-by-column copies take over).
+template <typename Vec>
+int add_payload_short_t(apex_replay *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                        const float *gacc, const RowMap &ring, hipStream_t stream)
+{
+  const uint32_t vpr = (uint32_t)(r->cfg.obs_bytes / sizeof(Vec));
+  if (vpr > 256) return APEX_ERR_NOT_READY;
+  uint32_t lanes_log2 = 0;
+  while ((1u << lanes_log2) < vpr) ++lanes_log2;
+  const uint64_t rows_per_block = 256u >> lanes_log2;
+  const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
+  if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+  add_payload_short_kernel<Vec><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(
+      static_cast<const uint8_t *>(obs), static_cast<const uint8_t *>(act), ret, gacc, r->obs(), r->act(), r->ret(),
+      r->gacc(), ring, count, vpr, lanes_log2, r->cfg.obs_bytes, r->cfg.act_bytes);
+  return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+}
+
+int add_payload_short(apex_replay *r, uint64_t count, const void *obs, const void *act, const float *ret,
+                      const float *gacc, const RowMap &ring, hipStream_t stream)
+{
+  const uintptr_t mis = (uintptr_t)obs | (uintptr_t)r->obs() | (uintptr_t)r->cfg.obs_bytes;
+  if ((mis & 15) == 0) return add_payload_short_t<u32x4>(r, count, obs, act, ret, gacc, ring, stream);
+  if ((mis & 3) == 0) return add_payload_short_t<uint32_t>(r, count, obs, act, ret, gacc, ring, stream);
+  return add_payload_short_t<uint8_t>(r, count, obs, act, ret, gacc, ring, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -292,6 +320,7 @@ int apex_replay_add_payload(apex_replay_t *r, uint64_t count, const void *obs, c
   const RowMap ident{nullptr, nullptr, 0};
   const RowMap ring{nullptr, &r->state()->tail, r->cfg.max_slots};
   int rc;
+  if (obs && (rc = add_payload_short(r, count, obs, act, ret, gacc, ring, stream)) != APEX_ERR_NOT_READY) return rc;
   if (obs && (rc = launch_copy(obs, ident, r->obs(), ring, count, r->cfg.obs_bytes, stream)) != APEX_OK) return rc;
   if (act && (rc = launch_copy(act, ident, r->act(), ring, count, r->cfg.act_bytes, stream)) != APEX_OK) return rc;
   if (ret && (rc = launch_copy(ret, ident, r->ret(), ring, count, 4, stream)) != APEX_OK) return rc;
@@ -311,7 +340,6 @@ int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio,
     if (both) r->second_version = r->tree_version;
     add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->tv2, both, r->state(), count,
                                                                               prio, r->qp);
-    advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), 0, count);
     APEX_HIP(hipGetLastError());
   }
   if (first_key_out) *first_key_out = r->tail;
@@ -451,7 +479,11 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
   int rc = sample_begin_impl(r, 1, k, rnd, b0.key, b0.slot, b0.mass, b0.act, b0.ret, b0.gacc, new_prio,
                              new_prio ? r->stepq(idx(0)) : nullptr, stream);
   if (rc != APEX_OK) return rc;
-  if (new_prio && (always_copy || r->second_version != r->tree_version)) {
+  // Only sequences of three steps or more draw from the second copy of the tree; shorter ones leave it
+  // as it is (in step, or stale and marked so).
+  const bool in_step = !always_copy && r->second_version == r->tree_version;
+  const bool reads_second = n >= 3;
+  if (new_prio && reads_second && !in_step) {
     copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
     APEX_HIP(hipGetLastError());
   }
@@ -502,7 +534,10 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     learner_step_kernel<u32x4, kStepThreads, kStepUnroll><<<dim3(k), dim3(kStepThreads), lds, stream>>>(a);
   }
   // (the last launch draws nothing and has brought both copies up to date)
-  if (new_prio) r->second_version = ++r->tree_version;
+  if (new_prio) {
+    ++r->tree_version;
+    if (reads_second || in_step) r->second_version = r->tree_version;
+  }
   APEX_HIP(hipGetLastError());
   return APEX_OK;
 }
@@ -612,7 +647,6 @@ int apex_replay_evict(apex_replay_t *r, uint64_t *evicted_out, void *hip_stream)
   ++r->tree_version;
   if (both) r->second_version = r->tree_version;
   evict_leaves_kernel<<<dim3(blocks_for(e, 256)), dim3(256), 0, stream>>>(r->tv, r->tv2, both, r->state(), e);
-  advance_state_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), e, 0);
   APEX_HIP(hipGetLastError());
   r->head += e;
   return APEX_OK;

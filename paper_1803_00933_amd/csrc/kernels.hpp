@@ -26,7 +26,24 @@ constexpr uint32_t kMaxLevels = 8;
 struct DeviceState {
   uint64_t head, tail;      // valid keys: head <= key < tail
   uint64_t n_stale, n_clamped;
+  uint32_t ticket;          // workgroups of the running add or evict launch that are done with head and tail
 };
+
+// Called by every thread of every workgroup of a launch once it has read what it needs of head and
+// tail: the workgroup that arrives last moves them on, so that the launch needs no follow-up
+// launch for it (the counter is back at 0 afterwards).  Contains a barrier.
+__device__ __forceinline__ void advance_state_when_all_done(DeviceState *st, uint64_t head_inc, uint64_t tail_inc)
+{
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t t = __hip_atomic_fetch_add(&st->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == gridDim.x - 1) {
+      st->ticket = 0;
+      st->head += head_inc;
+      st->tail += tail_inc;
+    }
+  }
+}
 
 struct TreeView {
   uint64_t *level[kMaxLevels];
@@ -405,6 +422,37 @@ __global__ __launch_bounds__(256) void copy_rows_short_kernel(const uint8_t *__r
   d[v] = s[v];
 }
 
+// All four payload columns of an add round with short observation rows, in one launch: 2^lanes_log2
+// lanes per transition copy its observation, its action bytes, and (first lane) its partial
+// return and accumulated discount.  act, ret, gacc may be null.
+template <typename Vec>
+__global__ __launch_bounds__(256) void add_payload_short_kernel(const uint8_t *__restrict__ obs,
+                                                                const uint8_t *__restrict__ act,
+                                                                const float *__restrict__ ret,
+                                                                const float *__restrict__ gacc,
+                                                                uint8_t *__restrict__ obs_ring,
+                                                                uint8_t *__restrict__ act_ring,
+                                                                float *__restrict__ ret_ring,
+                                                                float *__restrict__ gacc_ring, RowMap dmap,
+                                                                uint64_t nrows, uint32_t vecs_per_row,
+                                                                uint32_t lanes_log2, uint64_t obs_bytes,
+                                                                uint32_t act_bytes)
+{
+  const uint32_t rows_per_block = blockDim.x >> lanes_log2, lanes = 1u << lanes_log2;
+  const uint64_t row = (uint64_t)blockIdx.x * rows_per_block + (threadIdx.x >> lanes_log2);
+  const uint32_t v = threadIdx.x & (lanes - 1);
+  if (row >= nrows) return;
+  const uint64_t to = map_row(dmap, row);
+  if (v < vecs_per_row)
+    reinterpret_cast<Vec *>(obs_ring + to * obs_bytes)[v] = reinterpret_cast<const Vec *>(obs + row * obs_bytes)[v];
+  if (act)
+    for (uint32_t by = v; by < act_bytes; by += lanes) act_ring[to * act_bytes + by] = act[row * act_bytes + by];
+  if (v == 0) {
+    if (ret) ret_ring[to] = ret[row];
+    if (gacc) gacc_ring[to] = gacc[row];
+  }
+}
+
 // --------------------------------------------------------------------------------------------
 // add: masses of the new keys, and their sums into the upper levels
 // --------------------------------------------------------------------------------------------
@@ -426,11 +474,12 @@ __global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, TreeView t
   add_to_ancestors_grouped(tv, active, slot, q, both ? &tv2 : nullptr);
   const uint64_t nc = __popcll(__ballot(clamped));
   if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
+  advance_state_when_all_done(st, 0, count);
 }
 
 // evict: zero the masses of the e oldest keys and take them out of the upper levels
 __global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, TreeView tv2, bool both,
-                                                           const DeviceState *__restrict__ st, uint64_t e)
+                                                           DeviceState *__restrict__ st, uint64_t e)
 {
   const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
   const bool active = i < e;
@@ -442,15 +491,7 @@ __global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, TreeView
     if (both) tv2.level[0][slot] = 0;
   }
   add_to_ancestors_grouped(tv, active, slot, 0 - old, both ? &tv2 : nullptr);
-}
-
-// One thread, after the kernels that needed the old values.
-__global__ void advance_state_kernel(DeviceState *st, uint64_t head_inc, uint64_t tail_inc)
-{
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    st->head += head_inc;
-    st->tail += tail_inc;
-  }
+  advance_state_when_all_done(st, e, 0);
 }
 
 // --------------------------------------------------------------------------------------------

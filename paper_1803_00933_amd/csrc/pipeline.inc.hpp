@@ -30,6 +30,8 @@ struct apex_pipeline {
   uint64_t step = 0;          // learner steps issued so far
   uint64_t first_step = 0;    // steps before this one cannot be in flight (pipeline was drained)
   bool add_open = false;      // add_begin issued, add_end not yet
+  bool add_on_tree = false;   // ... with its payload copy on the learner's stream (small rounds)
+  bool tail_unmarked = false; // the tail has moved since tail_ready was last recorded
   uint64_t add_count = 0;
   float *add_prio = nullptr;
 
@@ -42,8 +44,9 @@ struct apex_pipeline {
 
 namespace {
 
-// From this many steps per call on, steps of one batch each are issued as one launch per step.
-constexpr uint32_t kFusedStepsMin = 3;
+// Add rounds whose observations are smaller than this are issued on the learner's stream: the events that
+// order the two streams would cost more than the copy.
+constexpr uint64_t kSmallPayloadBytes = 4u << 20;
 
 // From this many samples per step on, a step's gather goes to the copy stream.
 constexpr uint64_t kWideStepSamples = 2048;
@@ -175,7 +178,7 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
   if (!p || (n && !rnd) || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
   if (first_set_out) *first_set_out = (uint32_t)(p->step % p->depth);
   const uint64_t per = (uint64_t)p->nb * p->k;
-  if (n >= kFusedStepsMin && fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) {
+  if (n && fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) {
     APEX_TRY(fused_steps(p->r, n, p->k, beta, rnd, new_prio, p->sets.data(), p->depth,
                          (uint32_t)(p->step % p->depth), p->capturing, p->tree));
     p->step += n;
@@ -218,11 +221,19 @@ int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t
   apex_replay *r = p->r;
   const uint64_t count = (uint64_t)S * T;
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
-  APEX_TRY(mark_wait(p->tail_ready, p->add));  // the add stream reads tail on the device
+  p->add_on_tree = count * r->cfg.obs_bytes < kSmallPayloadBytes;
+  hipStream_t s = p->add_on_tree ? p->tree : p->add;
+  if (!p->add_on_tree) {
+    if (p->tail_unmarked) {  // small rounds have moved the tail since the last mark
+      APEX_TRY(mark_record(p, p->tail_ready, p->tree));
+      p->tail_unmarked = false;
+    }
+    APEX_TRY(mark_wait(p->tail_ready, p->add));  // the add stream reads tail on the device
+  }
   APEX_TRY(apex_nstep_priorities(S, T, n, A, q_online, q_target, action, reward, discount, r->cfg.alpha, r->cfg.eps,
-                                 r->cfg.frac_bits, r->cfg.max_slots, prio, ret, gacc, nullptr, p->add));
-  APEX_TRY(apex_replay_add_payload(r, count, obs, act, ret, gacc, p->add));
-  APEX_TRY(mark_record(p, p->payload_done, p->add));
+                                 r->cfg.frac_bits, r->cfg.max_slots, prio, ret, gacc, nullptr, s));
+  APEX_TRY(apex_replay_add_payload(r, count, obs, act, ret, gacc, s));
+  if (!p->add_on_tree) APEX_TRY(mark_record(p, p->payload_done, p->add));
   p->add_open = true;
   p->add_count = count;
   p->add_prio = prio;
@@ -232,12 +243,13 @@ int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t
 int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out, uint64_t *evicted_out)
 {
   if (!p || !p->add_open) return APEX_ERR_INVALID_ARG;
-  APEX_TRY(mark_wait(p->payload_done, p->tree));
+  if (!p->add_on_tree) APEX_TRY(mark_wait(p->payload_done, p->tree));
   APEX_TRY(apex_replay_add_publish(p->r, p->add_count, p->add_prio, first_key_out, p->tree));
   p->add_open = false;
   if (evicted_out) *evicted_out = 0;
   if (evict) APEX_TRY(apex_replay_evict(p->r, evicted_out, p->tree));
-  APEX_TRY(mark_record(p, p->tail_ready, p->tree));
+  if (!p->add_on_tree) APEX_TRY(mark_record(p, p->tail_ready, p->tree));
+  else p->tail_unmarked = true;
   return APEX_OK;
 }
 

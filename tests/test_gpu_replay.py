@@ -380,6 +380,53 @@ def test_pipeline_matches_the_plain_call_order(nb, k):
     pipe.close()
 
 
+def test_pipeline_small_and_large_add_rounds():
+    """Small add rounds travel on the learner's stream, large ones on the copy stream: rounds of both kinds
+    in one pipeline, with learner steps in between, against the oracle."""
+    from paper_1803_00933_amd import apex, synth
+    small = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=9000, max_slots=12288, streams=4, chunk=25, k=64)
+    large = small.scaled(streams=40)              # 1000 rows of 4224 B: above the size that stays on one stream
+    rng = np.random.default_rng(21)
+    g, o = make_pair(small.capacity, small.max_slots, small.obs_bytes, small.act_bytes)
+    add_both(g, o, rng, 8000)
+    depth = 4
+    pipe = apex.Pipeline(g, depth, 1, small.k)
+    assert pipe.fork() == 0
+    for i, w in enumerate([small, large, large, small, small, large, small]):
+        d = synth.actor_round(w, i)
+        n_rows = w.streams * w.chunk
+        d["obs"] = rng.integers(0, 256, (n_rows, w.obs_bytes), dtype=np.uint8)
+        dd = {k2: dev(v) for k2, v in d.items()}
+        scratch = [torch.empty(n_rows, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+        rnd = rng.integers(0, U64, (3, w.k), dtype=np.uint64)
+        newp = rng.lognormal(0, 1, (3, w.k)).astype(F32)
+        d_rnd, d_newp = dev(rnd), dev(newp)
+        assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                              dd["obs"], dd["act"], *scratch) == 0
+        rc, first = pipe.steps(3, 0.4, d_rnd, d_newp)
+        assert rc == 0
+        rc, first_key, ev = pipe.add_end(True)
+        refs = []
+        for s in range(3):
+            refs.append(o.sample(1, w.k, 0.4, rnd[s])[1])
+            o.update_priorities(refs[-1]["key"], newp[s])
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+        rco, fo = o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1), ref[2].reshape(-1))
+        assert (rc, first_key) == (rco, fo)
+        assert o.evict() == (0, ev)
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        for s in range(3):
+            assert_sample_equal(pipe.sets[(first + s) % depth], refs[s])
+        check_gpu_tree(g, o)
+        assert pipe.fork() == 0
+    assert pipe.join() == 0
+    # the payload of the last rounds is where the oracle has it
+    oo = sample_both(g, o, rng, 1, 64)
+    pipe.close()
+
+
 @pytest.mark.parametrize("nb,k", PIPELINE_STEP_SHAPES)
 def test_pipeline_graph_replays(nb, k):
     """One cycle (an add round beside six learner steps, then eviction) captured as a HIP graph by the
