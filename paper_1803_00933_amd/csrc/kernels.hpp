@@ -26,21 +26,21 @@ constexpr uint32_t kMaxLevels = 8;
 struct DeviceState {
   uint64_t head, tail;      // valid keys: head <= key < tail
   uint64_t n_stale, n_clamped;
-  uint32_t ticket;          // workgroups of the running add or evict launch that are done with head and tail
+  uint32_t ticket_add;      // workgroups of the running add launch that are done with tail ...
+  uint32_t ticket_evict;    // ... and of the running evict launch that are done with head (the two may overlap)
 };
 
-// Called by every thread of every workgroup of a launch once it has read what it needs of head and
-// tail: the workgroup that arrives last moves them on, so that the launch needs no follow-up
-// launch for it (the counter is back at 0 afterwards).  Contains a barrier.
-__device__ __forceinline__ void advance_state_when_all_done(DeviceState *st, uint64_t head_inc, uint64_t tail_inc)
+// Called by every thread of every workgroup of a launch once it has read what it needs of head or
+// tail: the workgroup that arrives last moves that counter on, so that the launch needs no
+// follow-up launch for it (the ticket is back at 0 afterwards).  Contains a barrier.
+__device__ __forceinline__ void advance_state_when_all_done(uint32_t *ticket, uint64_t *counter, uint64_t inc)
 {
   __syncthreads();
   if (threadIdx.x == 0) {
-    const uint32_t t = __hip_atomic_fetch_add(&st->ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (t == gridDim.x - 1) {
-      st->ticket = 0;
-      st->head += head_inc;
-      st->tail += tail_inc;
+      *ticket = 0;
+      *counter += inc;
     }
   }
 }
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, TreeView t
   add_to_ancestors_grouped(tv, active, slot, q, both ? &tv2 : nullptr);
   const uint64_t nc = __popcll(__ballot(clamped));
   if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
-  advance_state_when_all_done(st, 0, count);
+  advance_state_when_all_done(&st->ticket_add, &st->tail, count);
 }
 
 // evict: zero the masses of the e oldest keys and take them out of the upper levels
@@ -491,7 +491,7 @@ __global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, TreeView
     if (both) tv2.level[0][slot] = 0;
   }
   add_to_ancestors_grouped(tv, active, slot, 0 - old, both ? &tv2 : nullptr);
-  advance_state_when_all_done(st, e, 0);
+  advance_state_when_all_done(&st->ticket_evict, &st->head, e);
 }
 
 // --------------------------------------------------------------------------------------------
