@@ -96,7 +96,8 @@ typedef struct apex_replay_layout {
 
 /*
  * Sizes of the three device regions apex_replay_create adopts: the payload ring, the sum
- * tree, and scratch (device-side counters, per-call temporaries).  Any out pointer may be NULL.
+ * tree (two copies: the second serves the pipeline's fused learner steps), and scratch
+ * (device-side counters, per-call temporaries).  Any out pointer may be NULL.
  */
 int apex_replay_workspace_bytes(const apex_replay_config_t *cfg, size_t *storage_bytes, size_t *tree_bytes,
                                 size_t *scratch_bytes);
@@ -280,10 +281,13 @@ int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out /*host*/, void 
  * Prefetch pipeline.  Section 4.1 and Appendix "Implementation" describe a learner that fetches
  * batches asynchronously, ahead of use, while priorities flow back and actors keep adding.  An
  * apex_pipeline_t issues the same verbs as above on two streams of its own (default priority),
- * ordered by events: learner steps (draw; gather + weights + priority write-back as one launch)
- * and every other tree operation in program order on one, the payload copies of add rounds
- * (with their n-step priorities) beside them on the other.  Results are those of the plain
- * calls issued in the order: draw batch, update, [publish add], [evict].
+ * ordered by events: learner steps and every other tree operation in program order on one (the
+ * tree stream), the payload copies of large add rounds (with their n-step priorities) beside
+ * them on the other (the copy stream).  A sequence of steps of one batch each is issued as one
+ * launch per step (gather, weights and priority write-back of a batch together with the draw of
+ * the next one; it uses the second copy of the sum tree held in the tree region); steps of
+ * several batches put their gathers on the copy stream.  Results are in every case those of
+ * the plain calls issued in the order: draw batch, update, [publish add], [evict].
  * ---------------------------------------------------------------------------------------- */
 typedef struct apex_pipeline apex_pipeline_t;
 
@@ -302,7 +306,7 @@ typedef struct apex_batch_buffers {
 /*
  * sets: host array of `depth` (1..64) buffer sets, all pointers non-NULL device memory owned by
  * the caller; step i fills set i mod depth.  The caller must have consumed a set before depth
- * further steps are issued.  Creates two streams and four events.
+ * further steps are issued.  Creates two streams and a few events.
  */
 int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buffers_t *sets, uint32_t num_batches,
                          uint32_t k, apex_pipeline_t **out);
@@ -319,7 +323,8 @@ int apex_pipeline_join(apex_pipeline_t *p, void *stream);
  * [n, nb*k]) into the next buffer set, gathers them, and, if new_prio is not NULL, writes
  * new_prio[i] (device, [n, nb*k]) back as the priorities of the keys just drawn, before the next
  * step draws.  *first_set_out (host, may be NULL) receives the index of the set
- * the first of these steps fills.
+ * the first of these steps fills.  With the one-launch-per-step form the payload columns of a
+ * set are complete when the launch after its draw has run, i.e. once the call's work is done.
  */
 int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64_t *rnd, const float *new_prio,
                         uint32_t *first_set_out);
