@@ -326,16 +326,35 @@ def control_numbers(log, steps=1000):
         assert pipe.join() == 0
 
     full()
-    us_full = min(timed(full) for _ in range(2))
+    us_eager = min(timed(full) for _ in range(2))
+    # ten steps (one eviction cycle) recorded as a HIP graph and replayed: the eager loop above is bound by
+    # the three Python calls per step, not by the device
+    assert pipe.capture_begin() == 0
+    for s in range(10):
+        add_begin(s)
+        assert pipe.steps(1, w.beta, rnd[s:s + 1], td[s:s + 1])[0] == 0
+        assert pipe.add_end(s == 9)[0] == 0
+    assert pipe.capture_end() == 0
+
+    def replays():
+        assert pipe.fork() == 0
+        assert pipe.replay(steps // 10) == 0
+        assert pipe.join() == 0
+
+    replays()
+    us_graph = min(timed(replays) for _ in range(2))
+    assert rep.resync() == 0
+    us_full = min(us_eager, us_graph)
     learner_only()
     us_learner = min(timed(learner_only) for _ in range(2))
     assert rep.stats()["size"] <= w.capacity + 10 * w.add_count
     pipe.close()
-    log("control shape: %.2f us/step with an add round of %d before every step, %.2f us/step learner only"
-        % (us_full, w.add_count, us_learner))
+    log("control shape: %.2f us/step eager, %.2f as graph replays, with an add round of %d before every step; "
+        "%.2f us/step learner only" % (us_eager, us_graph, w.add_count, us_learner))
     return {"workload": "control: capacity 1,000,000 (ring 2^20) x fp32[64] obs + fp32[8] action, n=5, batch 512; "
                         "add round of 64x50 before every learner step, FIFO evict every 10 rounds",
-            "us_per_step": us_full, "sampled_transitions_per_s": w.k / (us_full * 1e-6),
+            "us_per_step": us_full, "us_per_step_eager": us_eager, "us_per_step_graph_replays": us_graph,
+            "sampled_transitions_per_s": w.k / (us_full * 1e-6),
             "adds_per_s": w.add_count / (us_full * 1e-6),
             "learner_only_us_per_step": us_learner,
             "learner_only_sampled_transitions_per_s": w.k / (us_learner * 1e-6)}

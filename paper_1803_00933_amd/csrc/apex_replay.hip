@@ -182,6 +182,46 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
 
 inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
 
+// A small add round (observations of at most 1 KB per row) as one launch: n-step priorities, payload,
+// masses.  Same effect as apex_nstep_priorities + apex_replay_add.  APEX_ERR_NOT_READY - with nothing
+// enqueued - when the rows are too long for it.
+template <typename Vec>
+int add_round_small_t(apex_replay *r, const NstepArgs &ns, const void *obs, const void *act, hipStream_t stream,
+                      bool both)
+{
+  const uint64_t count = (uint64_t)ns.S * ns.T;
+  const uint32_t vpr = (uint32_t)(r->cfg.obs_bytes / sizeof(Vec));
+  uint32_t lanes_log2 = 0;
+  while ((1u << lanes_log2) < vpr && lanes_log2 < 6) ++lanes_log2;  // at most one wave per row
+  const uint64_t rows_per_block = (uint32_t)kAddRoundThreads >> lanes_log2;
+  const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
+  if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+  add_round_small_kernel<Vec><<<dim3((uint32_t)blocks), dim3(kAddRoundThreads), 0, stream>>>(
+      ns, r->tv, r->tv2, both, r->state(), r->qp, static_cast<const uint8_t *>(obs), static_cast<const uint8_t *>(act),
+      r->obs(), r->act(), r->ret(), r->gacc(), vpr, lanes_log2, r->cfg.obs_bytes, r->cfg.act_bytes);
+  return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+}
+
+int add_round_small(apex_replay *r, const NstepArgs &ns, const void *obs, const void *act, uint64_t *first_key_out,
+                    hipStream_t stream)
+{
+  const uint64_t count = (uint64_t)ns.S * ns.T;
+  if (!obs || r->cfg.obs_bytes > 1024 || count == 0) return APEX_ERR_NOT_READY;
+  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  const bool both = r->second_version == r->tree_version;
+  const uintptr_t mis = (uintptr_t)obs | (uintptr_t)r->obs() | (uintptr_t)r->cfg.obs_bytes;
+  int rc;
+  if ((mis & 15) == 0) rc = add_round_small_t<u32x4>(r, ns, obs, act, stream, both);
+  else if ((mis & 3) == 0) rc = add_round_small_t<uint32_t>(r, ns, obs, act, stream, both);
+  else rc = add_round_small_t<uint8_t>(r, ns, obs, act, stream, both);
+  if (rc != APEX_OK) return rc;
+  ++r->tree_version;
+  if (both) r->second_version = r->tree_version;
+  if (first_key_out) *first_key_out = r->tail;
+  r->tail += count;
+  return APEX_OK;
+}
+
 // Short observation rows: the whole payload of an add round in one launch.  APEX_ERR_NOT_READY - with
 // nothing enqueued - when the rows are long (the column-by-column copies take over).
 template <typename Vec>
@@ -304,8 +344,9 @@ int apex_nstep_priorities(uint32_t S, uint32_t T, uint32_t n, uint32_t A, const 
   const uint64_t total = (uint64_t)S * T;
   if (total > 0x7fffffffull * 256 || (uint64_t)T + n > 0xffffffffull) return APEX_ERR_TOO_LARGE;
   const QuantParams qp{alpha, eps, frac_bits, qmax_for(max_slots)};
-  nstep_kernel<<<dim3(blocks_for(total, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(
-      S, T, n, A, q_online, q_target, action, reward, discount, qp, prio, ret, gacc, prio_fx);
+  const NstepArgs ns{S, T, n, A, q_online, q_target, action, reward, discount};
+  nstep_kernel<<<dim3(blocks_for(total, 256)), dim3(256), 0, static_cast<hipStream_t>(hip_stream)>>>(ns, qp, prio, ret,
+                                                                                                 gacc, prio_fx);
   APEX_HIP(hipGetLastError());
   return APEX_OK;
 }

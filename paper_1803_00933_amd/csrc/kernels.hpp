@@ -92,49 +92,62 @@ __device__ __forceinline__ void add_to_ancestors_grouped(const TreeView &tv, boo
 // --------------------------------------------------------------------------------------------
 // n-step priorities: one thread per transition (Algorithm 1, ComputePriorities; Sections 3.1, 3.2)
 // --------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void nstep_kernel(uint32_t S, uint32_t T, uint32_t n, uint32_t A,
-                                                    const float *__restrict__ q_online,
-                                                    const float *__restrict__ q_target,
-                                                    const int32_t *__restrict__ action,
-                                                    const float *__restrict__ reward,
-                                                    const float *__restrict__ discount, QuantParams qp,
-                                                    float *__restrict__ prio, float *__restrict__ ret,
-                                                    float *__restrict__ gacc, uint64_t *__restrict__ prio_fx)
+struct NstepArgs {
+  uint32_t S, T, n, A;
+  const float *q_online, *q_target;  // [S, T+n, A]
+  const int32_t *action;             // [S, T+n]
+  const float *reward, *discount;    // [S, T+n]
+};
+
+struct NstepOut {
+  float p, R, G;  // priority |delta|, partial return, accumulated discount
+};
+
+// Transition gid = s * T + t of an add round (gid < S * T).
+__device__ __forceinline__ NstepOut nstep_one(const NstepArgs &a, uint64_t gid)
 {
-  const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (gid >= (uint64_t)S * T) return;
+  const uint32_t T = a.T, n = a.n, A = a.A;
   const uint32_t s = (uint32_t)(gid / T), t = (uint32_t)(gid - (uint64_t)s * T);
   const uint64_t row0 = (uint64_t)s * (T + n);  // first row of this stream
-  const float *rw = reward + row0 + t;
-  const float *dc = discount + row0 + t;
+  const float *rw = a.reward + row0 + t;
+  const float *dc = a.discount + row0 + t;
 
   float R = 0.0f;
   for (int j = (int)n - 1; j >= 0; --j) R = __builtin_fmaf(dc[j], R, rw[j]);  // Horner, one rounding per step
   float G = 1.0f;
   for (uint32_t j = 0; j < n; ++j) G = G * dc[j];
 
-  const float *qrow = q_online + (row0 + t + n) * A;
+  const float *qrow = a.q_online + (row0 + t + n) * A;
   uint32_t best = 0;
   float vbest = qrow[0];
-  for (uint32_t a = 1; a < A; ++a) {
-    const float v = qrow[a];
+  for (uint32_t b = 1; b < A; ++b) {
+    const float v = qrow[b];
     if (v > vbest) {
       vbest = v;
-      best = a;
+      best = b;
     }
   }
-  const float boot = q_target[(row0 + t + n) * A + best];
-  uint32_t at = (uint32_t)action[row0 + t];
+  const float boot = a.q_target[(row0 + t + n) * A + best];
+  uint32_t at = (uint32_t)a.action[row0 + t];
   if (at >= A) at = A - 1;  // keeps a corrupt action index inside the row
   const float target = __builtin_fmaf(G, boot, R);
-  const float delta = target - q_online[(row0 + t) * A + at];
-  const float p = __builtin_fabsf(delta);
-  ret[gid] = R;
-  gacc[gid] = G;
-  prio[gid] = p;
+  const float delta = target - a.q_online[(row0 + t) * A + at];
+  return NstepOut{__builtin_fabsf(delta), R, G};
+}
+
+__global__ __launch_bounds__(256) void nstep_kernel(NstepArgs a, QuantParams qp, float *__restrict__ prio,
+                                                    float *__restrict__ ret, float *__restrict__ gacc,
+                                                    uint64_t *__restrict__ prio_fx)
+{
+  const uint64_t gid = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (gid >= (uint64_t)a.S * a.T) return;
+  const NstepOut o = nstep_one(a, gid);
+  ret[gid] = o.R;
+  gacc[gid] = o.G;
+  prio[gid] = o.p;
   if (prio_fx) {
     bool c;
-    prio_fx[gid] = quantise_priority(p, qp, &c);
+    prio_fx[gid] = quantise_priority(o.p, qp, &c);
   }
 }
 
@@ -474,6 +487,57 @@ __global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, TreeView t
   add_to_ancestors_grouped(tv, active, slot, q, both ? &tv2 : nullptr);
   const uint64_t nc = __popcll(__ballot(clamped));
   if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
+  advance_state_when_all_done(&st->ticket_add, &st->tail, count);
+}
+
+// A small add round in one launch (Algorithm 1: ComputePriorities, replay.Add): 2^lanes_log2 lanes
+// per transition copy its payload row into the ring; the first of them computes the n-step
+// priority, stores the partial return and the accumulated discount, and enters the mass into the
+// tree; the last workgroup to finish moves the tail on.  act may be null.
+// The masses of a workgroup's transitions are collected in LDS and entered into the upper levels by
+// whole waves of 64 neighbouring transitions, so that a node receives one atomic per 64 of them.
+constexpr int kAddRoundThreads = 1024;
+
+template <typename Vec>
+__global__ __launch_bounds__(kAddRoundThreads) void add_round_small_kernel(
+    NstepArgs ns, TreeView tv, TreeView tv2, bool both, DeviceState *__restrict__ st, QuantParams qp,
+    const uint8_t *__restrict__ obs, const uint8_t *__restrict__ act, uint8_t *__restrict__ obs_ring,
+    uint8_t *__restrict__ act_ring, float *__restrict__ ret_ring, float *__restrict__ gacc_ring, uint32_t vecs_per_row,
+    uint32_t lanes_log2, uint64_t obs_bytes, uint32_t act_bytes)
+{
+  __shared__ uint64_t sh_slot[kAddRoundThreads], sh_q[kAddRoundThreads];
+  const uint32_t rows_per_block = blockDim.x >> lanes_log2, lanes = 1u << lanes_log2;
+  const uint32_t r = threadIdx.x >> lanes_log2;  // row of this workgroup
+  const uint64_t i = (uint64_t)blockIdx.x * rows_per_block + r;
+  const uint32_t v = threadIdx.x & (lanes - 1);
+  const uint64_t count = (uint64_t)ns.S * ns.T;
+  const bool in_range = i < count;
+  bool clamped = false;
+  if (in_range) {
+    const uint64_t slot = (st->tail + i) % tv.P;
+    for (uint32_t vv = v; vv < vecs_per_row; vv += lanes)
+      reinterpret_cast<Vec *>(obs_ring + slot * obs_bytes)[vv] = reinterpret_cast<const Vec *>(obs + i * obs_bytes)[vv];
+    if (act)
+      for (uint32_t by = v; by < act_bytes; by += lanes) act_ring[slot * act_bytes + by] = act[i * act_bytes + by];
+    if (v == 0) {
+      const NstepOut o = nstep_one(ns, i);
+      ret_ring[slot] = o.R;
+      gacc_ring[slot] = o.G;
+      const uint64_t q = quantise_priority(o.p, qp, &clamped);
+      tv.level[0][slot] = q;  // the slot was empty (mass 0): the ring is never over-filled
+      if (both) tv2.level[0][slot] = q;
+      sh_slot[r] = slot;
+      sh_q[r] = q;
+    }
+  }
+  const uint64_t nc = __popcll(__ballot(clamped));
+  if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
+  __syncthreads();
+  if (threadIdx.x < ((rows_per_block + kWave - 1) & ~(uint32_t)(kWave - 1))) {  // whole waves
+    const uint32_t e = threadIdx.x;
+    const bool active = e < rows_per_block && (uint64_t)blockIdx.x * rows_per_block + e < count;
+    add_to_ancestors_grouped(tv, active, active ? sh_slot[e] : 0, active ? sh_q[e] : 0, both ? &tv2 : nullptr);
+  }
   advance_state_when_all_done(&st->ticket_add, &st->tail, count);
 }
 

@@ -32,6 +32,9 @@ struct apex_pipeline {
   bool add_open = false;      // add_begin issued, add_end not yet
   bool add_on_tree = false;   // ... with its payload copy on the learner's stream (small rounds)
   bool tail_unmarked = false; // the tail has moved since tail_ready was last recorded
+  bool add_deferred = false;  // the open round is issued as one launch by add_end
+  NstepArgs add_ns{};
+  const void *add_obs = nullptr, *add_act = nullptr;
   uint64_t add_count = 0;
   float *add_prio = nullptr;
 
@@ -221,19 +224,29 @@ int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t
   apex_replay *r = p->r;
   const uint64_t count = (uint64_t)S * T;
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  if (!S || !T || !n || !A || !q_online || !q_target || !action || !reward || !discount || !prio || !ret || !gacc)
+    return APEX_ERR_INVALID_ARG;
   p->add_on_tree = count * r->cfg.obs_bytes < kSmallPayloadBytes;
-  hipStream_t s = p->add_on_tree ? p->tree : p->add;
-  if (!p->add_on_tree) {
-    if (p->tail_unmarked) {  // small rounds have moved the tail since the last mark
-      APEX_TRY(mark_record(p, p->tail_ready, p->tree));
-      p->tail_unmarked = false;
+  p->add_deferred = p->add_on_tree && obs && r->cfg.obs_bytes <= 1024;
+  if (p->add_deferred) {
+    // a small round of short rows is one launch, issued by add_end (the inputs stay untouched until then)
+    p->add_ns = NstepArgs{S, T, n, A, q_online, q_target, action, reward, discount};
+    p->add_obs = obs;
+    p->add_act = act;
+  } else {
+    hipStream_t s = p->add_on_tree ? p->tree : p->add;
+    if (!p->add_on_tree) {
+      if (p->tail_unmarked) {  // small rounds have moved the tail since the last mark
+        APEX_TRY(mark_record(p, p->tail_ready, p->tree));
+        p->tail_unmarked = false;
+      }
+      APEX_TRY(mark_wait(p->tail_ready, p->add));  // the add stream reads tail on the device
     }
-    APEX_TRY(mark_wait(p->tail_ready, p->add));  // the add stream reads tail on the device
+    APEX_TRY(apex_nstep_priorities(S, T, n, A, q_online, q_target, action, reward, discount, r->cfg.alpha, r->cfg.eps,
+                                   r->cfg.frac_bits, r->cfg.max_slots, prio, ret, gacc, nullptr, s));
+    APEX_TRY(apex_replay_add_payload(r, count, obs, act, ret, gacc, s));
+    if (!p->add_on_tree) APEX_TRY(mark_record(p, p->payload_done, p->add));
   }
-  APEX_TRY(apex_nstep_priorities(S, T, n, A, q_online, q_target, action, reward, discount, r->cfg.alpha, r->cfg.eps,
-                                 r->cfg.frac_bits, r->cfg.max_slots, prio, ret, gacc, nullptr, s));
-  APEX_TRY(apex_replay_add_payload(r, count, obs, act, ret, gacc, s));
-  if (!p->add_on_tree) APEX_TRY(mark_record(p, p->payload_done, p->add));
   p->add_open = true;
   p->add_count = count;
   p->add_prio = prio;
@@ -244,7 +257,10 @@ int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out
 {
   if (!p || !p->add_open) return APEX_ERR_INVALID_ARG;
   if (!p->add_on_tree) APEX_TRY(mark_wait(p->payload_done, p->tree));
-  APEX_TRY(apex_replay_add_publish(p->r, p->add_count, p->add_prio, first_key_out, p->tree));
+  if (p->add_deferred)
+    APEX_TRY(add_round_small(p->r, p->add_ns, p->add_obs, p->add_act, first_key_out, p->tree));
+  else
+    APEX_TRY(apex_replay_add_publish(p->r, p->add_count, p->add_prio, first_key_out, p->tree));
   p->add_open = false;
   if (evicted_out) *evicted_out = 0;
   if (evict) APEX_TRY(apex_replay_evict(p->r, evicted_out, p->tree));

@@ -302,16 +302,18 @@ def test_captured_launches_replay_correctly():
 
 # (batches per step, k): one batch per step is two launches on one stream; 8 x 288 samples per step is
 # above the size from which the pipeline sends a step's gather to its copy stream
-PIPELINE_STEP_SHAPES = [(1, 96), (8, 288)]
+# (batches per step, k, observation bytes).  Rows of at most 1 KB make a small add round one launch
+# (n-step priorities, payload and masses together), issued by add_end.
+PIPELINE_STEP_SHAPES = [(1, 96, 4224), (8, 288, 4224), (1, 64, 256), (1, 64, 100), (1, 32, 7), (1, 32, 1001)]
 
 
-@pytest.mark.parametrize("nb,k", PIPELINE_STEP_SHAPES)
-def test_pipeline_matches_the_plain_call_order(nb, k):
+@pytest.mark.parametrize("nb,k,ob", PIPELINE_STEP_SHAPES)
+def test_pipeline_matches_the_plain_call_order(nb, k, ob):
     """apex_pipeline_*: learner steps (for steps of several batches: with the gathers on the second
     stream) and add rounds whose payload copy runs beside them, against the oracle doing draw, update,
     [add], [evict] one after the other."""
     from paper_1803_00933_amd import apex, synth
-    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=k)
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=ob, capacity=3000, max_slots=4096, streams=5, chunk=40, k=k)
     rng = np.random.default_rng(14)
     g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
     add_both(g, o, rng, w.capacity)
@@ -427,12 +429,12 @@ def test_pipeline_small_and_large_add_rounds():
     pipe.close()
 
 
-@pytest.mark.parametrize("nb,k", PIPELINE_STEP_SHAPES)
-def test_pipeline_graph_replays(nb, k):
+@pytest.mark.parametrize("nb,k,ob", PIPELINE_STEP_SHAPES)
+def test_pipeline_graph_replays(nb, k, ob):
     """One cycle (an add round beside six learner steps, then eviction) captured as a HIP graph by the
     pipeline and replayed; every replay is checked against the oracle, with eager work in between."""
     from paper_1803_00933_amd import apex, synth
-    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=4224, capacity=3000, max_slots=4096, streams=5, chunk=40, k=k)
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=ob, capacity=3000, max_slots=4096, streams=5, chunk=40, k=k)
     rng = np.random.default_rng(15)
     g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
     add_both(g, o, rng, w.capacity)
