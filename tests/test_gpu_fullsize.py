@@ -228,6 +228,79 @@ def test_continuous_control_shape_full_size():
     learner_steps(p, 300, 1, lambda s: w.beta, add_every=1, evict_every=10, add_fn=p.add_round_nstep)
     final_checks(p)
 
+    # the launch configuration the benchmark times for this shape: the pipeline with an add round (one
+    # launch) around every learner step, eviction every 10 rounds; eager, then as a replayed graph
+    from paper_1803_00933_amd import apex
+    depth, steps = 4, 10
+    pipe = apex.Pipeline(p.g, depth, 1, w.k)
+    rnd = np.stack([synth.uniforms(w.seed, 2000 + s, 1, w.k).reshape(-1) for s in range(steps)])
+    newp = np.stack([synth.priorities(w.td_dist, w.seed, 2000 + s, w.k) for s in range(steps)])
+    d_rnd, d_newp = dev(rnd), dev(newp)
+    rounds = [synth.actor_round(w, 7000 + i) for i in range(steps)]
+    d_rounds = [{k2: dev(v) for k2, v in d.items()} for d in rounds]
+    refs_n = [oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots) for d in rounds]
+    obs = synth.obs_rows_torch(w.seed, 0, w.add_count, w.obs_bytes, "cuda:0")
+    scratch = [torch.empty(w.add_count, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    outs = [{k2: torch.empty_like(v) for k2, v in pipe.sets[0].items() if k2 in ("slot", "key", "weight")}
+            for _ in range(steps)]
+
+    def cycle(keep):
+        for s in range(steps):
+            dd = d_rounds[s]
+            assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                                  obs, dd["act"], *scratch) == 0
+            rc, first = pipe.steps(1, w.beta, d_rnd[s:s + 1], d_newp[s:s + 1])
+            assert rc == 0
+            assert pipe.add_end(s == steps - 1)[0] == 0
+            if keep:                      # a set is overwritten `depth` steps later: copy it out, in stream order
+                assert pipe.join() == 0
+                for k2 in outs[s]:
+                    outs[s][k2].copy_(pipe.sets[first][k2])
+                assert pipe.fork() == 0
+
+    def oracle_cycle():
+        res = []
+        for s in range(steps):
+            res.append(p.o.sample(1, w.k, w.beta, rnd[s], payload=False)[1])
+            p.o.update_priorities(res[-1]["key"], newp[s])
+            assert p.o.add(refs_n[s][0].reshape(-1))[0] == 0
+        p.o.evict()
+        return res
+
+    torch.cuda.synchronize()
+    assert pipe.fork() == 0
+    cycle(keep=True)
+    assert pipe.join() == 0
+    torch.cuda.synchronize()
+    for s, o_ in enumerate(oracle_cycle()):
+        assert np.array_equal(host(outs[s]["slot"], np.uint32), o_["slot"]), s
+        assert np.array_equal(host(outs[s]["key"], np.uint64), o_["key"]), s
+        assert_close(host(outs[s]["weight"]), o_["weight"], "weight")
+    final_checks(p)
+    assert pipe.capture_begin() == 0
+    cycle(keep=False)
+    assert pipe.capture_end() == 0
+    for _ in range(3):
+        assert pipe.fork() == 0
+        assert pipe.replay(1) == 0
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        res = oracle_cycle()
+        for s in range(steps - depth, steps):
+            g_ = pipe.sets[(pipe_first_set(steps, depth, s))]
+            assert np.array_equal(host(g_["slot"], np.uint32), res[s]["slot"]), s
+            assert_close(host(g_["weight"]), res[s]["weight"], "weight")
+        assert p.g.resync() == 0
+        final_checks(p)
+    pipe.close()
+
+
+def pipe_first_set(steps, depth, s):
+    """The set that step s of the captured cycle fills: the pipeline numbers its steps from its creation, and
+    the eager cycle before the capture took `steps` of them."""
+    return (steps + s) % depth
+
 
 def test_scale_stress_full_size():
     """2^24 slots (ring 2^24 + 2^20), batch 4096, 1024 streams x 50 per add round, lognormal(0,2)."""
