@@ -135,9 +135,11 @@ def test_atari_shape_full_size():
     learner_steps(p, 200, 1, lambda s: w.beta, add_every=25, evict_every=100, add_fn=p.add_round_nstep)
     final_checks(p)
 
-    # the launch configuration the benchmark times: the library's pipeline, eager and as a replayed graph
-    depth, steps = 8, 8
+    # the launch configuration the benchmark times: the library's pipeline, eager and as a replayed graph,
+    # in windows of 25 learner steps beside one add round
+    depth, steps = 32, 25
     pipe = apex.Pipeline(p.g, depth, 1, w.k)
+    first_set = [0]
     rnd = np.stack([synth.uniforms(w.seed, 1000 + s, 1, w.k).reshape(-1) for s in range(steps)])
     newp = np.stack([synth.priorities(w.td_dist, w.seed, 1000 + s, w.k) for s in range(steps)])
     d_rnd, d_newp = dev(rnd), dev(newp)
@@ -151,7 +153,8 @@ def test_atari_shape_full_size():
     def cycle():
         assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
                               obs, dd["act"], *scratch) == 0
-        assert pipe.steps(steps, w.beta, d_rnd, d_newp)[0] == 0
+        rc, first_set[0] = pipe.steps(steps, w.beta, d_rnd, d_newp)
+        assert rc == 0
         assert pipe.add_end(True)[0] == 0
 
     def oracle_cycle():
@@ -165,7 +168,7 @@ def test_atari_shape_full_size():
 
     def compare(res):
         for s in range(steps):
-            o_, g_ = res[s], pipe.sets[s % depth]
+            o_, g_ = res[s], pipe.sets[(first_set[0] + s) % depth]
             assert np.array_equal(host(g_["slot"], np.uint32), o_["slot"])
             assert np.array_equal(host(g_["key"], np.uint64), o_["key"])
             assert_close(host(g_["weight"]), o_["weight"], "weight")
@@ -198,6 +201,37 @@ def test_atari_shape_full_size():
         compare(oracle_cycle())
         assert p.g.resync() == 0
         final_checks(p)
+    pipe.close()
+
+    # the paper's prefetch depth as one step: 16 batches of 512 per call, gathers on the copy stream
+    nb, calls = 16, 3
+    pipe = apex.Pipeline(p.g, 2, nb, w.k)
+    rnd16 = np.stack([synth.uniforms(w.seed, 3000 + c, nb, w.k).reshape(-1) for c in range(calls)])
+    newp16 = np.stack([synth.priorities(w.td_dist, w.seed, 3000 + c, nb * w.k) for c in range(calls)])
+    d_rnd16, d_newp16 = dev(rnd16), dev(newp16)
+    torch.cuda.synchronize()
+    assert pipe.fork() == 0
+    assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                          obs, dd["act"], *scratch) == 0
+    for c in range(calls):
+        rc, first = pipe.steps(1, w.beta, d_rnd16[c:c + 1], d_newp16[c:c + 1])
+        assert rc == 0
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        o_ = p.o.sample(nb, w.k, w.beta, rnd16[c], payload=False)[1]
+        p.o.update_priorities(o_["key"], newp16[c])
+        g_ = pipe.sets[first]
+        assert np.array_equal(host(g_["slot"], np.uint32), o_["slot"])
+        assert np.array_equal(host(g_["key"], np.uint64), o_["key"])
+        assert_close(host(g_["weight"]), o_["weight"], "weight")
+        idx = torch.from_numpy(o_["slot"][::257].astype(np.int64)).to("cuda:0")
+        assert torch.equal(g_["obs"][::257], p.g.obs_view()[idx])
+        assert pipe.fork() == 0
+    assert pipe.add_end(True)[0] == 0
+    assert pipe.join() == 0
+    assert p.o.add(ref_n[0].reshape(-1))[0] == 0
+    p.o.evict()
+    final_checks(p)
     pipe.close()
 
 
