@@ -360,6 +360,51 @@ def control_numbers(log, steps=1000):
             "learner_only_sampled_transitions_per_s": w.k / (us_learner * 1e-6)}
 
 
+def tree_bound_workloads(log, calls=300):
+    """The two tree-bound stress shapes (small rows, so the descent and the updates dominate): `skew` draws 16
+    batches of 512 per call from 2^21 Pareto-distributed priorities and writes all 8192 back, duplicates
+    included; `scale` draws one batch of 4096 from 2^24 transitions.  Learner calls only, through the
+    pipeline; microseconds per call."""
+    import torch
+    from paper_1803_00933_amd import apex, synth
+    out = {}
+    for name, dist in (("skew", "pareto"), ("scale", "lognormal2")):
+        w = synth.WORKLOADS[name]
+        rep = apex.Replay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes, w.alpha, w.eps, w.frac_bits)
+        left, piece = w.capacity, 0
+        while left > 0:
+            cnt = min(left, 1 << 21)
+            prio = dev(synth.priorities(dist, w.seed, piece, cnt, tag="bulk"))
+            obs = torch.zeros((cnt, w.obs_bytes), dtype=torch.uint8, device="cuda:0")
+            assert rep.add(prio, obs)[0] == 0
+            left -= cnt
+            piece += 1
+        nb, per = w.num_batches, w.num_batches * w.k
+        pipe = apex.Pipeline(rep, 4, nb, w.k)
+        rnd = dev(np.stack([synth.uniforms(w.seed, c, nb, w.k).reshape(-1) for c in range(calls)]))
+        td = dev(np.stack([synth.priorities(dist, w.seed, c, per) for c in range(calls)]))
+
+        def go():
+            assert pipe.fork() == 0
+            assert pipe.steps(calls, w.beta, rnd, td)[0] == 0
+            assert pipe.join() == 0
+
+        go()
+        best = 1e30
+        for _ in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            go()
+            torch.cuda.synchronize()
+            best = min(best, (time.perf_counter() - t0) / calls * 1e6)
+        pipe.close()
+        out[name] = {"samples_per_call": per, "us_per_call": best, "sampled_transitions_per_s": per / (best * 1e-6)}
+        log("%s shape: %d samples per call, %.2f us per call (draw + weights + gather + update)" % (name, per, best))
+        del pipe, rep, rnd, td
+        torch.cuda.empty_cache()
+    return out
+
+
 def cpu_baseline(w, budget_steps, log):
     """The oracle, untouched, on one host core: same schedule, bounded number of steps."""
     import oracle
@@ -402,7 +447,7 @@ def main():
     ap.add_argument("--steps", type=int, default=2000)
     ap.add_argument("--warmup", type=int, default=200)
     ap.add_argument("--cpu-steps", type=int, default=2000, help="learner steps timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--no-control", action="store_true", help="skip the continuous-control-shaped measurement")
+    ap.add_argument("--no-control", action="store_true", help="skip the measurements of the other workload shapes")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -464,6 +509,7 @@ def main():
     del job
     torch.cuda.empty_cache()
     control = control_numbers(log) if not args.no_control else None
+    tree_bound = tree_bound_workloads(log) if not args.no_control else None
     cpu = cpu_baseline(w, args.cpu_steps, log) if args.cpu_steps > 0 else None
 
     line = {
@@ -506,6 +552,7 @@ def main():
                                  "bytes_per_launch": 2 * w.add_count * w.obs_bytes,
                                  "us_per_launch": ops["add_payload_18000"]},
         "control_workload": control,
+        "tree_bound_workloads": tree_bound,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
