@@ -184,11 +184,12 @@ def test_atari_shape_full_size():
         assert np.array_equal(host(p.g.ret_view()[slots_new]).view(np.uint32), ref_n[1].reshape(-1)[rows].view(np.uint32))
 
     torch.cuda.synchronize()
-    assert pipe.fork() == 0
-    cycle()
-    assert pipe.join() == 0
-    torch.cuda.synchronize()
-    compare(oracle_cycle())
+    for _ in range(6):                    # 150 learner steps and six add rounds, checked window by window
+        assert pipe.fork() == 0
+        cycle()
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        compare(oracle_cycle())
     final_checks(p)
     assert pipe.capture_begin() == 0
     cycle()
