@@ -307,8 +307,9 @@ def test_captured_launches_replay_correctly():
 PIPELINE_STEP_SHAPES = [(1, 96, 4224), (8, 288, 4224), (1, 64, 256), (1, 64, 100), (1, 32, 7), (1, 32, 1001)]
 
 
+@pytest.mark.parametrize("depth", [3, 2])      # two buffer sets: too few for the one-launch step, two launches instead
 @pytest.mark.parametrize("nb,k,ob", PIPELINE_STEP_SHAPES)
-def test_pipeline_matches_the_plain_call_order(nb, k, ob):
+def test_pipeline_matches_the_plain_call_order(nb, k, ob, depth):
     """apex_pipeline_*: learner steps (for steps of several batches: with the gathers on the second
     stream) and add rounds whose payload copy runs beside them, against the oracle doing draw, update,
     [add], [evict] one after the other."""
@@ -317,7 +318,7 @@ def test_pipeline_matches_the_plain_call_order(nb, k, ob):
     rng = np.random.default_rng(14)
     g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
     add_both(g, o, rng, w.capacity)
-    depth, n_steps, per_round = 3, 24, 6
+    n_steps, per_round = 24, 6
     pipe = apex.Pipeline(g, depth, nb, w.k)
     rnd = rng.integers(0, U64, (n_steps, nb * w.k), dtype=np.uint64)
     newp = rng.lognormal(0, 1, (n_steps, nb * w.k)).astype(F32)
