@@ -405,6 +405,75 @@ def tree_bound_workloads(log, calls=300):
     return out
 
 
+def next_row_numbers(log):
+    """The two library features beyond the headline path, each timed on its own: learner-side priorities from
+    fresh Q-values fused into the write-back (Algorithm 2, ComputePriorities + SetPriority), and the memory with
+    prioritized eviction of the continuous-control variant (Appendix D: eviction by sampling with exponent -0.4)."""
+    import torch
+    from paper_1803_00933_amd import apex, synth
+    out = {}
+    rng = np.random.default_rng(5)
+    # --- priorities from Q-values, 512 pairs with 18 actions, on the Atari-shaped tree (payload rows of 16 bytes)
+    w = synth.WORKLOADS["atari"]
+    rep = apex.Replay(w.capacity, w.max_slots, 16, w.act_bytes, w.alpha, w.eps, w.frac_bits)
+    for piece in range(8):
+        cnt = w.capacity // 8
+        prio = dev(synth.priorities("lognormal1", w.seed, piece, cnt, tag="bulk"))
+        assert rep.add(prio, torch.zeros((cnt, 16), dtype=torch.uint8, device="cuda:0"), None,
+                       torch.zeros(cnt, device="cuda:0"), torch.full((cnt,), 0.97, device="cuda:0"))[0] == 0
+    o = rep.alloc_sample_outputs(1, w.k)
+    assert rep.sample(1, w.k, w.beta, dev(synth.uniforms(w.seed, 0, 1, w.k).reshape(-1)), out=o)[0] == 0
+    q_taken = torch.randn(w.k, device="cuda:0")
+    q_on, q_tg = torch.randn((w.k, w.num_actions), device="cuda:0"), torch.randn((w.k, w.num_actions), device="cuda:0")
+    n = 200
+    stream = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=stream):          # launches recorded once: host launch cost stays out
+        for _ in range(32):
+            assert rep.update_from_q(o["key"], q_taken, q_on, q_tg) == 0
+    graph.replay()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+    torch.cuda.synchronize()
+    ev[0].record()
+    for _ in range(4):
+        graph.replay()
+    ev[1].record()
+    torch.cuda.synchronize()
+    out["update_from_q_512x18_us"] = ev[0].elapsed_time(ev[1]) / (32 * 4) * 1e3
+    del graph, rep
+    # --- prioritized eviction, control shape: 32,000 of 1,032,000 transitions in 5 rounds
+    w = synth.WORKLOADS["control"]
+    g = apex.PeReplay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    assert g.add(dev(synth.priorities("lognormal1", 0, 0, w.capacity, tag="bulk"))) == 0
+    times = []
+    for r in range(3):
+        for i in range(10):
+            assert g.add(dev(synth.priorities("lognormal1", 0, 1 + i + 10 * r, w.add_count, tag="bulk"))) == 0
+        e = 10 * w.add_count
+        rnd = dev(rng.integers(0, 1 << 64, (5, e), dtype=np.uint64))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        rc, evicted = g.evict(5, rnd)
+        times.append((time.perf_counter() - t0) * 1e6)
+        assert rc == 0 and evicted == e, (rc, evicted)
+    out["prioritized_evict_32000_of_1032000_us"] = min(times)
+    rnds = dev(rng.integers(0, 1 << 64, (n, w.k), dtype=np.uint64))
+    td = torch.rand((n, w.k), device="cuda:0")
+    so = g.alloc_sample_outputs(1, w.k)
+    for rep_i in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            g.sample(1, w.k, 0.4, rnds[i], out=so)
+            g.update_priorities(so["key"], td[i])
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / n * 1e6
+    out["prioritized_evict_memory_sample_update_us"] = dt
+    log("next rows: %s" % {k: round(v, 2) for k, v in out.items()})
+    return out
+
+
 def cpu_baseline(w, budget_steps, log):
     """The oracle, untouched, on one host core: same schedule, bounded number of steps."""
     import oracle
@@ -510,6 +579,7 @@ def main():
     torch.cuda.empty_cache()
     control = control_numbers(log) if not args.no_control else None
     tree_bound = tree_bound_workloads(log) if not args.no_control else None
+    next_rows = next_row_numbers(log) if not args.no_control else None
     cpu = cpu_baseline(w, args.cpu_steps, log) if args.cpu_steps > 0 else None
 
     line = {
@@ -553,6 +623,7 @@ def main():
                                  "us_per_launch": ops["add_payload_18000"]},
         "control_workload": control,
         "tree_bound_workloads": tree_bound,
+        "next_rows": next_rows,
         "cpu_baseline": cpu,
     }
     print(json.dumps(line), flush=True)
