@@ -147,7 +147,7 @@ class GpuJob:
 
     def prefetch16_us_per_batch(self, batches, with_actors):
         """The paper's prefetch depth as the unit of work: 16 batches of 512 drawn per call from one state of
-        the memory, gathered and written back together (two launches per 16 batches).  With the actors' side:
+        the memory, gathered on the copy stream while the priorities are written back on the tree stream.  With the actors' side:
         the same insert rate (one add round per 25 batches) and eviction every 100 batches."""
         torch, w = self.torch, self.w
         nb = 16
@@ -544,7 +544,7 @@ def main():
     log("one stream: %.2f us/step (host enqueue %.2f us/step)" % (dt_serial / K * 1e6, host_serial / K * 1e6))
     dt_learner, _ = job.timed(lambda: job.run(W + K, K, with_actors=False))
     log("one stream, learner steps only: %.2f us/step" % (dt_learner / K * 1e6))
-    # (2) the library's pipeline (learner steps as two launches each; add payloads on a second stream)
+    # (2) the library's pipeline (one launch per learner step; add payloads on a second stream)
     dt_pipe, host_pipe = job.timed(lambda: job.run_pipelined(W, K))
     log("pipeline, two streams: %.2f us/step (host enqueue %.2f us/step)" % (dt_pipe / K * 1e6, host_pipe / K * 1e6))
     dt_pipe_learner, _ = job.timed(lambda: job.run_pipelined_learner_only(W + K, K))

@@ -300,8 +300,8 @@ def test_captured_launches_replay_correctly():
             assert g.resync() == 0
 
 
-# (batches per step, k): one batch per step is two launches on one stream; 8 x 288 samples per step is
-# above the size from which the pipeline sends a step's gather to its copy stream
+# One batch per step of 16-byte-aligned rows is one launch per step; 8 x 288 samples per step is above the
+# size from which the pipeline sends a step's gather to its copy stream.
 # (batches per step, k, observation bytes).  Rows of at most 1 KB make a small add round one launch
 # (n-step priorities, payload and masses together), issued by add_end.
 PIPELINE_STEP_SHAPES = [(1, 96, 4224), (8, 288, 4224), (1, 64, 256), (1, 64, 100), (1, 32, 7), (1, 32, 1001)]
