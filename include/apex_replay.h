@@ -20,7 +20,9 @@
  *     enqueues kernels on that stream and returns; device outputs are valid once the stream has
  *     reached that point.  No call allocates or frees device memory, none synchronises except
  *     apex_replay_create and apex_replay_stats.  Calls on one memory must be issued in order
- *     on one stream (or be ordered by events): the memory holds no locks.
+ *     on one stream (or be ordered by events): the memory holds no locks.  A memory object
+ *     (and a pipeline on it) is used by one host thread at a time; different objects are
+ *     independent.
  *   - Return value: APEX_OK or a negative apex_status; on error nothing has been enqueued and
  *     no state has changed.
  *   - Transitions are identified by a key: the running count of insertions (the first
