@@ -29,6 +29,7 @@ inline bool hip_failed(hipError_t e)
   } while (0)
 
 inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
+inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
 
 uint32_t ceil_log2(uint64_t v)
 {
@@ -125,6 +126,7 @@ namespace {
 struct SideJobs {
   WeightArgs wa{nullptr, nullptr, 1, 0.f};  // wa.weight_out != null: importance weights wanted
   UpdateArgs ua{};                          // ua.m != 0: a priority update of at most 1024 pairs
+  ClaimArgs claim{};                        // claim.m != 0: first pass of a larger update (short rows only)
 };
 
 template <typename Vec>
@@ -161,9 +163,21 @@ int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const Ro
     while ((1u << lanes_log2) < vpr) ++lanes_log2;
     const uint64_t rows_per_block = 256u >> lanes_log2;
     const uint64_t blocks = (nrows + rows_per_block - 1) / rows_per_block;
-    if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
-    copy_rows_short_kernel<Vec>
-        <<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(src, smap, dst, dmap, nrows, vpr, lanes_log2, row_bytes);
+    if (blocks > 0x7ffffff0ull) return APEX_ERR_TOO_LARGE;
+    const ShortCopyArgs c{src, smap, dst, dmap, nrows, vpr, lanes_log2, row_bytes};
+    const bool w = jobs && jobs->wa.weight_out, cl = jobs && jobs->claim.m;
+    if (w || cl) {
+      // the importance weights and the claim pass of a large update ride along
+      const uint32_t batches = w ? (uint32_t)(nrows / jobs->wa.k) : 0, parts = w ? blocks_for(jobs->wa.k, 512) : 0;
+      const uint32_t claim_blocks = cl ? blocks_for(jobs->claim.m, 256) : 0;
+      finish_short_kernel<Vec><<<dim3((uint32_t)blocks + batches * parts + claim_blocks), dim3(256), 0, stream>>>(
+          c, (uint32_t)blocks, w ? jobs->wa : WeightArgs{nullptr, nullptr, 1, 0.f}, batches, parts,
+          cl ? jobs->claim : ClaimArgs{});
+      if (w) jobs->wa.weight_out = nullptr;
+      if (cl) jobs->claim.m = 0;
+    } else {
+      copy_rows_short_kernel<Vec><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(c);
+    }
   }
   return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
 }
@@ -180,7 +194,6 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
   return launch_copy_t<uint8_t>(s, smap, d, dmap, nrows, row_bytes, stream, jobs);
 }
 
-inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
 
 // A small add round (observations of at most 1 KB per row) as one launch: n-step priorities, payload,
 // masses.  Same effect as apex_nstep_priorities + apex_replay_add.  APEX_ERR_NOT_READY - with nothing
@@ -429,7 +442,9 @@ int sample_begin_impl(apex_replay *r, uint32_t num_batches, uint32_t k, const ui
   a.first_dq = first_dq;
   a.qp = r->qp;
   a.counters = r->state();
-  const uint32_t waves = 4;
+  // every workgroup stages the whole top level: with a large top and many samples, larger workgroups
+  // (16 samples each) stage it fewer times
+  const uint32_t waves = (r->tv.n_top > 1024 && (uint64_t)num_batches * k >= 1024) ? 16 : 4;
   const size_t lds = ((size_t)r->tv.n_top + waves) * sizeof(uint64_t);
   sample_descent_kernel<<<dim3(blocks_for(k, waves), num_batches), dim3(waves * kWave), lds, stream>>>(a);
   APEX_HIP(hipGetLastError());
@@ -448,8 +463,9 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
 
 namespace {
 
+// claimed: the first pass (update_claim) of a large update has already run.
 int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *prio, hipStream_t stream,
-                  const QSource &qs = QSource{})
+                  const QSource &qs = QSource{}, bool claimed = false)
 {
   ++r->tree_version;
   if (m <= 1024) {
@@ -457,7 +473,8 @@ int launch_update(apex_replay *r, uint64_t m, const uint64_t *key, const float *
     update_small_kernel<<<dim3(1), dim3((uint32_t)round_up(m, kWave)), 0, stream>>>(ua);
   } else {
     const dim3 grid(blocks_for(m, 256)), block(256);
-    update_claim_kernel<<<grid, block, 0, stream>>>(r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim());
+    if (!claimed)
+      update_claim_kernel<<<grid, block, 0, stream>>>(ClaimArgs{r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim()});
     update_apply_kernel<<<grid, block, 0, stream>>>(r->tv, r->state(), (uint32_t)m, key, prio, r->qp, r->claim(), qs);
   }
   return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
@@ -478,6 +495,7 @@ int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, co
     jobs.ua = UpdateArgs{r->tv, r->state(), (uint32_t)m, key, prio, r->qp, hint ? slot : nullptr, hint ? mass : nullptr,
                          QSource{}};
   }
+  if (m > 1024) jobs.claim = ClaimArgs{r->cfg.max_slots, r->state(), (uint32_t)m, key, r->claim()};
   if (obs_out) {
     const RowMap by_slot{slot, nullptr, 0};
     const RowMap ident{nullptr, nullptr, 0};
@@ -485,10 +503,12 @@ int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, co
     if (rc != APEX_OK) return rc;
   }
   if (jobs.wa.weight_out) {  // no gather, or short rows: the weights get a small launch of their own
-    batch_weights_kernel<<<dim3(num_batches), dim3(256), 0, stream>>>(jobs.wa);
+    batch_weights_kernel<<<dim3(num_batches, blocks_for(k, 512)), dim3(256), 0, stream>>>(jobs.wa);
     APEX_HIP(hipGetLastError());
   }
-  if (m && (jobs.ua.m || !(m <= 1024 || hint))) return launch_update(r, m, key, prio, stream);
+  // whatever of the update no launch above has taken (a claim pass that has run leaves the second pass)
+  if (m && (jobs.ua.m || !(m <= 1024 || hint)))
+    return launch_update(r, m, key, prio, stream, QSource{}, /*claimed=*/m > 1024 && jobs.claim.m == 0);
   return APEX_OK;
 }
 

@@ -427,7 +427,7 @@ int apex_pe_sample(apex_pe_replay_t *r, uint32_t num_batches, uint32_t k, float 
     if (rc != APEX_OK) return rc;
   }
   if (jobs.wa.weight_out) {
-    batch_weights_kernel<<<dim3(num_batches), dim3(256), 0, stream>>>(jobs.wa);
+    batch_weights_kernel<<<dim3(num_batches, blocks_for(k, 512)), dim3(256), 0, stream>>>(jobs.wa);
     APEX_HIP(hipGetLastError());
   }
   return APEX_OK;

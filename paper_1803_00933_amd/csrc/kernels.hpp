@@ -318,7 +318,10 @@ struct WeightArgs {
   float beta;
 };
 
-__device__ __forceinline__ void batch_weights(const WeightArgs &wa, uint32_t b, uint64_t *red)
+// part, nparts: the workgroup writes the weights of samples [part * k / nparts ...) of batch b only
+// (every part still finds the minimum over the whole batch).
+__device__ __forceinline__ void batch_weights(const WeightArgs &wa, uint32_t b, uint64_t *red, uint32_t part = 0,
+                                              uint32_t nparts = 1)
 {
   const uint32_t tid = threadIdx.x, nthr = blockDim.x, nwave = nthr / kWave;
   const uint64_t *bm = wa.mass + (uint64_t)b * wa.k;
@@ -331,17 +334,20 @@ __device__ __forceinline__ void batch_weights(const WeightArgs &wa, uint32_t b, 
   // fp32 with the library's own power routine (relative error below 1e-6 here): a double-precision
   // pow would cost this kernel 70 registers per lane and half of its occupancy
   const float fmn = (float)mn;
-  for (uint32_t i = tid; i < wa.k; i += nthr)
+  const uint32_t per = (wa.k + nparts - 1) / nparts;
+  const uint32_t lo = min(part * per, wa.k), hi = min(lo + per, wa.k);
+  for (uint32_t i = lo + tid; i < hi; i += nthr)
     wa.weight_out[(uint64_t)b * wa.k + i] = pow_fixed_sequence(fmn / (float)bm[i], wa.beta);
 }
 
 constexpr int kLongCopyThreads = 1024;  // one workgroup of 16 waves per 28 KB frame stack
 constexpr int kLongCopyUnroll = 2;      // 1024 lanes * 2 * 16 B = 32 KB per workgroup
 
+// grid: (batches, parts of a batch)
 __global__ __launch_bounds__(256) void batch_weights_kernel(WeightArgs wa)
 {
   __shared__ uint64_t red[256 / kWave];
-  batch_weights(wa, blockIdx.x, red);
+  batch_weights(wa, blockIdx.x, red, blockIdx.y, gridDim.y);
 }
 
 // Long rows (frame stacks): a workgroup copies kUnroll * blockDim consecutive vectors of one row,
@@ -420,19 +426,32 @@ __global__ __launch_bounds__(kLongCopyThreads) void copy_rows_long_kernel(const 
 }
 
 // Short rows: 2^lanes_log2 lanes per row, several rows per workgroup.
+struct ShortCopyArgs {
+  const uint8_t *src;
+  RowMap smap;
+  uint8_t *dst;
+  RowMap dmap;
+  uint64_t nrows;
+  uint32_t vecs_per_row, lanes_log2;
+  uint64_t row_bytes;
+};
+
 template <typename Vec>
-__global__ __launch_bounds__(256) void copy_rows_short_kernel(const uint8_t *__restrict__ src, RowMap smap,
-                                                              uint8_t *__restrict__ dst, RowMap dmap,
-                                                              uint64_t nrows, uint32_t vecs_per_row,
-                                                              uint32_t lanes_log2, uint64_t row_bytes)
+__device__ __forceinline__ void copy_rows_short_block(const ShortCopyArgs &c, uint32_t blk)
 {
-  const uint32_t rows_per_block = blockDim.x >> lanes_log2;
-  const uint64_t row = (uint64_t)blockIdx.x * rows_per_block + (threadIdx.x >> lanes_log2);
-  const uint32_t v = threadIdx.x & ((1u << lanes_log2) - 1);
-  if (row >= nrows || v >= vecs_per_row) return;
-  const Vec *s = reinterpret_cast<const Vec *>(src + map_row(smap, row) * row_bytes);
-  Vec *d = reinterpret_cast<Vec *>(dst + map_row(dmap, row) * row_bytes);
+  const uint32_t rows_per_block = blockDim.x >> c.lanes_log2;
+  const uint64_t row = (uint64_t)blk * rows_per_block + (threadIdx.x >> c.lanes_log2);
+  const uint32_t v = threadIdx.x & ((1u << c.lanes_log2) - 1);
+  if (row >= c.nrows || v >= c.vecs_per_row) return;
+  const Vec *s = reinterpret_cast<const Vec *>(c.src + map_row(c.smap, row) * c.row_bytes);
+  Vec *d = reinterpret_cast<Vec *>(c.dst + map_row(c.dmap, row) * c.row_bytes);
   d[v] = s[v];
+}
+
+template <typename Vec>
+__global__ __launch_bounds__(256) void copy_rows_short_kernel(ShortCopyArgs c)
+{
+  copy_rows_short_block<Vec>(c, blockIdx.x);
 }
 
 // All four payload columns of an add round with short observation rows, in one launch: 2^lanes_log2
@@ -562,24 +581,50 @@ __global__ __launch_bounds__(256) void evict_leaves_kernel(TreeView tv, TreeView
 // update: two passes so that, of several pairs naming one key, the last one wins
 // --------------------------------------------------------------------------------------------
 // pass 1: every valid pair bids its position for the slot (highest position wins)
-__global__ __launch_bounds__(256) void update_claim_kernel(uint64_t P, DeviceState *__restrict__ st, uint32_t m,
-                                                           const uint64_t *__restrict__ key,
-                                                           uint32_t *__restrict__ claim)
+struct ClaimArgs {
+  uint64_t P;
+  DeviceState *st;
+  uint32_t m;           // 0: nothing to claim
+  const uint64_t *key;
+  uint32_t *claim;
+};
+
+__device__ __forceinline__ void update_claim_block(const ClaimArgs &c, uint32_t blk)
 {
-  const uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+  const uint32_t i = blk * blockDim.x + threadIdx.x;
   bool stale = false;
-  if (i < m) {
-    const uint64_t k = key[i];
-    if (k >= st->head && k < st->tail)
-      __hip_atomic_fetch_max(claim + (k % P), i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (i < c.m) {
+    const uint64_t k = c.key[i];
+    if (k >= c.st->head && k < c.st->tail)
+      __hip_atomic_fetch_max(c.claim + (k % c.P), i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     else
       stale = true;
   }
   const uint64_t ns = __popcll(__ballot(stale));
-  if (ns && lane_id() == 0) atomic_add_u64(&st->n_stale, ns);
+  if (ns && lane_id() == 0) atomic_add_u64(&c.st->n_stale, ns);
 }
 
-// pass 2: the winner of a slot writes the new mass, moves the difference up, and clears the bid
+__global__ __launch_bounds__(256) void update_claim_kernel(ClaimArgs c) { update_claim_block(c, blockIdx.x); }
+
+// Everything that only needs the results of a draw of short rows, in one launch: the gather of the rows,
+// the importance weights, and the first pass of a priority update of the drawn keys.  Workgroups
+// [0, copy_blocks) copy, the next batches * weight_parts write weights, the rest claim.
+template <typename Vec>
+__global__ __launch_bounds__(256) void finish_short_kernel(ShortCopyArgs c, uint32_t copy_blocks, WeightArgs wa,
+                                                           uint32_t batches, uint32_t weight_parts, ClaimArgs cl)
+{
+  __shared__ uint64_t red[256 / kWave];
+  const uint32_t blk = blockIdx.x, weight_blocks = batches * weight_parts;
+  if (blk < copy_blocks) {
+    copy_rows_short_block<Vec>(c, blk);
+  } else if (blk < copy_blocks + weight_blocks) {
+    const uint32_t wb = blk - copy_blocks;
+    batch_weights(wa, wb / weight_parts, red, wb % weight_parts, weight_parts);
+  } else {
+    update_claim_block(cl, blk - copy_blocks - weight_blocks);
+  }
+}
+
 __global__ __launch_bounds__(256) void update_apply_kernel(TreeView tv, DeviceState *__restrict__ st, uint32_t m,
                                                            const uint64_t *__restrict__ key,
                                                            const float *__restrict__ prio, QuantParams qp,

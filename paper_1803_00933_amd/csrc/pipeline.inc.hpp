@@ -53,6 +53,7 @@ constexpr uint64_t kSmallPayloadBytes = 4u << 20;
 
 // From this many samples per step on, a step's gather goes to the copy stream.
 constexpr uint64_t kWideStepSamples = 2048;
+constexpr uint64_t kWideStepBytes = 8u << 20;  // ... and only if the gather moves enough to be worth two events
 
 bool new_event(hipEvent_t *e) { return !hip_failed(hipEventCreateWithFlags(e, hipEventDisableTiming)); }
 
@@ -136,7 +137,8 @@ int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buff
     ok = ok && !hip_failed(hipStreamCreateWithFlags(s, hipStreamNonBlocking));  // default priority
   ok = ok && new_event(&p->payload_done.own) && new_event(&p->tail_ready.own) && new_event(&p->fork_ev) &&
        new_event(&p->join_ev) && new_event(&p->drawn.own);
-  p->wide = (uint64_t)num_batches * k >= kWideStepSamples && depth >= 2;
+  p->wide = (uint64_t)num_batches * k >= kWideStepSamples && depth >= 2 &&
+            (uint64_t)num_batches * k * r->cfg.obs_bytes >= kWideStepBytes;
   if (p->wide) {
     p->gathered.resize(depth);
     for (apex_pipeline::Mark &m : p->gathered) ok = ok && new_event(&m.own);

@@ -558,10 +558,12 @@ def test_one_launch_per_learner_step(P, C, k, ob):
     pipe.close()
 
 
-@pytest.mark.parametrize("ob,k,extra", [(28224, 512, 0), (4224, 100, 0), (64, 128, 0), (4224, 700, 600)])
+@pytest.mark.parametrize("ob,k,extra", [(28224, 512, 0), (4224, 100, 0), (64, 128, 0), (4224, 700, 600),
+                                        (64, 700, 600), (7, 512, 700)])   # short rows, more than 1024 pairs
 def test_finish_with_update_riding_along(ob, k, extra):
     """apex_replay_sample_finish_update == finish, then update (in the gather kernel's extra workgroup when
-    the batch fits one, by launches of its own otherwise)."""
+    the batch fits one; with short rows the first pass of a larger update rides in the gather launch; by
+    launches of its own otherwise)."""
     rng = np.random.default_rng(16 + k)
     g, o = make_pair(3000, 4096, ob, 4)
     add_both(g, o, rng, 3000)
