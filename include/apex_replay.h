@@ -338,7 +338,10 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
  * untouched until the matching add_end has run) and copies obs, act, ret, gacc into the ring on
  * the add stream; apex_pipeline_add_end publishes them on the tree stream (after whatever steps
  * were issued in between) and, if evict is non-zero, then trims the memory to its capacity.
- * One round at a time.
+ * One round at a time.  Small rounds take shortcuts with the same result: below 4 MB of
+ * observations the copies run on the tree stream (no events), and with rows of at most 1 KB the
+ * whole round (priorities, payload, masses) is a single launch issued by add_end, which is why
+ * every input of add_begin must stay untouched until add_end has run.
  */
 int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t n, uint32_t A, const float *q_online,
                             const float *q_target, const int32_t *action, const float *reward,
