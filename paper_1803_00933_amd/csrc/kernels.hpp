@@ -767,7 +767,7 @@ __device__ __forceinline__ Drawn wave_descend(const TreeView &tv, const uint64_t
         for (int t = 0; t < 8; ++t) {
           if (((uint64_t)es[t] >> (sh + kFanoutLog2)) == idx) {
             const uint64_t dv = pd.delta[e0 + t * kWave + lane];
-            if (dv) atomicAdd(reinterpret_cast<unsigned long long *>(pd.row + ((es[t] >> sh) & (kFanout - 1))),
+            if (dv) atomicAdd(reinterpret_cast<unsigned long long *>(pd.row + (((uint64_t)es[t] >> sh) & (kFanout - 1))),
                               (unsigned long long)dv);
           }
         }
