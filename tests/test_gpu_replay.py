@@ -506,7 +506,10 @@ def test_pipeline_graph_replays(nb, k, ob):
     (400_000, 300_000, 512, 4224),   # three levels
     (5000, 4000, 1024, 32768),       # as many samples as a workgroup has lanes, largest fused row
     (5000, 4000, 1, 4224),           # batches of one
-    (70_000, 60_000, 512, 256),      # short rows (feature vectors): a few lanes of each workgroup copy
+    (60_000, 50_000, 512, 256),      # short rows (feature vectors): a few lanes of each workgroup copy
+    (70_000, 60_000, 300, 4224),     # a top level of more than 1024 nodes: two launches per step instead
+    (33_000, 30_000, 517, 2064),     # 516 top nodes (two passes of the drawing wave), k no multiple of 8
+    (9000, 8000, 1000, 48),          # two passes over the pending pairs, a ragged last one
     (5000, 4000, 100, 4100),         # rows that are no multiple of 16 bytes: two launches per step instead
 ])
 def test_one_launch_per_learner_step(P, C, k, ob):
