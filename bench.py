@@ -250,6 +250,13 @@ def op_timings(job):
     o["mass"] = torch.empty(w.k, dtype=torch.int64, device="cuda:0")
     out["descent_512"] = replayed(lambda i: rep.sample_begin(1, w.k, job.rnd[i], o))
     out["update_512"] = replayed(lambda i: rep.update_priorities(o["key"], job.td[i]))
+
+    def plain_step(i):                       # the plain verbs, one learner step: three launches
+        oo = job.outs[i % len(job.outs)]
+        assert rep.sample(1, w.k, w.beta, job.rnd[i], out=oo)[0] == 0
+        assert rep.update_priorities(oo["key"], job.td[i]) == 0
+
+    out["plain_sample_plus_update_512"] = replayed(plain_step)
     # add rounds and the eviction that follows them change the size of the memory: timed once, eagerly
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
     torch.cuda.synchronize()
