@@ -622,7 +622,7 @@ def main():
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": MEASURED_STEP_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,
                      "us_per_launch": step_us},
-        "roofline_add_payload": {"bound": "hbm", "kernel": "copy_rows_long_kernel<u32x4,2> (18,000 frame stacks "
+        "roofline_add_payload": {"bound": "hbm", "kernel": "copy_rows_dense_kernel<u32x4,2> (18,000 frame stacks "
                                                            "of an add round into the ring)",
                                  "achieved": ops["add_payload_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                                  "frac": ops["add_payload_GBps"] / HBM_PEAK_GBS,

@@ -145,6 +145,13 @@ int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const Ro
     const WeightArgs wa = w ? jobs->wa : WeightArgs{nullptr, nullptr, 1, 0.f};
     const UpdateArgs ua = u ? jobs->ua : UpdateArgs{};
     const dim3 grid(blocks), block(kThreads);
+    if (!jobs && !smap.index && !smap.ring_key && !dmap.index && nrows * vpr < 0xfffff000ull && nrows >= 1024) {
+      // dense source, many rows (the payload of an add round): workgroups packed with vectors
+      const uint32_t total = (uint32_t)(nrows * vpr);
+      copy_rows_dense_kernel<Vec, kUnroll><<<dim3(blocks_for(total, kThreads * kUnroll)), block, 0, stream>>>(
+          src, dst, dmap, vpr, row_bytes, total);
+      return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+    }
     // a same-batch write-back (slot/mass known) has one pair per copied row: spread it over the rows
     const int umode = !u ? 0 : (ua.slot_hint && ua.m == nrows) ? 2 : 1;
 #define APEX_LAUNCH_COPY(W, U) \

@@ -425,6 +425,35 @@ __global__ __launch_bounds__(kLongCopyThreads) void copy_rows_long_kernel(const 
   }
 }
 
+// Long rows from a dense source into the ring (the payload of an add round: row i of the source is its
+// i-th run of row_bytes bytes): the copy is cut into runs of kUnroll * blockDim vectors whatever the row
+// boundaries, so that every lane carries a full load (a 28,224-byte row fills only 86 % of a workgroup's
+// 2048 vector slots); each vector finds its destination row by one division.  (For gathers, whose source
+// rows are looked up per row, one workgroup per row is faster.)
+template <typename Vec, int kUnroll>
+__global__ __launch_bounds__(kLongCopyThreads) void copy_rows_dense_kernel(const uint8_t *__restrict__ src,
+                                                                           uint8_t *__restrict__ dst, RowMap dmap,
+                                                                           uint32_t vecs_per_row, uint64_t row_bytes,
+                                                                           uint32_t total_vecs)
+{
+  const uint32_t f0 = blockIdx.x * (kUnroll * blockDim.x) + threadIdx.x;
+  const Vec *s = reinterpret_cast<const Vec *>(src);
+  Vec tmp[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t f = f0 + u * blockDim.x;
+    if (f < total_vecs) tmp[u] = __builtin_nontemporal_load(s + f);
+  }
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t f = f0 + u * blockDim.x;
+    if (f < total_vecs) {
+      const uint32_t row = f / vecs_per_row, v = f - row * vecs_per_row;
+      __builtin_nontemporal_store(tmp[u], reinterpret_cast<Vec *>(dst + map_row(dmap, row) * row_bytes) + v);
+    }
+  }
+}
+
 // Short rows: 2^lanes_log2 lanes per row, several rows per workgroup.
 struct ShortCopyArgs {
   const uint8_t *src;
