@@ -152,6 +152,20 @@ int launch_copy_t(const uint8_t *src, const RowMap &smap, uint8_t *dst, const Ro
           src, dst, dmap, vpr, row_bytes, total);
       return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
     }
+    if (!u && vpr <= kThreads * kUnroll / 2 && nrows * vpr < 0xfffff000ull && nrows < 0xffffffffull) {
+      // rows that would fill at most half of a workgroup (4 to 16 KB), no write-back riding along:
+      // workgroups packed with vectors.  (For longer rows one workgroup per row measured a little faster.)
+      const uint32_t total = (uint32_t)(nrows * vpr);
+      const dim3 pgrid(blocks_for(total, kThreads * kUnroll) + nb);
+      if (w)
+        copy_rows_packed_kernel<Vec, kUnroll, true><<<pgrid, block, 0, stream>>>(src, smap, dst, dmap, (uint32_t)nrows, vpr,
+                                                                             row_bytes, total, wa, nb);
+      else
+        copy_rows_packed_kernel<Vec, kUnroll, false><<<pgrid, block, 0, stream>>>(src, smap, dst, dmap, (uint32_t)nrows,
+                                                                              vpr, row_bytes, total, wa, 0);
+      if (w) jobs->wa.weight_out = nullptr;
+      return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+    }
     // a same-batch write-back (slot/mass known) has one pair per copied row: spread it over the rows
     const int umode = !u ? 0 : (ua.slot_hint && ua.m == nrows) ? 2 : 1;
 #define APEX_LAUNCH_COPY(W, U) \

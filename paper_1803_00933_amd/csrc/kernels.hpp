@@ -454,6 +454,50 @@ __global__ __launch_bounds__(kLongCopyThreads) void copy_rows_dense_kernel(const
   }
 }
 
+// Long rows looked up through row maps (gathers), packed the same way: a workgroup's run of
+// kUnroll * blockDim vectors touches at most kPackedRows rows, whose source and destination offsets its
+// first lanes fetch once.  The first weight_blocks workgroups write one batch's importance weights
+// each instead of copying.
+constexpr uint32_t kPackedRows = 10;  // rows longer than 256 vectors: 2048 / 257 + 2
+
+template <typename Vec, int kUnroll, bool kWeights>
+__global__ __launch_bounds__(kLongCopyThreads) void copy_rows_packed_kernel(const uint8_t *__restrict__ src, RowMap smap,
+                                                                            uint8_t *__restrict__ dst, RowMap dmap,
+                                                                            uint32_t nrows, uint32_t vecs_per_row,
+                                                                            uint64_t row_bytes, uint32_t total_vecs,
+                                                                            WeightArgs wa, uint32_t weight_blocks)
+{
+  if (kWeights && blockIdx.x < weight_blocks) {
+    __shared__ uint64_t red[kLongCopyThreads / kWave];
+    batch_weights(wa, blockIdx.x, red);
+    return;
+  }
+  __shared__ uint64_t src_off[kPackedRows], dst_off[kPackedRows];
+  const uint32_t blk = blockIdx.x - (kWeights ? weight_blocks : 0);
+  const uint32_t first = blk * (kUnroll * blockDim.x);
+  const uint32_t r0 = first / vecs_per_row;
+  if (threadIdx.x < kPackedRows && r0 + threadIdx.x < nrows) {
+    src_off[threadIdx.x] = map_row(smap, r0 + threadIdx.x) * row_bytes;
+    dst_off[threadIdx.x] = map_row(dmap, r0 + threadIdx.x) * row_bytes;
+  }
+  __syncthreads();
+  Vec tmp[kUnroll];
+  uint32_t ri[kUnroll], v[kUnroll];
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t f = first + threadIdx.x + u * blockDim.x;
+    const uint32_t row = f / vecs_per_row;
+    ri[u] = row - r0;
+    v[u] = f - row * vecs_per_row;
+    if (f < total_vecs) tmp[u] = __builtin_nontemporal_load(reinterpret_cast<const Vec *>(src + src_off[ri[u]]) + v[u]);
+  }
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t f = first + threadIdx.x + u * blockDim.x;
+    if (f < total_vecs) __builtin_nontemporal_store(tmp[u], reinterpret_cast<Vec *>(dst + dst_off[ri[u]]) + v[u]);
+  }
+}
+
 // Short rows: 2^lanes_log2 lanes per row, several rows per workgroup.
 struct ShortCopyArgs {
   const uint8_t *src;
