@@ -397,9 +397,18 @@ int apex_replay_add_payload(apex_replay_t *r, uint64_t count, const void *obs, c
   int rc;
   if (obs && (rc = add_payload_short(r, count, obs, act, ret, gacc, ring, stream)) != APEX_ERR_NOT_READY) return rc;
   if (obs && (rc = launch_copy(obs, ident, r->obs(), ring, count, r->cfg.obs_bytes, stream)) != APEX_OK) return rc;
-  if (act && (rc = launch_copy(act, ident, r->act(), ring, count, r->cfg.act_bytes, stream)) != APEX_OK) return rc;
-  if (ret && (rc = launch_copy(ret, ident, r->ret(), ring, count, 4, stream)) != APEX_OK) return rc;
-  if (gacc && (rc = launch_copy(gacc, ident, r->gacc(), ring, count, 4, stream)) != APEX_OK) return rc;
+  if (act || ret || gacc) {
+    // the three small columns in one launch: 2^lanes_log2 lanes per transition share the action bytes
+    uint32_t lanes_log2 = 0;
+    while ((4u << lanes_log2) < r->cfg.act_bytes && lanes_log2 < 6) ++lanes_log2;
+    const uint64_t rows_per_block = 256u >> lanes_log2;
+    const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
+    if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+    add_payload_short_kernel<uint8_t><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(
+        nullptr, static_cast<const uint8_t *>(act), ret, gacc, r->obs(), r->act(), r->ret(), r->gacc(), ring, count,
+        /*vecs_per_row=*/0, lanes_log2, r->cfg.obs_bytes, r->cfg.act_bytes);
+    APEX_HIP(hipGetLastError());
+  }
   return APEX_OK;
 }
 
