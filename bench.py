@@ -477,6 +477,34 @@ def next_row_numbers(log):
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / n * 1e6
     out["prioritized_evict_memory_sample_update_us"] = dt
+    # the whole control-shaped schedule on this memory, as Appendix D runs it: an add round of 64 x 50 before
+    # every learner step, and every 10 rounds the excess of 32,000 evicted by priority in 5 rounds
+    rounds_in = [{k2: dev(v) for k2, v in synth.actor_round(w, i).items()} for i in range(4)]
+    obs = synth.obs_rows_torch(w.seed, 0, w.add_count, w.obs_bytes, "cuda:0")
+    outs = [torch.empty((w.streams, w.chunk), dtype=torch.float32, device="cuda:0") for _ in range(3)] + [None]
+    rnd_ev = dev(rng.integers(0, 1 << 64, (5, 10 * w.add_count), dtype=np.uint64))
+    steps = 100
+
+    def schedule():
+        for s in range(steps):
+            t = rounds_in[s % 4]
+            rc, prio, ret, gacc, _ = apex.nstep_priorities(t["q_online"], t["q_target"], t["action"], t["reward"],
+                                                           t["discount"], w.n, w.alpha, w.eps, w.frac_bits, w.max_slots,
+                                                           want_fx=False, out=outs)
+            assert rc == 0 and g.add(prio.view(-1), obs, t["act"], ret.view(-1), gacc.view(-1)) == 0
+            g.sample(1, w.k, 0.4, rnds[s], out=so)
+            g.update_priorities(so["key"], td[s])
+            if (s + 1) % 10 == 0:
+                rc, evicted = g.evict(5, rnd_ev)
+                assert rc == 0 and evicted == 10 * w.add_count, (rc, evicted)
+
+    for rep_i in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        schedule()
+        torch.cuda.synchronize()
+        dt = (time.perf_counter() - t0) / steps * 1e6
+    out["prioritized_evict_memory_control_schedule_us_per_step"] = dt
     log("next rows: %s" % {k: round(v, 2) for k, v in out.items()})
     return out
 

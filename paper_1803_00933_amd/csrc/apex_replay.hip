@@ -258,11 +258,18 @@ int add_round_small(apex_replay *r, const NstepArgs &ns, const void *obs, const 
 
 // Short observation rows: the whole payload of an add round in one launch.  APEX_ERR_NOT_READY - with
 // nothing enqueued - when the rows are long (the column-by-column copies take over).
+struct PayloadRing {
+  uint8_t *obs, *act;
+  float *ret, *gacc;
+  uint64_t obs_bytes;
+  uint32_t act_bytes;
+};
+
 template <typename Vec>
-int add_payload_short_t(apex_replay *r, uint64_t count, const void *obs, const void *act, const float *ret,
-                        const float *gacc, const RowMap &ring, hipStream_t stream)
+int add_payload_short_t(const PayloadRing &pr, uint64_t count, const void *obs, const void *act, const float *ret,
+                        const float *gacc, const RowMap &to, hipStream_t stream)
 {
-  const uint32_t vpr = (uint32_t)(r->cfg.obs_bytes / sizeof(Vec));
+  const uint32_t vpr = (uint32_t)(pr.obs_bytes / sizeof(Vec));
   if (vpr > 256) return APEX_ERR_NOT_READY;
   uint32_t lanes_log2 = 0;
   while ((1u << lanes_log2) < vpr) ++lanes_log2;
@@ -270,18 +277,46 @@ int add_payload_short_t(apex_replay *r, uint64_t count, const void *obs, const v
   const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
   if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
   add_payload_short_kernel<Vec><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(
-      static_cast<const uint8_t *>(obs), static_cast<const uint8_t *>(act), ret, gacc, r->obs(), r->act(), r->ret(),
-      r->gacc(), ring, count, vpr, lanes_log2, r->cfg.obs_bytes, r->cfg.act_bytes);
+      static_cast<const uint8_t *>(obs), static_cast<const uint8_t *>(act), ret, gacc, pr.obs, pr.act, pr.ret, pr.gacc,
+      to, count, vpr, lanes_log2, pr.obs_bytes, pr.act_bytes);
   return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
 }
 
-int add_payload_short(apex_replay *r, uint64_t count, const void *obs, const void *act, const float *ret,
-                      const float *gacc, const RowMap &ring, hipStream_t stream)
+int add_payload_short(const PayloadRing &pr, uint64_t count, const void *obs, const void *act, const float *ret,
+                      const float *gacc, const RowMap &to, hipStream_t stream)
 {
-  const uintptr_t mis = (uintptr_t)obs | (uintptr_t)r->obs() | (uintptr_t)r->cfg.obs_bytes;
-  if ((mis & 15) == 0) return add_payload_short_t<u32x4>(r, count, obs, act, ret, gacc, ring, stream);
-  if ((mis & 3) == 0) return add_payload_short_t<uint32_t>(r, count, obs, act, ret, gacc, ring, stream);
-  return add_payload_short_t<uint8_t>(r, count, obs, act, ret, gacc, ring, stream);
+  const uintptr_t mis = (uintptr_t)obs | (uintptr_t)pr.obs | (uintptr_t)pr.obs_bytes;
+  if ((mis & 15) == 0) return add_payload_short_t<u32x4>(pr, count, obs, act, ret, gacc, to, stream);
+  if ((mis & 3) == 0) return add_payload_short_t<uint32_t>(pr, count, obs, act, ret, gacc, to, stream);
+  return add_payload_short_t<uint8_t>(pr, count, obs, act, ret, gacc, to, stream);
+}
+
+// The three small columns (action bytes, partial return, accumulated discount) in one launch:
+// 2^lanes_log2 lanes per transition share the action bytes.
+int add_small_columns(const PayloadRing &pr, uint64_t count, const void *act, const float *ret, const float *gacc,
+                      const RowMap &to, hipStream_t stream)
+{
+  uint32_t lanes_log2 = 0;
+  while ((4u << lanes_log2) < pr.act_bytes && lanes_log2 < 6) ++lanes_log2;
+  const uint64_t rows_per_block = 256u >> lanes_log2;
+  const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
+  if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+  add_payload_short_kernel<uint8_t><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(
+      nullptr, static_cast<const uint8_t *>(act), ret, gacc, pr.obs, pr.act, pr.ret, pr.gacc, to, count,
+      /*vecs_per_row=*/0, lanes_log2, pr.obs_bytes, pr.act_bytes);
+  return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+}
+
+// obs, act, ret, gacc (any may be null) of `count` transitions into the rows that `to` names.
+int add_payload_rows(const PayloadRing &pr, uint64_t count, const void *obs, const void *act, const float *ret,
+                     const float *gacc, const RowMap &to, hipStream_t stream)
+{
+  const RowMap ident{nullptr, nullptr, 0};
+  int rc;
+  if (obs && (rc = add_payload_short(pr, count, obs, act, ret, gacc, to, stream)) != APEX_ERR_NOT_READY) return rc;
+  if (obs && (rc = launch_copy(obs, ident, pr.obs, to, count, pr.obs_bytes, stream)) != APEX_OK) return rc;
+  if (act || ret || gacc) return add_small_columns(pr, count, act, ret, gacc, to, stream);
+  return APEX_OK;
 }
 
 }  // namespace
@@ -392,24 +427,9 @@ int apex_replay_add_payload(apex_replay_t *r, uint64_t count, const void *obs, c
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
   if (count == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const RowMap ident{nullptr, nullptr, 0};
   const RowMap ring{nullptr, &r->state()->tail, r->cfg.max_slots};
-  int rc;
-  if (obs && (rc = add_payload_short(r, count, obs, act, ret, gacc, ring, stream)) != APEX_ERR_NOT_READY) return rc;
-  if (obs && (rc = launch_copy(obs, ident, r->obs(), ring, count, r->cfg.obs_bytes, stream)) != APEX_OK) return rc;
-  if (act || ret || gacc) {
-    // the three small columns in one launch: 2^lanes_log2 lanes per transition share the action bytes
-    uint32_t lanes_log2 = 0;
-    while ((4u << lanes_log2) < r->cfg.act_bytes && lanes_log2 < 6) ++lanes_log2;
-    const uint64_t rows_per_block = 256u >> lanes_log2;
-    const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
-    if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
-    add_payload_short_kernel<uint8_t><<<dim3((uint32_t)blocks), dim3(256), 0, stream>>>(
-        nullptr, static_cast<const uint8_t *>(act), ret, gacc, r->obs(), r->act(), r->ret(), r->gacc(), ring, count,
-        /*vecs_per_row=*/0, lanes_log2, r->cfg.obs_bytes, r->cfg.act_bytes);
-    APEX_HIP(hipGetLastError());
-  }
-  return APEX_OK;
+  const PayloadRing pr{r->obs(), r->act(), r->ret(), r->gacc(), r->cfg.obs_bytes, r->cfg.act_bytes};
+  return add_payload_rows(pr, count, obs, act, ret, gacc, ring, stream);
 }
 
 int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio, uint64_t *first_key_out,

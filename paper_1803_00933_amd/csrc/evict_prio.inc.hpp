@@ -53,13 +53,15 @@ __global__ __launch_bounds__(256) void pe_add_kernel(PeView v, PeState *__restri
   }
   const uint64_t nc = wave_sum(nclamp);
   if (nc && lane_id() == 0) atomic_add_u64(&st->base.n_clamped, nc);
-}
-
-__global__ void pe_after_add_kernel(PeState *st, uint64_t count)
-{
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    st->free_head += count;
-    st->base.tail += count;
+  // the last workgroup to finish moves the free ring's head and the insertion count on
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t t = __hip_atomic_fetch_add(&st->base.ticket_add, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == gridDim.x - 1) {
+      st->base.ticket_add = 0;
+      st->free_head += count;
+      st->base.tail += count;
+    }
   }
 }
 
@@ -374,15 +376,11 @@ int apex_pe_add(apex_pe_replay_t *r, uint64_t count, const void *obs, const void
   if (r->size() + count > r->cfg.max_slots) return APEX_ERR_FULL;
   if (count == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
-  const RowMap ident{nullptr, nullptr, 0};
   const RowMap freed{r->v.free_ring, &r->state()->free_head, r->cfg.max_slots};  // the next free slots, in order
-  int rc;
-  if (obs && (rc = launch_copy(obs, ident, r->obs(), freed, count, r->cfg.obs_bytes, stream)) != APEX_OK) return rc;
-  if (act && (rc = launch_copy(act, ident, r->act(), freed, count, r->cfg.act_bytes, stream)) != APEX_OK) return rc;
-  if (ret && (rc = launch_copy(ret, ident, r->ret(), freed, count, 4, stream)) != APEX_OK) return rc;
-  if (gacc && (rc = launch_copy(gacc, ident, r->gacc(), freed, count, 4, stream)) != APEX_OK) return rc;
+  const PayloadRing pr{r->obs(), r->act(), r->ret(), r->gacc(), r->cfg.obs_bytes, r->cfg.act_bytes};
+  const int rc = add_payload_rows(pr, count, obs, act, ret, gacc, freed, stream);
+  if (rc != APEX_OK) return rc;
   pe_add_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->v, r->state(), count, prio);
-  pe_after_add_kernel<<<dim3(1), dim3(64), 0, stream>>>(r->state(), count);
   APEX_HIP(hipGetLastError());
   r->inserted += count;
   return APEX_OK;
