@@ -594,12 +594,14 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
   // as it is (in step, or stale and marked so).
   const bool in_step = !always_copy && r->second_version == r->tree_version;
   const bool reads_second = n >= 3;
-  if (new_prio && reads_second && !in_step) {
-    copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
+  if (new_prio) {
+    if (reads_second && !in_step)
+      copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
+    // the first batch's changes into the first copy (the second one gets them from the first step launch)
+    apply_first_deltas_kernel<<<dim3(blocks_for(k, 256)), dim3(256), 0, stream>>>(r->tv, b0.slot, r->stepq(idx(0)), k);
     APEX_HIP(hipGetLastError());
   }
-  const size_t k_pad = round_up(k, 8);
-  const size_t lds = (round_up(r->tv.n_top, kFanout) + k_pad + kFanout) * 8 + k_pad * 4;
+  const size_t lds = round_up(r->tv.n_top, kFanout) * 8;
   for (uint32_t i = 0; i < n; ++i) {
     const apex_batch_buffers_t &b = set(i);
     const TreeView &rd = (new_prio && (i & 1)) ? r->tv2 : r->tv;
@@ -609,7 +611,6 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     a.dst = static_cast<uint8_t *>(b.obs);
     a.row_bytes = r->cfg.obs_bytes;
     a.vecs_per_row = (uint32_t)(a.row_bytes / sizeof(u32x4));
-    a.k = k;
     a.act = r->act();
     a.act_bytes = r->cfg.act_bytes;
     a.ret = r->ret();
@@ -617,12 +618,9 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     a.act_out = static_cast<uint8_t *>(b.act);
     a.ret_out = b.ret;
     a.gacc_out = b.gacc;
+    a.k = k;
     a.slot = b.slot;
     a.dq = new_prio ? r->stepq(idx(i)) : nullptr;
-    if (new_prio && i > 0) {
-      a.prev_slot = set(i - 1).slot;
-      a.prev_dq = r->stepq(idx(i - 1));
-    }
     a.qp = r->qp;
     a.wr = wr;
     a.st = r->state();
@@ -644,7 +642,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     }
     learner_step_kernel<u32x4, kStepThreads, kStepUnroll><<<dim3(k), dim3(kStepThreads), lds, stream>>>(a);
   }
-  // (the last launch draws nothing and has brought both copies up to date)
+  // (every change has now been applied to both copies)
   if (new_prio) {
     ++r->tree_version;
     if (reads_second || in_step) r->second_version = r->tree_version;

@@ -755,15 +755,6 @@ struct SampleArgs {
   DeviceState *counters;
 };
 
-// Pending changes of leaf masses that the tree in memory does not hold yet (LDS): a descent adds
-// them to every row of children it reads.  count == 0: none.
-struct PendingDeltas {
-  const uint32_t *slot;   // [count]
-  const uint64_t *delta;  // [count], mod 2^64; 0: nothing to add
-  uint32_t count;
-  uint64_t *row;          // 64 words of scratch, private to the wave that descends
-};
-
 // Turns pre[0, n_top) (LDS, the top level's masses, complete and visible) into exclusive prefix sums in
 // place and returns their total.  wave_total: blockDim/64 words of LDS.  Called by every thread
 // of the workgroup; ends with a barrier.
@@ -797,68 +788,53 @@ struct Drawn {
   uint64_t slot, mass;
 };
 
-// One wavefront walks from the top level (exclusive prefix sums `pre` in LDS) down to the slot
-// whose cumulative-mass interval holds x.  Called by all 64 lanes.
-template <bool kPending>
-__device__ __forceinline__ Drawn wave_descend(const TreeView &tv, const uint64_t *pre, uint64_t total, uint64_t x,
-                                              const PendingDeltas &pd)
+// One wavefront walks from the top level (exclusive prefix sums `pre` in LDS) down to the slots whose
+// cumulative-mass intervals hold x[0 .. kSamples): the loads of all samples go out together on every
+// level, so that several draws take the time of one.  Called by all 64 lanes.
+template <int kSamples>
+__device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t *pre, uint64_t total,
+                                             const uint64_t (&x_in)[kSamples], Drawn (&out)[kSamples])
 {
   const int lane = lane_id();
   const uint32_t n_top = tv.n_top;
-  // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
   const uint32_t stride = (n_top + kWave - 1) / kWave;
-  uint32_t p0 = lane * stride;
-  uint32_t cnt = __popcll(__ballot(p0 < n_top && pre[p0] <= x));
-  const uint32_t base = (cnt - 1) * stride;  // pre[0] = 0 <= x, so cnt >= 1
-  cnt = 0;
-  for (uint32_t off = 0; off < stride; off += kWave) {
-    const uint32_t p1 = base + off + lane;
-    cnt += __popcll(__ballot(off + lane < stride && p1 < n_top && pre[p1] <= x));
+  uint64_t x[kSamples], idx[kSamples], mass[kSamples];
+#pragma unroll
+  for (int s = 0; s < kSamples; ++s) {
+    // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
+    x[s] = x_in[s];
+    const uint32_t p0 = lane * stride;
+    uint32_t cnt = __popcll(__ballot(p0 < n_top && pre[p0] <= x[s]));
+    const uint32_t base = (cnt - 1) * stride;  // pre[0] = 0 <= x, so cnt >= 1
+    cnt = 0;
+    for (uint32_t off = 0; off < stride; off += kWave) {
+      const uint32_t p1 = base + off + lane;
+      cnt += __popcll(__ballot(off + lane < stride && p1 < n_top && pre[p1] <= x[s]));
+    }
+    idx[s] = base + cnt - 1;
+    mass[s] = ((idx[s] + 1 < n_top) ? pre[idx[s] + 1] : total) - pre[idx[s]];
+    x[s] -= pre[idx[s]];
   }
-  uint64_t idx = base + cnt - 1;
-  uint64_t mass = ((idx + 1 < n_top) ? pre[idx + 1] : total) - pre[idx];
-  x -= pre[idx];
-
   // lower levels: 64 children per step, prefix sum across the wave, first child whose
   // running sum exceeds the remainder
   for (int l = (int)tv.nlev - 2; l >= 0; --l) {
-    uint64_t c = tv.level[l][idx * kFanout + lane];
-    if (kPending && pd.count) {
-      // the pending deltas that fall under node idx, summed per child in LDS
-      pd.row[lane] = 0;
-      __builtin_amdgcn_wave_barrier();
-      const uint32_t sh = kFanoutLog2 * (uint32_t)l;
-      // (the loads of a group of eight entries per lane go out together)
-      for (uint32_t e0 = 0; e0 < pd.count; e0 += 8 * kWave) {
-        uint32_t es[8];
+    uint64_t c[kSamples];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          const uint32_t e = e0 + t * kWave + lane;
-          es[t] = e < pd.count ? pd.slot[e] : 0xffffffffu;  // no node has this prefix: slots are below 2^31
-        }
+    for (int s = 0; s < kSamples; ++s) c[s] = tv.level[l][idx[s] * kFanout + lane];
 #pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          if (((uint64_t)es[t] >> (sh + kFanoutLog2)) == idx) {
-            const uint64_t dv = pd.delta[e0 + t * kWave + lane];
-            if (dv) atomicAdd(reinterpret_cast<unsigned long long *>(pd.row + (((uint64_t)es[t] >> sh) & (kFanout - 1))),
-                              (unsigned long long)dv);
-          }
-        }
-      }
-      __builtin_amdgcn_wave_barrier();
-      c += pd.row[lane];
-      __builtin_amdgcn_wave_barrier();
+    for (int s = 0; s < kSamples; ++s) {
+      const uint64_t sc = wave_inclusive_scan(c[s]);
+      const uint64_t hit = __ballot(sc > x[s]);
+      const int sel = hit ? __ffsll((unsigned long long)hit) - 1 : kWave - 1;
+      const uint64_t c_sel = __shfl(c[s], sel, kWave);
+      const uint64_t s_sel = __shfl(sc, sel, kWave);
+      x[s] -= s_sel - c_sel;
+      idx[s] = idx[s] * kFanout + sel;
+      mass[s] = c_sel;
     }
-    const uint64_t sc = wave_inclusive_scan(c);
-    const uint64_t hit = __ballot(sc > x);
-    const int sel = hit ? __ffsll((unsigned long long)hit) - 1 : kWave - 1;
-    const uint64_t c_sel = __shfl(c, sel, kWave);
-    const uint64_t s_sel = __shfl(sc, sel, kWave);
-    x -= s_sel - c_sel;
-    idx = idx * kFanout + sel;
-    mass = c_sel;
   }
-  return Drawn{idx, mass};
+#pragma unroll
+  for (int s = 0; s < kSamples; ++s) out[s] = Drawn{idx[s], mass[s]};
 }
 
 // What a draw writes for sample o (called by all 64 lanes of the wave that drew it).
@@ -908,7 +884,10 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
   if (j < k) {
     const uint64_t w = total / k;                           // stratum width
     const uint64_t x = (uint64_t)j * w + __umul64hi(u, w);  // point inside stratum j
-    const Drawn dr = wave_descend<false>(tv, pre, total, x, PendingDeltas{});
+    const uint64_t xs[1] = {x};
+    Drawn drs[1];
+    wave_descend<1>(tv, pre, total, xs, drs);
+    const Drawn dr = drs[0];
     write_drawn(a, o, dr, head);
     if (a.first_prio) {
       bool clamped;
@@ -923,21 +902,22 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
 
 // --------------------------------------------------------------------------------------------
 // One launch per learner step (Algorithm 2: replay.Sample, replay.SetPriority in strict order):
-// the gather of batch i, its importance weights, the write-back of its new priorities, and the
-// draw of batch i+1 as it follows that write-back.
+// the gather of batch i, its importance weights, and the draw of batch i+1 together with the
+// write-back of batch i+1's new priorities (which are an argument of the call), so that the next
+// launch finds a tree that is up to date.
 //
 // A draw may not read a tree that other workgroups of the same launch are writing, so the memory
-// keeps two copies of the sum tree.  The launch reads one of them, which holds every write-back
-// up to batch i-1, and each workgroup adds the changes of batch i to what it reads from it: the
-// k pairs (slot, new mass - old mass) are loaded by every workgroup and held in LDS (the new
-// mass of a pair is worked out once, by the wave that draws it).  The same changes, and those of
-// batch i-1 which the other copy still lacks, go into the other copy with atomics, one pair per
-// workgroup; the next launch reads that copy.  The two copies swap roles from launch to launch.
-// The last launch of a sequence draws nothing, so nothing reads a tree in it, and it brings
-// both copies up to date.
+// keeps two copies of the sum tree.  Launch i reads copy R, which holds every write-back up to
+// batch i, and writes copy W, which holds those up to batch i-1: workgroup j adds the change of
+// pair j of batch i (known from the launch before) and of pair j of batch i+1 (which it has just
+// drawn) to W with atomics.  The next launch reads W and writes R: every change is applied twice,
+// once to each copy, in consecutive launches.  Before the first launch of a sequence the changes
+// of its first batch are applied to the first copy by a small launch of their own.
 //
 // Within a batch the drawn slots do not decrease (the strata are ordered), so the pairs that
-// share a slot are neighbours and the last of them is the one that counts.
+// share a slot are neighbours and the last of them is the one that counts: the wave that draws
+// sample j draws sample j+1 as well (both walks load together), only to see whether it lands
+// in the same slot.
 // --------------------------------------------------------------------------------------------
 __device__ __forceinline__ void add_delta(const TreeView &tv, uint32_t slot, uint64_t delta)
 {
@@ -959,7 +939,7 @@ __device__ __forceinline__ void wave_lds_sync()
 // an add round's payload copy on the other stream (measured: 16.9 instead of 18.4 us per step there).
 constexpr int kStepThreads = 512;
 constexpr int kStepUnroll = 4;
-constexpr uint32_t kStepMaxK = 1024;    // pairs per batch that the fused step handles
+constexpr uint32_t kStepMaxK = 1024;    // pairs per batch that the fused step handles (size of its scratch rows)
 constexpr uint32_t kStepMaxTop = 1024;  // top-level nodes that its single drawing wave stages
 
 struct StepArgs {
@@ -975,125 +955,42 @@ struct StepArgs {
   float *ret_out, *gacc_out;
   uint32_t k;             // <= kStepMaxK
   const uint32_t *slot;   // [k] batch i as it was drawn
-  const uint64_t *dq;     // [k] new mass - mass as drawn; null: nothing is written back in this sequence
-  const uint32_t *prev_slot;  // batch i-1, which the written copy still lacks; null: none
-  const uint64_t *prev_dq;
+  const uint64_t *dq;     // [k] its changes: new mass - mass as drawn; null: nothing is written back in this sequence
   TreeView wr;            // the copy that is written
   WeightArgs wa;          // weights of batch i
   SampleArgs next;        // draw of batch i+1 from next.tv, the copy that is read; next.rnd == null: none
   const float *next_prio; // [k] new priorities of batch i+1 (null: none) ...
-  uint64_t *next_dq;      // ... their mass differences, written by the wave that draws the sample
+  uint64_t *next_dq;      // ... the changes they bring, kept for the next launch
   QuantParams qp;
   DeviceState *st;
 };
 
 typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
-// The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier:
-// pending changes and the top level into LDS, the changes added to the top level, prefix sums,
-// descent.  Every lane takes eight consecutive pairs and eight consecutive top-level nodes per
-// pass, with 16-byte loads.
-// LDS, in words of 8 bytes: round_up(n_top, 64) + round_up(k, 8) + 64, then round_up(k, 8) words of 4 bytes.
-__device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *lds)
+// The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier: the
+// top level (eight consecutive nodes per lane and pass, 16-byte loads) into registers, its prefix
+// sums into LDS, two walks down, outputs, and the change that the sample's new priority brings.
+// LDS: round_up(n_top, 64) words of 8 bytes.
+__device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *pre)
 {
   const TreeView &rd = a.next.tv;
   const uint32_t n_top = rd.n_top, lane = lane_id();
   const uint32_t n_top_pad = (n_top + kFanout - 1) & ~(kFanout - 1);  // the level is zero-padded to this in memory
-  const uint32_t kp = a.dq ? a.k : 0, k_pad = (a.k + 7) & ~7u;
-  uint64_t *pre = lds;
-  uint64_t *p_delta = pre + n_top_pad;
-  uint64_t *p_row = p_delta + k_pad;
-  uint32_t *p_slot = reinterpret_cast<uint32_t *>(p_row + kFanout);
+  const bool second = a.next_prio && row + 1 < a.next.k;              // a next sample to compare slots with
   __builtin_amdgcn_s_setprio(2);
 
-  const uint64_t un = a.next.rnd[row];
+  const uint64_t un0 = a.next.rnd[row], un1 = second ? a.next.rnd[row + 1] : 0;
   const float prio_next = a.next_prio ? a.next_prio[row] : 0.0f;
   const uint64_t head = a.next.st->head;
-  const uint32_t sh_top = kFanoutLog2 * (rd.nlev - 1);
   const uint64_t *top = rd.level[rd.nlev - 1];
 
-  // the first 512 nodes of the top level are requested before anything else
-  uint64_t v_top[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-  if (8 * lane < n_top_pad) {
-#pragma unroll
-    for (int t = 0; t < 8; t += 2) {
-      const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + 8 * lane + t);
-      v_top[t] = v2.x, v_top[t + 1] = v2.y;
-    }
-  }
-
-  // ---- pending changes of this batch -> LDS; a pair counts unless the next pair has the same slot
-  for (uint32_t c0 = 0; c0 < kp; c0 += 8 * kWave) {
-    const uint32_t j0 = c0 + 8 * lane;
-    uint32_t sj[9];
-    uint64_t dj[8];
-    if (j0 + 8 <= kp) {
-      const u32x4 s0 = *reinterpret_cast<const u32x4 *>(a.slot + j0), s1 = *reinterpret_cast<const u32x4 *>(a.slot + j0 + 4);
-      sj[0] = s0.x, sj[1] = s0.y, sj[2] = s0.z, sj[3] = s0.w, sj[4] = s1.x, sj[5] = s1.y, sj[6] = s1.z, sj[7] = s1.w;
-      sj[8] = j0 + 8 < kp ? a.slot[j0 + 8] : 0xfffffffeu;
-#pragma unroll
-      for (int t = 0; t < 8; t += 2) {
-        const u64x2 d2 = *reinterpret_cast<const u64x2 *>(a.dq + j0 + t);
-        dj[t] = d2.x, dj[t + 1] = d2.y;
-      }
-    } else {
-#pragma unroll
-      for (int t = 0; t < 9; ++t) sj[t] = j0 + t < kp ? a.slot[j0 + t] : 0xfffffffeu - (t & 1);
-#pragma unroll
-      for (int t = 0; t < 8; ++t) dj[t] = j0 + t < kp ? a.dq[j0 + t] : 0;
-    }
-    if (j0 < k_pad) {
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        p_slot[j0 + t] = j0 + t < kp ? sj[t] : 0xffffffffu;
-        p_delta[j0 + t] = (j0 + t < kp && sj[t + 1] != sj[t]) ? dj[t] : 0;
-      }
-    }
-  }
-  bool clamped = false;
-  const uint64_t q_next = a.next_prio ? quantise_priority(prio_next, a.qp, &clamped) : 0;
-
-  // ---- top level: exclusive prefix sums of (masses + pending changes) -> LDS
-  if (kp) {  // the changes land on nodes of other lanes: add them in LDS
-    if (8 * lane < n_top_pad) {
-#pragma unroll
-      for (int t = 0; t < 8; ++t) pre[8 * lane + t] = v_top[t];
-    }
-    for (uint32_t i0 = 8 * (kWave + lane); i0 < n_top_pad; i0 += 8 * kWave) {
-#pragma unroll
-      for (int t = 0; t < 8; t += 2) {
-        const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + i0 + t);
-        pre[i0 + t] = v2.x, pre[i0 + t + 1] = v2.y;
-      }
-    }
-    wave_lds_sync();
-    for (uint32_t j0 = 0; j0 < kp; j0 += 8 * kWave) {
-      uint64_t dv[8];
-      uint32_t ss[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const uint32_t j = j0 + t * kWave + lane;
-        dv[t] = j < kp ? p_delta[j] : 0;
-        ss[t] = j < kp ? p_slot[j] : 0;
-      }
-#pragma unroll
-      for (int t = 0; t < 8; ++t)
-        if (dv[t]) atomicAdd(reinterpret_cast<unsigned long long *>(pre + (ss[t] >> sh_top)), (unsigned long long)dv[t]);
-    }
-    wave_lds_sync();
-  }
+  // ---- top level: exclusive prefix sums -> LDS
   uint64_t carry = 0;
   for (uint32_t c0 = 0; c0 < n_top_pad; c0 += 8 * kWave) {
     const uint32_t i0 = c0 + 8 * lane;
     const bool have = i0 < n_top_pad;
     uint64_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (have && kp) {
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = pre[i0 + t];
-    } else if (have && c0 == 0) {
-#pragma unroll
-      for (int t = 0; t < 8; ++t) v[t] = v_top[t];
-    } else if (have) {
+    if (have) {
 #pragma unroll
       for (int t = 0; t < 8; t += 2) {
         const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + i0 + t);
@@ -1115,25 +1012,39 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
     carry += __shfl(incl, kWave - 1, kWave);
   }
   const uint64_t total = carry;
+  bool clamped = false;
+  const uint64_t q_next = a.next_prio ? quantise_priority(prio_next, a.qp, &clamped) : 0;
   wave_lds_sync();
 
   const uint64_t w = total / a.next.k;
-  const uint64_t x = (uint64_t)row * w + __umul64hi(un, w);
-  const PendingDeltas pd{p_slot, p_delta, rd.nlev > 1 ? kp : 0, p_row};
-  const Drawn dr = wave_descend<true>(rd, pre, total, x, pd);
-  write_drawn(a.next, row, dr, head);
+  const uint64_t xs[2] = {(uint64_t)row * w + __umul64hi(un0, w), (uint64_t)(row + 1) * w + __umul64hi(un1, w)};
+  Drawn dr[2];
+  if (second) {
+    wave_descend<2>(rd, pre, total, xs, dr);
+  } else {
+    const uint64_t x1[1] = {xs[0]};
+    Drawn d1[1];
+    wave_descend<1>(rd, pre, total, x1, d1);
+    dr[0] = d1[0];
+    dr[1] = Drawn{~0ull, 0};
+  }
+  write_drawn(a.next, row, dr[0], head);
   if (a.next_prio && lane == 0) {
-    a.next_dq[row] = q_next - dr.mass;
+    // the change this pair brings: none if the next pair has the same slot (the later one counts)
+    const uint64_t delta = dr[1].slot != dr[0].slot ? q_next - dr[0].mass : 0;
+    a.next_dq[row] = delta;
+    add_delta(a.wr, (uint32_t)dr[0].slot, delta);
     if (clamped) atomic_add_u64(&a.st->n_clamped, 1);
   }
   __builtin_amdgcn_s_setprio(0);
 }
 
 // No barrier anywhere: the waves of a workgroup run independently.
-//   wave 0       draws sample `row` of the next batch; copies too only when the other waves cannot
-//                hold the whole row (its dependent loads would queue behind the row loads)
-//   wave 1       lane 0 carries pair `row` of this batch and of the batch before into the written
-//                copy; lanes 1, 2 gather ret and gacc of the row
+//   wave 0       draws sample `row` of the next batch and writes its change into the written copy;
+//                copies too only when the other waves cannot hold the whole row (its dependent
+//                loads would queue behind the row loads)
+//   wave 1       lane 0 carries the change of pair `row` of this batch into the written copy;
+//                lanes 1, 2 gather ret and gacc of the row
 //   wave 2       gathers the action bytes of the row
 //   wave 3       in the first ceil(k / 64) workgroups: importance weights of 64 samples
 // Dynamic LDS: see draw_in_first_wave.
@@ -1151,23 +1062,13 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   }
   const uint32_t my_slot = a.slot[row];
   // The drawing wave's first loads are to reach the memory pipeline ahead of the row loads: the
-  // other waves wait a few hundred cycles (longer when the pending changes are loaded as well).
-  if (draw && write_back) __builtin_amdgcn_s_sleep(12);
-  else if (draw) __builtin_amdgcn_s_sleep(4);
+  // other waves wait a few hundred cycles.
+  if (draw) __builtin_amdgcn_s_sleep(6);
 
   // ---- small loads first, so that nothing that uses them waits for the row
   const bool carrier = write_back && tid == kWave;
-  uint32_t pc_next = 0xfffffffeu, pp_slot = 0, pp_next = 0xfffffffeu;
-  uint64_t pc_dq = 0, pp_dq = 0;
-  if (carrier) {
-    if (row + 1 < a.k) pc_next = a.slot[row + 1];
-    pc_dq = a.dq[row];
-    if (a.prev_dq) {
-      pp_slot = a.prev_slot[row];
-      if (row + 1 < a.k) pp_next = a.prev_slot[row + 1];
-      pp_dq = a.prev_dq[row];
-    }
-  }
+  uint64_t pc_dq = 0;
+  if (carrier) pc_dq = a.dq[row];  // 0 if a later pair of the batch has the same slot
   float small = 0.0f;
   if (tid == kWave + 1 && a.ret_out) small = a.ret[my_slot];
   if (tid == kWave + 2 && a.gacc_out) small = a.gacc[my_slot];
@@ -1207,13 +1108,7 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
     if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
   }
 
-  if (carrier) {
-    if (pc_next != my_slot) {
-      add_delta(a.wr, my_slot, pc_dq);
-      if (!draw) add_delta(a.next.tv, my_slot, pc_dq);  // last launch of a sequence: nothing reads the other copy
-    }
-    if (pp_next != pp_slot) add_delta(a.wr, pp_slot, pp_dq);  // pp_dq = 0 without a batch before
-  }
+  if (carrier) add_delta(a.wr, my_slot, pc_dq);
   if (tid == kWave + 1 && a.ret_out) a.ret_out[row] = small;
   if (tid == kWave + 2 && a.gacc_out) a.gacc_out[row] = small;
   if (act_early) {
@@ -1237,6 +1132,20 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   if (wave == 2 && a.act_out && !act_early)  // long action rows: after the row, which they would hold up
     for (uint32_t by = lane; by < a.act_bytes; by += kWave)
       a.act_out[(uint64_t)row * a.act_bytes + by] = a.act[(uint64_t)my_slot * a.act_bytes + by];
+}
+
+// The changes of the first batch of a sequence of fused steps into the tree (the batch was drawn, and
+// new mass - mass as drawn written to dq, by the launch before): one pair per lane.  A pair that the
+// next pair overrides (same slot) brings no change; dq is rewritten accordingly for the launch after.
+__global__ __launch_bounds__(256) void apply_first_deltas_kernel(TreeView tv, const uint32_t *slot, uint64_t *dq,
+                                                                 uint32_t k)
+{
+  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= k) return;
+  const uint32_t sj = slot[j];
+  const uint64_t d = (j + 1 == k || slot[j + 1] != sj) ? dq[j] : 0;
+  dq[j] = d;
+  add_delta(tv, sj, d);
 }
 
 // dst[i] = src[i]: brings the second copy of the tree up to date
