@@ -462,10 +462,9 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
 
 namespace {
 
-// first_prio, first_dq: see SampleArgs (null for a plain draw).
 int sample_begin_impl(apex_replay *r, uint32_t num_batches, uint32_t k, const uint64_t *rnd, uint64_t *key_out,
                       uint32_t *slot_out, uint64_t *mass_out, void *act_out, float *ret_out, float *gacc_out,
-                      const float *first_prio, uint64_t *first_dq, hipStream_t stream)
+                      hipStream_t stream)
 {
   if (!r || !num_batches || !k || !rnd || !slot_out || !mass_out) return APEX_ERR_INVALID_ARG;
   if (num_batches > APEX_MAX_BATCHES_PER_CALL || (uint64_t)num_batches * k > APEX_MAX_SAMPLES_PER_CALL)
@@ -488,10 +487,6 @@ int sample_begin_impl(apex_replay *r, uint32_t num_batches, uint32_t k, const ui
   a.act_out = static_cast<uint8_t *>(act_out);
   a.ret_out = ret_out;
   a.gacc_out = gacc_out;
-  a.first_prio = first_prio;
-  a.first_dq = first_dq;
-  a.qp = r->qp;
-  a.counters = r->state();
   // every workgroup stages the whole top level: with a large top and many samples, larger workgroups
   // (16 samples each) stage it fewer times
   const uint32_t waves = (r->tv.n_top > 1024 && (uint64_t)num_batches * k >= 1024) ? 16 : 4;
@@ -507,8 +502,8 @@ int apex_replay_sample_begin(apex_replay_t *r, uint32_t num_batches, uint32_t k,
                              uint64_t *key_out, uint32_t *slot_out, uint64_t *mass_out, void *act_out, float *ret_out,
                              float *gacc_out, void *hip_stream)
 {
-  return sample_begin_impl(r, num_batches, k, rnd, key_out, slot_out, mass_out, act_out, ret_out, gacc_out, nullptr,
-                           nullptr, static_cast<hipStream_t>(hip_stream));
+  return sample_begin_impl(r, num_batches, k, rnd, key_out, slot_out, mass_out, act_out, ret_out, gacc_out,
+                           static_cast<hipStream_t>(hip_stream));
 }
 
 namespace {
@@ -581,31 +576,42 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
 }
 
 int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64_t *rnd, const float *new_prio,
-                const apex_batch_buffers_t *sets, uint32_t depth, uint32_t first_set, bool always_copy,
-                hipStream_t stream)
+                const apex_batch_buffers_t *sets, uint32_t depth, uint32_t first_set, hipStream_t stream)
 {
   const auto idx = [&](uint32_t i) { return (first_set + i) % depth; };
   const auto set = [&](uint32_t i) -> const apex_batch_buffers_t & { return sets[idx(i)]; };
   const apex_batch_buffers_t &b0 = set(0);
-  int rc = sample_begin_impl(r, 1, k, rnd, b0.key, b0.slot, b0.mass, b0.act, b0.ret, b0.gacc, new_prio,
-                             new_prio ? r->stepq(idx(0)) : nullptr, stream);
-  if (rc != APEX_OK) return rc;
-  // Only sequences of three steps or more draw from the second copy of the tree; shorter ones leave it
-  // as it is (in step, or stale and marked so).
-  const bool in_step = !always_copy && r->second_version == r->tree_version;
-  const bool reads_second = n >= 3;
-  if (new_prio) {
-    if (reads_second && !in_step)
-      copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
-    // the first batch's changes into the first copy (the second one gets them from the first step launch)
-    apply_first_deltas_kernel<<<dim3(blocks_for(k, 256)), dim3(256), 0, stream>>>(r->tv, b0.slot, r->stepq(idx(0)), k);
-    APEX_HIP(hipGetLastError());
-  }
   const size_t lds = round_up(r->tv.n_top, kFanout) * 8;
+  if (new_prio) {
+    // Launch i reads one copy of the tree and writes the other; the first draw is launch "-1" of that
+    // scheme (it reads the first copy and writes the first batch's changes into the second), so both
+    // copies have to be equal before it.
+    if (r->second_version != r->tree_version)
+      copy_words_kernel<<<dim3(2048), dim3(256), 0, stream>>>(r->tv2.level[0], r->tv.level[0], r->geo.tree_words);
+    StepArgs a{};
+    a.k = k;
+    a.qp = r->qp;
+    a.st = r->state();
+    a.wr = r->tv2;
+    a.next.tv = r->tv;
+    a.next.st = r->state();
+    a.next.k = k;
+    a.next.rnd = rnd;
+    a.next.key_out = b0.key;
+    a.next.slot_out = b0.slot;
+    a.next.mass = b0.mass;
+    a.next_prio = new_prio;
+    a.next_dq = r->stepq(idx(0));
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll><<<dim3(k), dim3(kWave), lds, stream>>>(a);
+    APEX_HIP(hipGetLastError());
+  } else {
+    const int rc = sample_begin_impl(r, 1, k, rnd, b0.key, b0.slot, b0.mass, nullptr, nullptr, nullptr, stream);
+    if (rc != APEX_OK) return rc;
+  }
   for (uint32_t i = 0; i < n; ++i) {
     const apex_batch_buffers_t &b = set(i);
-    const TreeView &rd = (new_prio && (i & 1)) ? r->tv2 : r->tv;
-    const TreeView &wr = (new_prio && (i & 1)) ? r->tv : r->tv2;
+    const TreeView &rd = (new_prio && !(i & 1)) ? r->tv2 : r->tv;
+    const TreeView &wr = (new_prio && !(i & 1)) ? r->tv : r->tv2;
     StepArgs a{};
     a.src = r->obs();
     a.dst = static_cast<uint8_t *>(b.obs);
@@ -643,10 +649,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     learner_step_kernel<u32x4, kStepThreads, kStepUnroll><<<dim3(k), dim3(kStepThreads), lds, stream>>>(a);
   }
   // (every change has now been applied to both copies)
-  if (new_prio) {
-    ++r->tree_version;
-    if (reads_second || in_step) r->second_version = r->tree_version;
-  }
+  if (new_prio) r->second_version = ++r->tree_version;
   APEX_HIP(hipGetLastError());
   return APEX_OK;
 }

@@ -748,11 +748,6 @@ struct SampleArgs {
   uint8_t *act_out;
   float *ret_out, *gacc_out;
   // not null (one batch only): the new priorities of the batch being drawn; their mass differences
-  // Q(prio) - mass as drawn go to first_dq, for a sequence of fused learner steps
-  const float *first_prio;
-  uint64_t *first_dq;
-  QuantParams qp;
-  DeviceState *counters;
 };
 
 // Turns pre[0, n_top) (LDS, the top level's masses, complete and visible) into exclusive prefix sums in
@@ -889,14 +884,6 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
     wave_descend<1>(tv, pre, total, xs, drs);
     const Drawn dr = drs[0];
     write_drawn(a, o, dr, head);
-    if (a.first_prio) {
-      bool clamped;
-      const uint64_t q = quantise_priority(a.first_prio[o], a.qp, &clamped);
-      if (lane_id() == 0) {
-        a.first_dq[o] = q - dr.mass;
-        if (clamped) atomic_add_u64(&a.counters->n_clamped, 1);
-      }
-    }
   }
 }
 
@@ -911,8 +898,9 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
 // batch i, and writes copy W, which holds those up to batch i-1: workgroup j adds the change of
 // pair j of batch i (known from the launch before) and of pair j of batch i+1 (which it has just
 // drawn) to W with atomics.  The next launch reads W and writes R: every change is applied twice,
-// once to each copy, in consecutive launches.  Before the first launch of a sequence the changes
-// of its first batch are applied to the first copy by a small launch of their own.
+// once to each copy, in consecutive launches.  The first batch of a sequence is drawn by a launch
+// of the same kernel that has nothing to gather yet (slot == null, one wave per workgroup), which
+// needs both copies equal when it starts.
 //
 // Within a batch the drawn slots do not decrease (the strata are ordered), so the pairs that
 // share a slot are neighbours and the last of them is the one that counts: the wave that draws
@@ -1055,6 +1043,10 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   const uint32_t row = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
   const uint32_t wave = tid / kWave, lane = lane_id();
   const bool write_back = a.dq != nullptr, draw = a.next.rnd != nullptr;
+  if (!a.slot) {  // the first draw of a sequence (one wave per workgroup): no batch to gather yet
+    if (draw && wave == 0) draw_in_first_wave(a, row, lds);
+    return;
+  }
   const uint32_t first = (draw && a.vecs_per_row <= (nthr - kWave) * kUnroll) ? kWave : 0;
   if (draw && wave == 0) {
     draw_in_first_wave(a, row, lds);
@@ -1132,20 +1124,6 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   if (wave == 2 && a.act_out && !act_early)  // long action rows: after the row, which they would hold up
     for (uint32_t by = lane; by < a.act_bytes; by += kWave)
       a.act_out[(uint64_t)row * a.act_bytes + by] = a.act[(uint64_t)my_slot * a.act_bytes + by];
-}
-
-// The changes of the first batch of a sequence of fused steps into the tree (the batch was drawn, and
-// new mass - mass as drawn written to dq, by the launch before): one pair per lane.  A pair that the
-// next pair overrides (same slot) brings no change; dq is rewritten accordingly for the launch after.
-__global__ __launch_bounds__(256) void apply_first_deltas_kernel(TreeView tv, const uint32_t *slot, uint64_t *dq,
-                                                                 uint32_t k)
-{
-  const uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= k) return;
-  const uint32_t sj = slot[j];
-  const uint64_t d = (j + 1 == k || slot[j + 1] != sj) ? dq[j] : 0;
-  dq[j] = d;
-  add_delta(tv, sj, d);
 }
 
 // dst[i] = src[i]: brings the second copy of the tree up to date

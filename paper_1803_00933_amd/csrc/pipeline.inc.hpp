@@ -185,7 +185,7 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
   const uint64_t per = (uint64_t)p->nb * p->k;
   if (n && fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) {
     APEX_TRY(fused_steps(p->r, n, p->k, beta, rnd, new_prio, p->sets.data(), p->depth,
-                         (uint32_t)(p->step % p->depth), p->capturing, p->tree));
+                         (uint32_t)(p->step % p->depth), p->tree));
     p->step += n;
     return APEX_OK;
   }
@@ -279,6 +279,7 @@ int apex_pipeline_capture_begin(apex_pipeline_t *p)
   forget_marks(p);
   APEX_HIP(hipStreamBeginCapture(p->tree, hipStreamCaptureModeRelaxed));
   p->capturing = true;
+  p->r->second_version = 0;  // a replay cannot know the state it starts from: the record refreshes the second copy first
   // fork the add stream into the capture
   apex_pipeline::Mark origin;
   int rc = mark_record(p, origin, p->tree);
