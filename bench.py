@@ -124,15 +124,17 @@ class GpuJob:
     def setup_pipeline(self):
         self.pipe = self.apex.Pipeline(self.rep, 8, 1, self.w.k)
 
-    def issue_windows(self, first, count):
-        """Same order of tree operations as run(): draw s, update s, [publish the add round], [evict]."""
+    def issue_windows(self, first, count, in_place=False):
+        """Same order of tree operations as run(): draw s, update s, [publish the add round], [evict].
+        in_place: the observations of the add rounds are not copied (a producer is taken to have written
+        them into the ring itself; the other columns and the priorities are handled as usual)."""
         w, pipe = self.w, self.pipe
         assert first % ADD_EVERY == 0 and count % ADD_EVERY == 0
         for f in range(first, first + count, ADD_EVERY):
             t = self.rounds[(f // ADD_EVERY) % self.n_pool]
             prio, ret, gacc, _ = t["out"]
             rc = pipe.add_begin(t["q_online"], t["q_target"], t["action"], t["reward"], t["discount"], w.n,
-                                self.obs_stage, t["act"], prio, ret, gacc)
+                                None if in_place else self.obs_stage, t["act"], prio, ret, gacc)
             assert rc == 0, rc
             rc, _ = pipe.steps(ADD_EVERY, w.beta, self.rnd[f:f + ADD_EVERY], self.td[f:f + ADD_EVERY])
             assert rc == 0, rc
@@ -177,9 +179,9 @@ class GpuJob:
         pipe.close()
         return dt / (calls * nb) * 1e6
 
-    def run_pipelined(self, first, count):
+    def run_pipelined(self, first, count, in_place=False):
         assert self.pipe.fork() == 0
-        self.issue_windows(first, count)
+        self.issue_windows(first, count, in_place)
         assert self.pipe.join() == 0
 
     def capture_cycle(self, first):
@@ -201,6 +203,11 @@ class GpuJob:
         t_host = time.perf_counter() - t0
         torch.cuda.synchronize()
         return time.perf_counter() - t0, t_host
+
+    def timed_median(self, fn, reps=5):
+        """(median wall time, its host-enqueue time, all wall times) over `reps` runs of fn."""
+        runs = sorted(self.timed(fn) for _ in range(reps))
+        return runs[reps // 2][0], runs[reps // 2][1], [r[0] for r in runs]
 
     def step_kernel_us(self, first, count):
         """Average time per launch of the dominant kernel as it runs in the timed loop: the learner-step launch
@@ -580,10 +587,14 @@ def main():
     dt_learner, _ = job.timed(lambda: job.run(W + K, K, with_actors=False))
     log("one stream, learner steps only: %.2f us/step" % (dt_learner / K * 1e6))
     # (2) the library's pipeline (one launch per learner step; add payloads on a second stream)
-    dt_pipe, host_pipe = job.timed(lambda: job.run_pipelined(W, K))
-    log("pipeline, two streams: %.2f us/step (host enqueue %.2f us/step)" % (dt_pipe / K * 1e6, host_pipe / K * 1e6))
-    dt_pipe_learner, _ = job.timed(lambda: job.run_pipelined_learner_only(W + K, K))
-    log("pipeline, learner steps only: %.2f us/step" % (dt_pipe_learner / K * 1e6))
+    dt_pipe, host_pipe, reps_pipe = job.timed_median(lambda: job.run_pipelined(W, K))
+    log("pipeline, two streams: %.2f us/step, median of %d runs (%s; host enqueue %.2f us/step)"
+        % (dt_pipe / K * 1e6, len(reps_pipe), " ".join("%.2f" % (t / K * 1e6) for t in reps_pipe), host_pipe / K * 1e6))
+    dt_pipe_learner, _, _ = job.timed_median(lambda: job.run_pipelined_learner_only(W + K, K))
+    log("pipeline, learner steps only: %.2f us/step (median of 5)" % (dt_pipe_learner / K * 1e6))
+    dt_in_place, _, _ = job.timed_median(lambda: job.run_pipelined(W, K, in_place=True))
+    log("pipeline, observations of the add rounds written in place by their producer (no copy): %.2f us/step"
+        % (dt_in_place / K * 1e6))
     us16 = job.prefetch16_us_per_batch(K, with_actors=False)
     us16_full = job.prefetch16_us_per_batch(K, with_actors=True)
     log("pipeline, 16 batches of 512 per call: %.2f us per batch learner only, %.2f with adds and eviction"
@@ -592,7 +603,7 @@ def main():
     # (3) one cycle of the same pipeline captured as a HIP graph and replayed
     job.capture_cycle(W)
     job.run_replays(max(1, W // EVICT_EVERY))
-    dt_graph, host_graph = job.timed(lambda: job.run_replays(K // EVICT_EVERY))
+    dt_graph, host_graph, reps_graph = job.timed_median(lambda: job.run_replays(K // EVICT_EVERY))
     assert job.rep.resync() == 0
     log("pipeline, graph replays: %.2f us/step (host %.2f us/step)" % (dt_graph / K * 1e6, host_graph / K * 1e6))
     if dt_graph < dt:
@@ -637,8 +648,12 @@ def main():
         "adds_per_s": w.add_count * (K // ADD_EVERY) / dt,
         "nstep_priorities_per_s": w.add_count / (ops["nstep_priorities_18000"] * 1e-6),
         "ops_us": ops,
+        "repetitions": {"n": 5, "value_is": "median",
+                        "pipeline_us_per_step": [t / K * 1e6 for t in reps_pipe],
+                        "pipeline_graph_us_per_step": [t / K * 1e6 for t in reps_graph]},
         "variants_us_per_step": {"one_stream": dt_serial / K * 1e6, "one_stream_learner_only": dt_learner / K * 1e6,
                                  "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6,
+                                 "pipeline_add_payload_in_place": dt_in_place / K * 1e6,
                                  "pipeline_16_batches_per_call_learner_only": us16,
                                  "pipeline_16_batches_per_call": us16_full},
         "hbm_frac_of_step": {name: STEP_ALGORITHMIC_BYTES / (us * 1e-6) / 1e9 / HBM_PEAK_GBS

@@ -162,6 +162,12 @@ int apex_replay_add(apex_replay_t *r, uint64_t count, const void *obs, const voi
  * and publishes nothing; apex_replay_add_publish enters the same count keys into the sum tree and
  * advances tail.  The publish must be ordered after its payload (same stream, or an event), and
  * one payload/publish pair must complete before the next payload call is issued.
+ *
+ * Adding without a copy: a producer (a DMA from the host, a kernel of the caller's) may write a
+ * column of the coming keys into the ring itself and pass NULL for it.  Key tail + i lives in
+ * row (tail + i) mod max_slots of every column (apex_replay_layout gives the columns' offsets in
+ * d_storage; tail is first_key_out + count of the last add, or apex_replay_stats).  No call
+ * reads or writes the rows of keys that are not published yet.
  */
 int apex_replay_add_payload(apex_replay_t *r, uint64_t count, const void *obs, const void *act, const float *ret,
                             const float *gacc, void *hip_stream);

@@ -57,11 +57,18 @@ constexpr uint64_t kWideStepBytes = 8u << 20;  // ... and only if the gather mov
 
 bool new_event(hipEvent_t *e) { return !hip_failed(hipEventCreateWithFlags(e, hipEventDisableTiming)); }
 
+// Events that only order the pipeline's two streams on this device: no system-scope fence when
+// they are recorded (the host and other devices never wait on them).
+bool new_mark_event(hipEvent_t *e)
+{
+  return !hip_failed(hipEventCreateWithFlags(e, hipEventDisableTiming | hipEventDisableSystemFence));
+}
+
 int mark_record(apex_pipeline *p, apex_pipeline::Mark &m, hipStream_t s)
 {
   hipEvent_t e = m.own;
   if (p->capturing) {
-    if (!new_event(&e)) return APEX_ERR_HIP;
+    if (!new_mark_event(&e)) return APEX_ERR_HIP;
     p->capture_events.push_back(e);
   }
   APEX_HIP(hipEventRecord(e, s));
@@ -135,13 +142,13 @@ int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buff
   bool ok = true;
   for (hipStream_t *s : {&p->tree, &p->add})
     ok = ok && !hip_failed(hipStreamCreateWithFlags(s, hipStreamNonBlocking));  // default priority
-  ok = ok && new_event(&p->payload_done.own) && new_event(&p->tail_ready.own) && new_event(&p->fork_ev) &&
-       new_event(&p->join_ev) && new_event(&p->drawn.own);
+  ok = ok && new_mark_event(&p->payload_done.own) && new_mark_event(&p->tail_ready.own) && new_event(&p->fork_ev) &&
+       new_event(&p->join_ev) && new_mark_event(&p->drawn.own);
   p->wide = (uint64_t)num_batches * k >= kWideStepSamples && depth >= 2 &&
             (uint64_t)num_batches * k * r->cfg.obs_bytes >= kWideStepBytes;
   if (p->wide) {
     p->gathered.resize(depth);
-    for (apex_pipeline::Mark &m : p->gathered) ok = ok && new_event(&m.own);
+    for (apex_pipeline::Mark &m : p->gathered) ok = ok && new_mark_event(&m.own);
   }
   if (!ok) {
     pipeline_free(p);

@@ -77,6 +77,31 @@ def test_random_operation_sequences(P, C, ob, ab):
         sample_both(g, o, rng, 2, 64)
 
 
+@pytest.mark.parametrize("P,C,ob,ab", [(5000, 4000, 48, 8), (3000, 2500, 4112, 4)])
+def test_add_with_payload_written_in_place(P, C, ob, ab):
+    """A producer writes observations and actions of the coming keys straight into the ring (row
+    (tail + i) mod P of each column) and adds with NULL for those columns: same memory as a copying add."""
+    rng = np.random.default_rng(P + ob)
+    g, o = make_pair(C, P, ob, ab)
+    for it in range(7):     # wraps around the ring
+        cnt = int(rng.integers(1, P - o.size + 1)) if o.size < P else 0
+        if cnt:
+            obs = rng.integers(0, 256, (cnt, ob), dtype=np.uint8)
+            act = rng.integers(0, 256, (cnt, ab), dtype=np.uint8)
+            ret, gacc = rng.standard_normal(cnt).astype(F32), rng.random(cnt).astype(F32)
+            prio = rng.lognormal(0, 1, cnt).astype(F32)
+            rows = torch.from_numpy(((o.tail + np.arange(cnt)) % P).astype(np.int64)).cuda()
+            g.obs_view().index_copy_(0, rows, dev(obs))
+            g.act_view().index_copy_(0, rows, dev(act))
+            assert o.add(prio, obs, act, ret, gacc)[0] == 0
+            rc, first = g.add(dev(prio), None, None, dev(ret), dev(gacc))
+            assert (rc, first) == (0, o.tail - cnt)
+        check_gpu_tree(g, o)
+        sample_both(g, o, rng, 2, 96)
+        assert g.evict() == o.evict()
+    sample_both(g, o, rng, 8, 500)      # the payload of most live keys, as the oracle stored it
+
+
 def test_large_update_batches_with_heavy_duplication():
     # more than one workgroup's worth of pairs: the two-pass path; few distinct keys: many repeats
     rng = np.random.default_rng(10)
