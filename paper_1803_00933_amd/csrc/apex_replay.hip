@@ -567,12 +567,23 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
 {
   const uint64_t row_bytes = r->cfg.obs_bytes;
   const uint64_t vpr = row_bytes / sizeof(u32x4);
-  if (num_batches != 1 || k > kStepMaxK || depth < 3 || depth > kStepSets || r->tv.n_top > kStepMaxTop) return false;
+  if (num_batches != 1 || k > kStepMaxK || depth < 3 || depth > kStepSets) return false;
   if (row_bytes % sizeof(u32x4) || vpr > (uint64_t)kStepThreads * kStepUnroll) return false;
   if ((uintptr_t)r->obs() & 15) return false;
   for (uint32_t i = 0; i < depth; ++i)
     if (((uintptr_t)sets[i].obs | (uintptr_t)sets[i].slot) & 15) return false;
   return true;
+}
+
+void launch_step(const StepArgs &a, uint32_t n_top, uint32_t k, uint32_t threads, size_t lds, hipStream_t stream)
+{
+  const dim3 grid(k), block(threads);
+  if (n_top <= 8 * kWave)
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1><<<grid, block, lds, stream>>>(a);
+  else if (n_top <= 16 * kWave)
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 2><<<grid, block, lds, stream>>>(a);
+  else
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 4><<<grid, block, lds, stream>>>(a);
 }
 
 int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64_t *rnd, const float *new_prio,
@@ -602,7 +613,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     a.next.mass = b0.mass;
     a.next_prio = new_prio;
     a.next_dq = r->stepq(idx(0));
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll><<<dim3(k), dim3(kWave), lds, stream>>>(a);
+    launch_step(a, r->tv.n_top, k, kWave, lds, stream);
     APEX_HIP(hipGetLastError());
   } else {
     const int rc = sample_begin_impl(r, 1, k, rnd, b0.key, b0.slot, b0.mass, nullptr, nullptr, nullptr, stream);
@@ -646,7 +657,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
         a.next_dq = r->stepq(idx(i + 1));
       }
     }
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll><<<dim3(k), dim3(kStepThreads), lds, stream>>>(a);
+    launch_step(a, r->tv.n_top, k, kStepThreads, lds, stream);
   }
   // (every change has now been applied to both copies)
   if (new_prio) r->second_version = ++r->tree_version;

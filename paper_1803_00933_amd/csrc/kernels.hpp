@@ -928,7 +928,6 @@ __device__ __forceinline__ void wave_lds_sync()
 constexpr int kStepThreads = 512;
 constexpr int kStepUnroll = 4;
 constexpr uint32_t kStepMaxK = 1024;    // pairs per batch that the fused step handles (size of its scratch rows)
-constexpr uint32_t kStepMaxTop = 1024;  // top-level nodes that its single drawing wave stages
 
 struct StepArgs {
   // gather of batch i: row j of dst = row slot[j] of src; the small columns likewise
@@ -956,9 +955,10 @@ struct StepArgs {
 typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
 // The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier: the
-// top level (eight consecutive nodes per lane and pass, 16-byte loads) into registers, its prefix
+// top level (eight consecutive nodes per lane and pass of 512, 16-byte loads) into registers, its prefix
 // sums into LDS, two walks down, outputs, and the change that the sample's new priority brings.
 // LDS: round_up(n_top, 64) words of 8 bytes.
+template <int kTopChunk>
 __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *pre)
 {
   const TreeView &rd = a.next.tv;
@@ -972,32 +972,40 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
   const uint64_t head = a.next.st->head;
   const uint64_t *top = rd.level[rd.nlev - 1];
 
-  // ---- top level: exclusive prefix sums -> LDS
+  // ---- top level: exclusive prefix sums -> LDS; the loads of kTopChunk passes go out together
   uint64_t carry = 0;
-  for (uint32_t c0 = 0; c0 < n_top_pad; c0 += 8 * kWave) {
-    const uint32_t i0 = c0 + 8 * lane;
-    const bool have = i0 < n_top_pad;
-    uint64_t v[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    if (have) {
+  for (uint32_t c0 = 0; c0 < n_top_pad; c0 += kTopChunk * 8 * kWave) {
+    uint64_t v[kTopChunk][8];
 #pragma unroll
-      for (int t = 0; t < 8; t += 2) {
-        const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + i0 + t);
-        v[t] = v2.x, v[t + 1] = v2.y;
+    for (int p = 0; p < kTopChunk; ++p) {
+      const uint32_t i0 = c0 + p * 8 * kWave + 8 * lane;
+#pragma unroll
+      for (int t = 0; t < 8; ++t) v[p][t] = 0;
+      if (i0 < n_top_pad) {
+#pragma unroll
+        for (int t = 0; t < 8; t += 2) {
+          const u64x2 v2 = *reinterpret_cast<const u64x2 *>(top + i0 + t);
+          v[p][t] = v2.x, v[p][t + 1] = v2.y;
+        }
       }
     }
-    uint64_t mine = 0;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) mine += v[t];
-    const uint64_t incl = wave_inclusive_scan(mine);
-    uint64_t run = carry + incl - mine;
-    if (have) {
+    for (int p = 0; p < kTopChunk; ++p) {
+      const uint32_t i0 = c0 + p * 8 * kWave + 8 * lane;
+      uint64_t mine = 0;
 #pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        pre[i0 + t] = run;
-        run += v[t];
+      for (int t = 0; t < 8; ++t) mine += v[p][t];
+      const uint64_t incl = wave_inclusive_scan(mine);
+      uint64_t run = carry + incl - mine;
+      if (i0 < n_top_pad) {
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+          pre[i0 + t] = run;
+          run += v[p][t];
+        }
       }
+      carry += __shfl(incl, kWave - 1, kWave);
     }
-    carry += __shfl(incl, kWave - 1, kWave);
   }
   const uint64_t total = carry;
   bool clamped = false;
@@ -1036,7 +1044,9 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
 //   wave 2       gathers the action bytes of the row
 //   wave 3       in the first ceil(k / 64) workgroups: importance weights of 64 samples
 // Dynamic LDS: see draw_in_first_wave.
-template <typename Vec, int kThreads, int kUnroll>
+// kTopChunk: passes of 512 top-level nodes whose loads the drawing wave issues together (1 for tops of at
+// most 512 nodes, 2 up to 1024, 4 beyond: more registers, fewer memory round trips).
+template <typename Vec, int kThreads, int kUnroll, int kTopChunk>
 __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
 {
   extern __shared__ uint64_t lds[];
@@ -1044,12 +1054,12 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   const uint32_t wave = tid / kWave, lane = lane_id();
   const bool write_back = a.dq != nullptr, draw = a.next.rnd != nullptr;
   if (!a.slot) {  // the first draw of a sequence (one wave per workgroup): no batch to gather yet
-    if (draw && wave == 0) draw_in_first_wave(a, row, lds);
+    if (draw && wave == 0) draw_in_first_wave<kTopChunk>(a, row, lds);
     return;
   }
   const uint32_t first = (draw && a.vecs_per_row <= (nthr - kWave) * kUnroll) ? kWave : 0;
   if (draw && wave == 0) {
-    draw_in_first_wave(a, row, lds);
+    draw_in_first_wave<kTopChunk>(a, row, lds);
     if (first) return;
   }
   const uint32_t my_slot = a.slot[row];

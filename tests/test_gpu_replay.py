@@ -532,7 +532,9 @@ def test_pipeline_graph_replays(nb, k, ob):
     (5000, 4000, 1024, 32768),       # as many samples as a workgroup has lanes, largest fused row
     (5000, 4000, 1, 4224),           # batches of one
     (60_000, 50_000, 512, 256),      # short rows (feature vectors): a few lanes of each workgroup copy
-    (70_000, 60_000, 300, 4224),     # a top level of more than 1024 nodes: two launches per step instead
+    (70_000, 60_000, 300, 4224),     # a top level of 1094 nodes: the drawing wave stages it in chunks of four passes
+    (280_000, 250_000, 256, 1040),   # a ragged top level of 4375 nodes (three chunks)
+    (4608, 4000, 64, 4112),          # one level of the largest size
     (33_000, 30_000, 517, 2064),     # 516 top nodes (two passes of the drawing wave), k no multiple of 8
     (9000, 8000, 1000, 48),          # two passes over the pending pairs, a ragged last one
     (5000, 4000, 100, 4100),         # rows that are no multiple of 16 bytes: two launches per step instead
