@@ -216,6 +216,19 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
 }
 
 
+// One launch of the fused learner step (see learner_step_kernel) for vectors of sizeof(Vec) bytes.
+template <typename Vec>
+void launch_step_t(const StepArgs &a, uint32_t n_top, uint32_t k, uint32_t threads, size_t lds, hipStream_t stream)
+{
+  const dim3 grid(k), block(threads);
+  if (n_top <= 8 * kWave)
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1><<<grid, block, lds, stream>>>(a);
+  else if (n_top <= 16 * kWave)
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 2><<<grid, block, lds, stream>>>(a);
+  else
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 4><<<grid, block, lds, stream>>>(a);
+}
+
 // A small add round (observations of at most 1 KB per row) as one launch: n-step priorities, payload,
 // masses.  Same effect as apex_nstep_priorities + apex_replay_add.  APEX_ERR_NOT_READY - with nothing
 // enqueued - when the rows are too long for it.
@@ -562,28 +575,29 @@ int finish_impl(apex_replay *r, uint32_t num_batches, uint32_t k, float beta, co
 // learner_step_kernel.  Batch i goes to sets[(first_set + i) % depth]; kernel i reads the sets of
 // batches i-1 and i and writes that of batch i+1, hence depth >= 3.
 // Returns APEX_ERR_NOT_READY - with nothing enqueued - when the shapes do not fit the fused launch.
+// The widest vector that the rows of the ring and of the batch buffers allow: 16, 4 or 1 bytes.
+uint32_t step_vector_bytes(const apex_replay *r, uint32_t depth, const apex_batch_buffers_t *sets)
+{
+  uintptr_t mis = (uintptr_t)r->obs() | (uintptr_t)r->cfg.obs_bytes;
+  for (uint32_t i = 0; i < depth; ++i) mis |= (uintptr_t)sets[i].obs;
+  return (mis & 15) == 0 ? 16 : (mis & 3) == 0 ? 4 : 1;
+}
+
 bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uint32_t depth,
                      const apex_batch_buffers_t *sets)
 {
-  const uint64_t row_bytes = r->cfg.obs_bytes;
-  const uint64_t vpr = row_bytes / sizeof(u32x4);
   if (num_batches != 1 || k > kStepMaxK || depth < 3 || depth > kStepSets) return false;
-  if (row_bytes % sizeof(u32x4) || vpr > (uint64_t)kStepThreads * kStepUnroll) return false;
-  if ((uintptr_t)r->obs() & 15) return false;
   for (uint32_t i = 0; i < depth; ++i)
-    if (((uintptr_t)sets[i].obs | (uintptr_t)sets[i].slot) & 15) return false;
+    if ((uintptr_t)sets[i].slot & 15) return false;
   return true;
 }
 
-void launch_step(const StepArgs &a, uint32_t n_top, uint32_t k, uint32_t threads, size_t lds, hipStream_t stream)
+void launch_step(const StepArgs &a, uint32_t vector_bytes, uint32_t n_top, uint32_t k, uint32_t threads, size_t lds,
+                 hipStream_t stream)
 {
-  const dim3 grid(k), block(threads);
-  if (n_top <= 8 * kWave)
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1><<<grid, block, lds, stream>>>(a);
-  else if (n_top <= 16 * kWave)
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 2><<<grid, block, lds, stream>>>(a);
-  else
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 4><<<grid, block, lds, stream>>>(a);
+  if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, k, threads, lds, stream);
+  else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, k, threads, lds, stream);
+  else launch_step_t<uint8_t>(a, n_top, k, threads, lds, stream);
 }
 
 int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64_t *rnd, const float *new_prio,
@@ -593,6 +607,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
   const auto set = [&](uint32_t i) -> const apex_batch_buffers_t & { return sets[idx(i)]; };
   const apex_batch_buffers_t &b0 = set(0);
   const size_t lds = round_up(r->tv.n_top, kFanout) * 8;
+  const uint32_t vb = step_vector_bytes(r, depth, sets);
   if (new_prio) {
     // Launch i reads one copy of the tree and writes the other; the first draw is launch "-1" of that
     // scheme (it reads the first copy and writes the first batch's changes into the second), so both
@@ -613,7 +628,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     a.next.mass = b0.mass;
     a.next_prio = new_prio;
     a.next_dq = r->stepq(idx(0));
-    launch_step(a, r->tv.n_top, k, kWave, lds, stream);
+    launch_step(a, vb, r->tv.n_top, k, kWave, lds, stream);
     APEX_HIP(hipGetLastError());
   } else {
     const int rc = sample_begin_impl(r, 1, k, rnd, b0.key, b0.slot, b0.mass, nullptr, nullptr, nullptr, stream);
@@ -627,7 +642,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     a.src = r->obs();
     a.dst = static_cast<uint8_t *>(b.obs);
     a.row_bytes = r->cfg.obs_bytes;
-    a.vecs_per_row = (uint32_t)(a.row_bytes / sizeof(u32x4));
+    a.vecs_per_row = (uint32_t)(a.row_bytes / vb);
     a.act = r->act();
     a.act_bytes = r->cfg.act_bytes;
     a.ret = r->ret();
@@ -657,7 +672,7 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
         a.next_dq = r->stepq(idx(i + 1));
       }
     }
-    launch_step(a, r->tv.n_top, k, kStepThreads, lds, stream);
+    launch_step(a, vb, r->tv.n_top, k, kStepThreads, lds, stream);
   }
   // (every change has now been applied to both copies)
   if (new_prio) r->second_version = ++r->tree_version;

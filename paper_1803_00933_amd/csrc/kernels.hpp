@@ -933,7 +933,7 @@ struct StepArgs {
   // gather of batch i: row j of dst = row slot[j] of src; the small columns likewise
   const uint8_t *src;
   uint8_t *dst;
-  uint32_t vecs_per_row;  // <= kStepUnroll * kStepThreads
+  uint32_t vecs_per_row;  // vectors of sizeof(Vec) bytes
   uint64_t row_bytes;
   const uint8_t *act;
   uint32_t act_bytes;
@@ -1130,6 +1130,19 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = tid - first + u * copiers;
     if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+  }
+  // rows longer than one pass of the workgroup (more than 32 KB, or narrow vectors)
+  for (uint32_t base = copiers * kUnroll; base < a.vecs_per_row; base += copiers * kUnroll) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = base + tid - first + u * copiers;
+      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = base + tid - first + u * copiers;
+      if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+    }
   }
   if (wave == 2 && a.act_out && !act_early)  // long action rows: after the row, which they would hold up
     for (uint32_t by = lane; by < a.act_bytes; by += kWave)

@@ -537,7 +537,10 @@ def test_pipeline_graph_replays(nb, k, ob):
     (4608, 4000, 64, 4112),          # one level of the largest size
     (33_000, 30_000, 517, 2064),     # 516 top nodes (two passes of the drawing wave), k no multiple of 8
     (9000, 8000, 1000, 48),          # two passes over the pending pairs, a ragged last one
-    (5000, 4000, 100, 4100),         # rows that are no multiple of 16 bytes: two launches per step instead
+    (5000, 4000, 100, 4100),         # rows that are no multiple of 16 bytes: 4-byte vectors, several passes per row
+    (3000, 2500, 64, 1001),          # odd row size: byte copies
+    (3000, 2500, 96, 56448),         # rows longer than one pass of a workgroup (two frame stacks per transition)
+    (3000, 2500, 40, 32784),         # just beyond one pass
 ])
 def test_one_launch_per_learner_step(P, C, k, ob):
     """Sequences of learner steps issued as one launch per step (draw of the next batch inside the launch
