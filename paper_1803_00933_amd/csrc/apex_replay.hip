@@ -218,54 +218,77 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
 
 // One launch of the fused learner step (see learner_step_kernel) for vectors of sizeof(Vec) bytes.
 template <typename Vec>
-void launch_step_t(const StepArgs &a, uint32_t n_top, uint32_t k, uint32_t threads, size_t lds, hipStream_t stream)
+void launch_step_t(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds, hipStream_t stream)
 {
-  const dim3 grid(k), block(threads);
-  if (n_top <= 8 * kWave)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1><<<grid, block, lds, stream>>>(a);
+  const dim3 grid(wgs), block(threads);
+  if (wgs > a.k)  // with an add round in the further workgroups (such a launch draws nothing)
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, true><<<grid, block, lds, stream>>>(a);
+  else if (n_top <= 8 * kWave)
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, false><<<grid, block, lds, stream>>>(a);
   else if (n_top <= 16 * kWave)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 2><<<grid, block, lds, stream>>>(a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 2, false><<<grid, block, lds, stream>>>(a);
   else
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 4><<<grid, block, lds, stream>>>(a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 4, false><<<grid, block, lds, stream>>>(a);
 }
 
 // A small add round (observations of at most 1 KB per row) as one launch: n-step priorities, payload,
-// masses.  Same effect as apex_nstep_priorities + apex_replay_add.  APEX_ERR_NOT_READY - with nothing
-// enqueued - when the rows are too long for it.
-template <typename Vec>
-int add_round_small_t(apex_replay *r, const NstepArgs &ns, const void *obs, const void *act, hipStream_t stream,
-                      bool both)
+// masses.  Same effect as apex_nstep_priorities + apex_replay_add.
+
+// Arguments of such a round for workgroups of `threads` lanes and vectors of vector_bytes bytes;
+// *blocks: the workgroups it takes.
+int add_round_args(const apex_replay *r, const NstepArgs &ns, const void *obs, const void *act, uint32_t vector_bytes,
+                   uint32_t threads, bool both, AddRoundArgs *out, uint32_t *blocks)
 {
   const uint64_t count = (uint64_t)ns.S * ns.T;
-  const uint32_t vpr = (uint32_t)(r->cfg.obs_bytes / sizeof(Vec));
+  const uint32_t vpr = r->cfg.obs_bytes / vector_bytes;
   uint32_t lanes_log2 = 0;
   while ((1u << lanes_log2) < vpr && lanes_log2 < 6) ++lanes_log2;  // at most one wave per row
-  const uint64_t rows_per_block = (uint32_t)kAddRoundThreads >> lanes_log2;
-  const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
-  if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
-  add_round_small_kernel<Vec><<<dim3((uint32_t)blocks), dim3(kAddRoundThreads), 0, stream>>>(
-      ns, r->tv, r->tv2, both, r->state(), r->qp, static_cast<const uint8_t *>(obs), static_cast<const uint8_t *>(act),
-      r->obs(), r->act(), r->ret(), r->gacc(), vpr, lanes_log2, r->cfg.obs_bytes, r->cfg.act_bytes);
-  return hip_failed(hipGetLastError()) ? APEX_ERR_HIP : APEX_OK;
+  const uint64_t rows_per_block = threads >> lanes_log2;
+  const uint64_t nb = (count + rows_per_block - 1) / rows_per_block;
+  if (nb > 0x7ffffff0ull) return APEX_ERR_TOO_LARGE;
+  *blocks = (uint32_t)nb;
+  *out = AddRoundArgs{ns, r->tv, r->tv2, both, r->state(), r->qp, static_cast<const uint8_t *>(obs),
+                      static_cast<const uint8_t *>(act), r->obs(), r->act(), r->ret(), r->gacc(), vpr, lanes_log2,
+                      r->cfg.obs_bytes, r->cfg.act_bytes};
+  return APEX_OK;
 }
 
-int add_round_small(apex_replay *r, const NstepArgs &ns, const void *obs, const void *act, uint64_t *first_key_out,
-                    hipStream_t stream)
+// Whether a round can go that way, and the widest vector its rows allow (16, 4 or 1 bytes).
+bool add_round_small_fits(const apex_replay *r, const NstepArgs &ns, const void *obs, uint32_t *vector_bytes)
 {
-  const uint64_t count = (uint64_t)ns.S * ns.T;
-  if (!obs || r->cfg.obs_bytes > 1024 || count == 0) return APEX_ERR_NOT_READY;
-  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
-  const bool both = r->second_version == r->tree_version;
+  if (!obs || r->cfg.obs_bytes > 1024 || (uint64_t)ns.S * ns.T == 0) return false;
   const uintptr_t mis = (uintptr_t)obs | (uintptr_t)r->obs() | (uintptr_t)r->cfg.obs_bytes;
-  int rc;
-  if ((mis & 15) == 0) rc = add_round_small_t<u32x4>(r, ns, obs, act, stream, both);
-  else if ((mis & 3) == 0) rc = add_round_small_t<uint32_t>(r, ns, obs, act, stream, both);
-  else rc = add_round_small_t<uint8_t>(r, ns, obs, act, stream, both);
-  if (rc != APEX_OK) return rc;
+  *vector_bytes = (mis & 15) == 0 ? 16 : (mis & 3) == 0 ? 4 : 1;
+  return true;
+}
+
+// Host-side bookkeeping of a round that has been enqueued.
+void add_round_published(apex_replay *r, uint64_t count, bool both, uint64_t *first_key_out)
+{
   ++r->tree_version;
   if (both) r->second_version = r->tree_version;
   if (first_key_out) *first_key_out = r->tail;
   r->tail += count;
+}
+
+// APEX_ERR_NOT_READY - with nothing enqueued - when the rows are too long for the single launch.
+int add_round_small(apex_replay *r, const NstepArgs &ns, const void *obs, const void *act, uint64_t *first_key_out,
+                    hipStream_t stream)
+{
+  const uint64_t count = (uint64_t)ns.S * ns.T;
+  uint32_t vb = 0, blocks = 0;
+  if (!add_round_small_fits(r, ns, obs, &vb)) return APEX_ERR_NOT_READY;
+  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  const bool both = r->second_version == r->tree_version;
+  AddRoundArgs a;
+  const int rc = add_round_args(r, ns, obs, act, vb, kAddRoundThreads, both, &a, &blocks);
+  if (rc != APEX_OK) return rc;
+  const dim3 grid(blocks), block(kAddRoundThreads);
+  if (vb == 16) add_round_small_kernel<u32x4><<<grid, block, 0, stream>>>(a);
+  else if (vb == 4) add_round_small_kernel<uint32_t><<<grid, block, 0, stream>>>(a);
+  else add_round_small_kernel<uint8_t><<<grid, block, 0, stream>>>(a);
+  APEX_HIP(hipGetLastError());
+  add_round_published(r, count, both, first_key_out);
   return APEX_OK;
 }
 
@@ -592,16 +615,54 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
   return true;
 }
 
-void launch_step(const StepArgs &a, uint32_t vector_bytes, uint32_t n_top, uint32_t k, uint32_t threads, size_t lds,
+void launch_step(const StepArgs &a, uint32_t vector_bytes, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds,
                  hipStream_t stream)
 {
-  if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, k, threads, lds, stream);
-  else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, k, threads, lds, stream);
-  else launch_step_t<uint8_t>(a, n_top, k, threads, lds, stream);
+  if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, wgs, threads, lds, stream);
+  else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, wgs, threads, lds, stream);
+  else launch_step_t<uint8_t>(a, n_top, wgs, threads, lds, stream);
+}
+
+// A step launch that has been prepared but not issued: the last one of a call, held back while a small
+// add round is open, because the round can ride in the same launch (see StepArgs::add).
+struct HeldStep {
+  bool valid = false;
+  StepArgs a;
+  uint32_t vector_bytes, n_top;
+  size_t lds;
+};
+
+int issue_held_step(HeldStep *h, hipStream_t stream)
+{
+  if (!h->valid) return APEX_OK;
+  h->valid = false;
+  launch_step(h->a, h->vector_bytes, h->n_top, h->a.k, kStepThreads, h->lds, stream);
+  APEX_HIP(hipGetLastError());
+  return APEX_OK;
+}
+
+// The held step and a small add round in one launch.  APEX_ERR_NOT_READY - with nothing enqueued - if
+// there is no held step or the two do not fit together (the round's rows allow only narrower vectors).
+int issue_held_step_with_round(apex_replay *r, HeldStep *h, const NstepArgs &ns, const void *obs, const void *act,
+                               uint64_t *first_key_out, hipStream_t stream)
+{
+  const uint64_t count = (uint64_t)ns.S * ns.T;
+  uint32_t vb = 0, blocks = 0;
+  if (!h->valid || !add_round_small_fits(r, ns, obs, &vb) || vb < h->vector_bytes) return APEX_ERR_NOT_READY;
+  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  const bool both = r->second_version == r->tree_version;
+  const int rc = add_round_args(r, ns, obs, act, h->vector_bytes, kStepThreads, both, &h->a.add, &blocks);
+  if (rc != APEX_OK) return rc;
+  h->valid = false;
+  launch_step(h->a, h->vector_bytes, h->n_top, h->a.k + blocks, kStepThreads, h->lds, stream);
+  APEX_HIP(hipGetLastError());
+  add_round_published(r, count, both, first_key_out);
+  return APEX_OK;
 }
 
 int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64_t *rnd, const float *new_prio,
-                const apex_batch_buffers_t *sets, uint32_t depth, uint32_t first_set, hipStream_t stream)
+                const apex_batch_buffers_t *sets, uint32_t depth, uint32_t first_set, HeldStep *hold,
+                hipStream_t stream)
 {
   const auto idx = [&](uint32_t i) { return (first_set + i) % depth; };
   const auto set = [&](uint32_t i) -> const apex_batch_buffers_t & { return sets[idx(i)]; };
@@ -672,7 +733,15 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
         a.next_dq = r->stepq(idx(i + 1));
       }
     }
-    launch_step(a, vb, r->tv.n_top, k, kStepThreads, lds, stream);
+    if (hold && i + 1 == n) {  // issued by the caller's next call, perhaps together with an add round
+      hold->valid = true;
+      hold->a = a;
+      hold->vector_bytes = vb;
+      hold->n_top = r->tv.n_top;
+      hold->lds = lds;
+    } else {
+      launch_step(a, vb, r->tv.n_top, k, kStepThreads, lds, stream);
+    }
   }
   // (every change has now been applied to both copies)
   if (new_prio) r->second_version = ++r->tree_version;

@@ -33,12 +33,14 @@ struct DeviceState {
 // Called by every thread of every workgroup of a launch once it has read what it needs of head or
 // tail: the workgroup that arrives last moves that counter on, so that the launch needs no
 // follow-up launch for it (the ticket is back at 0 afterwards).  Contains a barrier.
-__device__ __forceinline__ void advance_state_when_all_done(uint32_t *ticket, uint64_t *counter, uint64_t inc)
+// n_wgs: the workgroups that take part (all of the launch unless stated).
+__device__ __forceinline__ void advance_state_when_all_done(uint32_t *ticket, uint64_t *counter, uint64_t inc,
+                                                            uint32_t n_wgs = gridDim.x)
 {
   __syncthreads();
   if (threadIdx.x == 0) {
     const uint32_t t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (t == gridDim.x - 1) {
+    if (t == n_wgs - 1) {
       *ticket = 0;
       *counter += inc;
     }
@@ -590,47 +592,67 @@ __global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, TreeView t
 // whole waves of 64 neighbouring transitions, so that a node receives one atomic per 64 of them.
 constexpr int kAddRoundThreads = 1024;
 
+struct AddRoundArgs {
+  NstepArgs ns;
+  TreeView tv, tv2;
+  bool both;  // tv2 receives the same masses
+  DeviceState *st;
+  QuantParams qp;
+  const uint8_t *obs, *act;  // [S*T, obs_bytes], [S*T, act_bytes] (act may be null)
+  uint8_t *obs_ring, *act_ring;
+  float *ret_ring, *gacc_ring;
+  uint32_t vecs_per_row, lanes_log2;
+  uint64_t obs_bytes;
+  uint32_t act_bytes;
+};
+
+// Workgroup blk of n_wgs of such a round; sh_slot, sh_q: blockDim words of LDS each.
 template <typename Vec>
-__global__ __launch_bounds__(kAddRoundThreads) void add_round_small_kernel(
-    NstepArgs ns, TreeView tv, TreeView tv2, bool both, DeviceState *__restrict__ st, QuantParams qp,
-    const uint8_t *__restrict__ obs, const uint8_t *__restrict__ act, uint8_t *__restrict__ obs_ring,
-    uint8_t *__restrict__ act_ring, float *__restrict__ ret_ring, float *__restrict__ gacc_ring, uint32_t vecs_per_row,
-    uint32_t lanes_log2, uint64_t obs_bytes, uint32_t act_bytes)
+__device__ __forceinline__ void add_round_small_block(const AddRoundArgs &a, uint32_t blk, uint32_t n_wgs,
+                                                      uint64_t *sh_slot, uint64_t *sh_q)
 {
-  __shared__ uint64_t sh_slot[kAddRoundThreads], sh_q[kAddRoundThreads];
-  const uint32_t rows_per_block = blockDim.x >> lanes_log2, lanes = 1u << lanes_log2;
-  const uint32_t r = threadIdx.x >> lanes_log2;  // row of this workgroup
-  const uint64_t i = (uint64_t)blockIdx.x * rows_per_block + r;
+  const uint32_t rows_per_block = blockDim.x >> a.lanes_log2, lanes = 1u << a.lanes_log2;
+  const uint32_t r = threadIdx.x >> a.lanes_log2;  // row of this workgroup
+  const uint64_t i = (uint64_t)blk * rows_per_block + r;
   const uint32_t v = threadIdx.x & (lanes - 1);
-  const uint64_t count = (uint64_t)ns.S * ns.T;
+  const uint64_t count = (uint64_t)a.ns.S * a.ns.T;
   const bool in_range = i < count;
   bool clamped = false;
   if (in_range) {
-    const uint64_t slot = (st->tail + i) % tv.P;
-    for (uint32_t vv = v; vv < vecs_per_row; vv += lanes)
-      reinterpret_cast<Vec *>(obs_ring + slot * obs_bytes)[vv] = reinterpret_cast<const Vec *>(obs + i * obs_bytes)[vv];
-    if (act)
-      for (uint32_t by = v; by < act_bytes; by += lanes) act_ring[slot * act_bytes + by] = act[i * act_bytes + by];
+    const uint64_t slot = (a.st->tail + i) % a.tv.P;
+    for (uint32_t vv = v; vv < a.vecs_per_row; vv += lanes)
+      reinterpret_cast<Vec *>(a.obs_ring + slot * a.obs_bytes)[vv] =
+          reinterpret_cast<const Vec *>(a.obs + i * a.obs_bytes)[vv];
+    if (a.act)
+      for (uint32_t by = v; by < a.act_bytes; by += lanes)
+        a.act_ring[slot * a.act_bytes + by] = a.act[i * a.act_bytes + by];
     if (v == 0) {
-      const NstepOut o = nstep_one(ns, i);
-      ret_ring[slot] = o.R;
-      gacc_ring[slot] = o.G;
-      const uint64_t q = quantise_priority(o.p, qp, &clamped);
-      tv.level[0][slot] = q;  // the slot was empty (mass 0): the ring is never over-filled
-      if (both) tv2.level[0][slot] = q;
+      const NstepOut o = nstep_one(a.ns, i);
+      a.ret_ring[slot] = o.R;
+      a.gacc_ring[slot] = o.G;
+      const uint64_t q = quantise_priority(o.p, a.qp, &clamped);
+      a.tv.level[0][slot] = q;  // the slot was empty (mass 0): the ring is never over-filled
+      if (a.both) a.tv2.level[0][slot] = q;
       sh_slot[r] = slot;
       sh_q[r] = q;
     }
   }
   const uint64_t nc = __popcll(__ballot(clamped));
-  if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
+  if (nc && lane_id() == 0) atomic_add_u64(&a.st->n_clamped, nc);
   __syncthreads();
   if (threadIdx.x < ((rows_per_block + kWave - 1) & ~(uint32_t)(kWave - 1))) {  // whole waves
     const uint32_t e = threadIdx.x;
-    const bool active = e < rows_per_block && (uint64_t)blockIdx.x * rows_per_block + e < count;
-    add_to_ancestors_grouped(tv, active, active ? sh_slot[e] : 0, active ? sh_q[e] : 0, both ? &tv2 : nullptr);
+    const bool active = e < rows_per_block && (uint64_t)blk * rows_per_block + e < count;
+    add_to_ancestors_grouped(a.tv, active, active ? sh_slot[e] : 0, active ? sh_q[e] : 0, a.both ? &a.tv2 : nullptr);
   }
-  advance_state_when_all_done(&st->ticket_add, &st->tail, count);
+  advance_state_when_all_done(&a.st->ticket_add, &a.st->tail, count, n_wgs);
+}
+
+template <typename Vec>
+__global__ __launch_bounds__(kAddRoundThreads) void add_round_small_kernel(AddRoundArgs a)
+{
+  __shared__ uint64_t sh_slot[kAddRoundThreads], sh_q[kAddRoundThreads];
+  add_round_small_block<Vec>(a, blockIdx.x, gridDim.x, sh_slot, sh_q);
 }
 
 // evict: zero the masses of the e oldest keys and take them out of the upper levels
@@ -950,6 +972,10 @@ struct StepArgs {
   uint64_t *next_dq;      // ... the changes they bring, kept for the next launch
   QuantParams qp;
   DeviceState *st;
+  // A small add round that the workgroups beyond the first k of the launch carry out (see
+  // add_round_small_block; gridDim.x == k: none).  Only in a launch that draws nothing: what the round
+  // adds to the tree commutes with the write-back of this batch, not with a draw.
+  AddRoundArgs add;
 };
 
 typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
@@ -1046,11 +1072,19 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
 // Dynamic LDS: see draw_in_first_wave.
 // kTopChunk: passes of 512 top-level nodes whose loads the drawing wave issues together (1 for tops of at
 // most 512 nodes, 2 up to 1024, 4 beyond: more registers, fewer memory round trips).
-template <typename Vec, int kThreads, int kUnroll, int kTopChunk>
+// kWithRound: the workgroups beyond the first k carry a small add round (StepArgs::add).
+template <typename Vec, int kThreads, int kUnroll, int kTopChunk, bool kWithRound>
 __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
 {
   extern __shared__ uint64_t lds[];
   const uint32_t row = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
+  if constexpr (kWithRound) {
+    if (row >= a.k) {
+      __shared__ uint64_t sh_slot[kThreads], sh_q[kThreads];
+      add_round_small_block<Vec>(a.add, row - a.k, gridDim.x - a.k, sh_slot, sh_q);
+      return;
+    }
+  }
   const uint32_t wave = tid / kWave, lane = lane_id();
   const bool write_back = a.dq != nullptr, draw = a.next.rnd != nullptr;
   if (!a.slot) {  // the first draw of a sequence (one wave per workgroup): no batch to gather yet

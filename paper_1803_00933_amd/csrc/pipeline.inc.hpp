@@ -33,6 +33,7 @@ struct apex_pipeline {
   bool add_on_tree = false;   // ... with its payload copy on the learner's stream (small rounds)
   bool tail_unmarked = false; // the tail has moved since tail_ready was last recorded
   bool add_deferred = false;  // the open round is issued as one launch by add_end
+  HeldStep held;              // the last step launch of the latest steps call, if it waits for that launch
   NstepArgs add_ns{};
   const void *add_obs = nullptr, *add_act = nullptr;
   uint64_t add_count = 0;
@@ -161,6 +162,7 @@ int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buff
 int apex_pipeline_destroy(apex_pipeline_t *p)
 {
   if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
+  (void)issue_held_step(&p->held, p->tree);
   for (int i = 0; i < 2; ++i) (void)hipStreamSynchronize(p->streams(i));
   pipeline_free(p);
   return APEX_OK;
@@ -169,6 +171,7 @@ int apex_pipeline_destroy(apex_pipeline_t *p)
 int apex_pipeline_fork(apex_pipeline_t *p, void *after)
 {
   if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(issue_held_step(&p->held, p->tree));
   APEX_HIP(hipEventRecord(p->fork_ev, static_cast<hipStream_t>(after)));
   for (int i = 0; i < 2; ++i) APEX_HIP(hipStreamWaitEvent(p->streams(i), p->fork_ev, 0));
   return APEX_OK;
@@ -177,6 +180,7 @@ int apex_pipeline_fork(apex_pipeline_t *p, void *after)
 int apex_pipeline_join(apex_pipeline_t *p, void *stream)
 {
   if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(issue_held_step(&p->held, p->tree));
   for (int i = 0; i < 2; ++i) {
     APEX_HIP(hipEventRecord(p->join_ev, p->streams(i)));
     APEX_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), p->join_ev, 0));
@@ -188,11 +192,14 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
                         uint32_t *first_set_out)
 {
   if (!p || (n && !rnd) || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(issue_held_step(&p->held, p->tree));
   if (first_set_out) *first_set_out = (uint32_t)(p->step % p->depth);
   const uint64_t per = (uint64_t)p->nb * p->k;
   if (n && fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) {
+    // With a small add round open the last launch is held back: add_end issues it with the round inside.
     APEX_TRY(fused_steps(p->r, n, p->k, beta, rnd, new_prio, p->sets.data(), p->depth,
-                         (uint32_t)(p->step % p->depth), p->tree));
+                         (uint32_t)(p->step % p->depth), (p->add_open && p->add_deferred) ? &p->held : nullptr,
+                         p->tree));
     p->step += n;
     return APEX_OK;
   }
@@ -230,6 +237,7 @@ int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t
                             float *gacc)
 {
   if (!p || p->add_open) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(issue_held_step(&p->held, p->tree));
   apex_replay *r = p->r;
   const uint64_t count = (uint64_t)S * T;
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
@@ -266,10 +274,18 @@ int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out
 {
   if (!p || !p->add_open) return APEX_ERR_INVALID_ARG;
   if (!p->add_on_tree) APEX_TRY(mark_wait(p->payload_done, p->tree));
-  if (p->add_deferred)
-    APEX_TRY(add_round_small(p->r, p->add_ns, p->add_obs, p->add_act, first_key_out, p->tree));
-  else
+  if (p->add_deferred) {
+    // in the launch of the step that was held back for it, if there is one and the two fit together
+    int rc = issue_held_step_with_round(p->r, &p->held, p->add_ns, p->add_obs, p->add_act, first_key_out, p->tree);
+    if (rc == APEX_ERR_NOT_READY) {
+      APEX_TRY(issue_held_step(&p->held, p->tree));
+      rc = add_round_small(p->r, p->add_ns, p->add_obs, p->add_act, first_key_out, p->tree);
+    }
+    APEX_TRY(rc);
+  } else {
+    APEX_TRY(issue_held_step(&p->held, p->tree));
     APEX_TRY(apex_replay_add_publish(p->r, p->add_count, p->add_prio, first_key_out, p->tree));
+  }
   p->add_open = false;
   if (evicted_out) *evicted_out = 0;
   if (evict) APEX_TRY(apex_replay_evict(p->r, evicted_out, p->tree));
@@ -281,6 +297,7 @@ int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out
 int apex_pipeline_capture_begin(apex_pipeline_t *p)
 {
   if (!p || p->capturing || p->add_open) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(issue_held_step(&p->held, p->tree));
   for (int i = 0; i < 2; ++i) APEX_HIP(hipStreamSynchronize(p->streams(i)));  // drained: nothing older to wait for
   drop_graph(p);
   forget_marks(p);
@@ -297,6 +314,7 @@ int apex_pipeline_capture_begin(apex_pipeline_t *p)
 int apex_pipeline_capture_end(apex_pipeline_t *p)
 {
   if (!p || !p->capturing || p->add_open) return APEX_ERR_INVALID_ARG;
+  (void)issue_held_step(&p->held, p->tree);
   // join the add stream back into the origin of the capture
   apex_pipeline::Mark done;
   int rc = mark_record(p, done, p->add);
@@ -318,6 +336,7 @@ int apex_pipeline_capture_end(apex_pipeline_t *p)
 int apex_pipeline_replay(apex_pipeline_t *p, uint32_t times)
 {
   if (!p || p->capturing || !p->graph_exec) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(issue_held_step(&p->held, p->tree));
   for (uint32_t i = 0; i < times; ++i) APEX_HIP(hipGraphLaunch(p->graph_exec, p->tree));
   if (times) ++p->r->tree_version;
   return APEX_OK;

@@ -455,6 +455,73 @@ def test_pipeline_small_and_large_add_rounds():
     pipe.close()
 
 
+@pytest.mark.parametrize("ob", [256, 100, 7])
+def test_small_add_round_rides_in_the_last_step_launch(ob):
+    """With a small add round open (rows of at most 1 KB), the last step launch of a steps call is held back
+    and issued by add_end with the round inside it; any other call issues it on its own.  Every order of
+    calls against the oracle's plain order: steps, then the round, then the eviction."""
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=ob, capacity=9000, max_slots=12288, streams=6, chunk=25, k=96)
+    rng = np.random.default_rng(ob)
+    g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    add_both(g, o, rng, 8000)
+    depth = 5
+    pipe = apex.Pipeline(g, depth, 1, w.k)
+    n_rows = w.streams * w.chunk
+    scratch = [torch.empty(n_rows, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    # (steps calls between add_begin and add_end, write-back, join before add_end, misaligned source rows)
+    patterns = [([2], True, False, False), ([1, 1], True, False, False), ([1], True, True, False),
+                ([], True, False, False), ([3], True, False, True), ([2], False, False, False),
+                ([2], True, False, False)]
+    assert pipe.fork() == 0
+    for i, (calls, wb, join_between, misaligned) in enumerate(patterns):
+        d = synth.actor_round(w, i)
+        d["obs"] = rng.integers(0, 256, (n_rows, w.obs_bytes), dtype=np.uint8)
+        dd = {k2: dev(v) for k2, v in d.items()}
+        if misaligned:   # the same bytes at an address that is no multiple of 16 (nor of 4)
+            buf = torch.empty(n_rows * ob + 64, dtype=torch.uint8, device="cuda:0")
+            view = buf[3:3 + n_rows * ob].view(n_rows, ob)
+            view.copy_(dd["obs"])
+            dd["obs"] = view
+        total = sum(calls)
+        rnd = rng.integers(0, U64, (max(total, 1), w.k), dtype=np.uint64)
+        newp = rng.lognormal(0, 1, (max(total, 1), w.k)).astype(F32)
+        d_rnd, d_newp = dev(rnd), dev(newp)
+        assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                              dd["obs"], dd["act"], *scratch) == 0
+        firsts, at = [], 0
+        for c in calls:
+            rc, first = pipe.steps(c, 0.4, d_rnd[at:at + c], d_newp[at:at + c] if wb else None)
+            assert rc == 0
+            firsts += [(first + j) % depth for j in range(c)]
+            at += c
+        if join_between:
+            assert pipe.join() == 0
+            assert pipe.fork() == 0
+        rc, first_key, ev = pipe.add_end(True)
+        refs = []
+        for s_ in range(total):
+            refs.append(o.sample(1, w.k, 0.4, rnd[s_])[1])
+            if wb:
+                o.update_priorities(refs[-1]["key"], newp[s_])
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+        rco, fo = o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1), ref[2].reshape(-1))
+        assert (rc, first_key) == (rco, fo)
+        assert o.evict() == (0, ev)
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        for s_ in range(total):
+            assert_sample_equal(pipe.sets[firsts[s_]], refs[s_])
+        check_gpu_tree(g, o)
+        sample_both(g, o, rng, 2, 200)      # payload of the rounds added so far
+        assert pipe.fork() == 0
+    assert pipe.join() == 0
+    st = g.stats()
+    assert (st["size"], st["n_clamped"], st["n_stale_dropped"]) == (o.size, o.n_clamped, o.n_stale)
+    pipe.close()
+
+
 @pytest.mark.parametrize("nb,k,ob", PIPELINE_STEP_SHAPES)
 def test_pipeline_graph_replays(nb, k, ob):
     """One cycle (an add round beside six learner steps, then eviction) captured as a HIP graph by the
