@@ -347,10 +347,11 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
  * One round at a time.  Small rounds take shortcuts with the same result: below 4 MB of
  * observations the copies run on the tree stream (no events), and with rows of at most 1 KB the
  * whole round (priorities, payload, masses) is a single launch issued by add_end, which is why
- * every input of add_begin must stay untouched until add_end has run.  While such a round is
+ * every input of add_begin must stay untouched until add_end has run.  While a round is
  * open, apex_pipeline_steps holds the last launch of its call back until the next call on the
- * pipeline: add_end issues it with the round in further workgroups of the same launch (what the
- * round adds to the tree commutes with that step's write-back; the step draws nothing), every
+ * pipeline: add_end issues it with the round (a small one) or the round's masses (any other) in
+ * further workgroups of the same launch (what a round adds to the tree commutes with that
+ * step's write-back; the step draws nothing), every
  * other call (steps, join, fork, add_begin, capture_end, replay, destroy) issues it as it is.
  * A caller therefore orders its own stream after the pipeline with apex_pipeline_join, never
  * by waiting on the pipeline's streams themselves.

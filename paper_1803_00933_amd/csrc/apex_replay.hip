@@ -218,17 +218,20 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
 
 // One launch of the fused learner step (see learner_step_kernel) for vectors of sizeof(Vec) bytes.
 template <typename Vec>
-void launch_step_t(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds, hipStream_t stream)
+void launch_step_t(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds, int rider,
+                   hipStream_t stream)
 {
   const dim3 grid(wgs), block(threads);
-  if (wgs > a.k)  // with an add round in the further workgroups (such a launch draws nothing)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, true><<<grid, block, lds, stream>>>(a);
+  if (rider == kRoundRides)  // further workgroups carry part of an add round (such a launch draws nothing)
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kRoundRides><<<grid, block, lds, stream>>>(a);
+  else if (rider == kLeavesRide)
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kLeavesRide><<<grid, block, lds, stream>>>(a);
   else if (n_top <= 8 * kWave)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, false><<<grid, block, lds, stream>>>(a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kNoRider><<<grid, block, lds, stream>>>(a);
   else if (n_top <= 16 * kWave)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 2, false><<<grid, block, lds, stream>>>(a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 2, kNoRider><<<grid, block, lds, stream>>>(a);
   else
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 4, false><<<grid, block, lds, stream>>>(a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 4, kNoRider><<<grid, block, lds, stream>>>(a);
 }
 
 // A small add round (observations of at most 1 KB per row) as one launch: n-step priorities, payload,
@@ -478,8 +481,8 @@ int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio,
     const bool both = r->second_version == r->tree_version;
     ++r->tree_version;
     if (both) r->second_version = r->tree_version;
-    add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->tv, r->tv2, both, r->state(), count,
-                                                                              prio, r->qp);
+    add_leaves_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(
+        AddLeavesArgs{r->tv, r->tv2, both, r->state(), count, prio, r->qp});
     APEX_HIP(hipGetLastError());
   }
   if (first_key_out) *first_key_out = r->tail;
@@ -616,11 +619,11 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
 }
 
 void launch_step(const StepArgs &a, uint32_t vector_bytes, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds,
-                 hipStream_t stream)
+                 hipStream_t stream, int rider = kNoRider)
 {
-  if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, wgs, threads, lds, stream);
-  else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, wgs, threads, lds, stream);
-  else launch_step_t<uint8_t>(a, n_top, wgs, threads, lds, stream);
+  if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, wgs, threads, lds, rider, stream);
+  else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, wgs, threads, lds, rider, stream);
+  else launch_step_t<uint8_t>(a, n_top, wgs, threads, lds, rider, stream);
 }
 
 // A step launch that has been prepared but not issued: the last one of a call, held back while a small
@@ -654,7 +657,24 @@ int issue_held_step_with_round(apex_replay *r, HeldStep *h, const NstepArgs &ns,
   const int rc = add_round_args(r, ns, obs, act, h->vector_bytes, kStepThreads, both, &h->a.add, &blocks);
   if (rc != APEX_OK) return rc;
   h->valid = false;
-  launch_step(h->a, h->vector_bytes, h->n_top, h->a.k + blocks, kStepThreads, h->lds, stream);
+  launch_step(h->a, h->vector_bytes, h->n_top, h->a.k + blocks, kStepThreads, h->lds, stream, kRoundRides);
+  APEX_HIP(hipGetLastError());
+  add_round_published(r, count, both, first_key_out);
+  return APEX_OK;
+}
+
+// The held step and the masses of `count` new keys whose payload is in place (apex_replay_add_publish)
+// in one launch.  APEX_ERR_NOT_READY - with nothing enqueued - if there is no held step.
+int issue_held_step_with_leaves(apex_replay *r, HeldStep *h, uint64_t count, const float *prio,
+                                uint64_t *first_key_out, hipStream_t stream)
+{
+  if (!h->valid || !count || !prio) return APEX_ERR_NOT_READY;
+  if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
+  const bool both = r->second_version == r->tree_version;
+  h->a.leaves = AddLeavesArgs{r->tv, r->tv2, both, r->state(), count, prio, r->qp};
+  h->valid = false;
+  launch_step(h->a, h->vector_bytes, h->n_top, h->a.k + blocks_for(count, kStepThreads), kStepThreads, h->lds, stream,
+              kLeavesRide);
   APEX_HIP(hipGetLastError());
   add_round_published(r, count, both, first_key_out);
   return APEX_OK;

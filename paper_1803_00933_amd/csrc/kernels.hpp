@@ -564,25 +564,35 @@ __global__ __launch_bounds__(256) void add_payload_short_kernel(const uint8_t *_
 // add: masses of the new keys, and their sums into the upper levels
 // --------------------------------------------------------------------------------------------
 // both: the second copy of the tree (tv2) is in step with the first and is kept so.
-__global__ __launch_bounds__(256) void add_leaves_kernel(TreeView tv, TreeView tv2, bool both,
-                                                         DeviceState *__restrict__ st, uint64_t count,
-                                                         const float *__restrict__ prio, QuantParams qp)
+struct AddLeavesArgs {
+  TreeView tv, tv2;
+  bool both;
+  DeviceState *st;
+  uint64_t count;
+  const float *prio;  // [count]
+  QuantParams qp;
+};
+
+// Workgroup blk of n_wgs.
+__device__ __forceinline__ void add_leaves_block(const AddLeavesArgs &a, uint32_t blk, uint32_t n_wgs)
 {
-  const uint64_t i = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const bool active = i < count;
+  const uint64_t i = (uint64_t)blk * blockDim.x + threadIdx.x;
+  const bool active = i < a.count;
   uint64_t slot = 0, q = 0;
   bool clamped = false;
   if (active) {
-    slot = (st->tail + i) % tv.P;
-    q = quantise_priority(prio[i], qp, &clamped);
-    tv.level[0][slot] = q;  // the slot was empty (mass 0): the ring is never over-filled
-    if (both) tv2.level[0][slot] = q;
+    slot = (a.st->tail + i) % a.tv.P;
+    q = quantise_priority(a.prio[i], a.qp, &clamped);
+    a.tv.level[0][slot] = q;  // the slot was empty (mass 0): the ring is never over-filled
+    if (a.both) a.tv2.level[0][slot] = q;
   }
-  add_to_ancestors_grouped(tv, active, slot, q, both ? &tv2 : nullptr);
+  add_to_ancestors_grouped(a.tv, active, slot, q, a.both ? &a.tv2 : nullptr);
   const uint64_t nc = __popcll(__ballot(clamped));
-  if (nc && lane_id() == 0) atomic_add_u64(&st->n_clamped, nc);
-  advance_state_when_all_done(&st->ticket_add, &st->tail, count);
+  if (nc && lane_id() == 0) atomic_add_u64(&a.st->n_clamped, nc);
+  advance_state_when_all_done(&a.st->ticket_add, &a.st->tail, a.count, n_wgs);
 }
+
+__global__ __launch_bounds__(256) void add_leaves_kernel(AddLeavesArgs a) { add_leaves_block(a, blockIdx.x, gridDim.x); }
 
 // A small add round in one launch (Algorithm 1: ComputePriorities, replay.Add): 2^lanes_log2 lanes
 // per transition copy its payload row into the ring; the first of them computes the n-step
@@ -972,11 +982,15 @@ struct StepArgs {
   uint64_t *next_dq;      // ... the changes they bring, kept for the next launch
   QuantParams qp;
   DeviceState *st;
-  // A small add round that the workgroups beyond the first k of the launch carry out (see
-  // add_round_small_block; gridDim.x == k: none).  Only in a launch that draws nothing: what the round
-  // adds to the tree commutes with the write-back of this batch, not with a draw.
+  // What the workgroups beyond the first k of the launch carry out (gridDim.x == k: nothing): a small
+  // add round (add_round_small_block) or the masses of a round whose payload is in place
+  // (add_leaves_block).  Only in a launch that draws nothing: what a round adds to the tree commutes
+  // with the write-back of this batch, not with a draw.
   AddRoundArgs add;
+  AddLeavesArgs leaves;
 };
+
+enum StepRider { kNoRider = 0, kRoundRides = 1, kLeavesRide = 2 };
 
 typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
@@ -1072,16 +1086,22 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
 // Dynamic LDS: see draw_in_first_wave.
 // kTopChunk: passes of 512 top-level nodes whose loads the drawing wave issues together (1 for tops of at
 // most 512 nodes, 2 up to 1024, 4 beyond: more registers, fewer memory round trips).
-// kWithRound: the workgroups beyond the first k carry a small add round (StepArgs::add).
-template <typename Vec, int kThreads, int kUnroll, int kTopChunk, bool kWithRound>
+// kRider: what the workgroups beyond the first k carry (StepArgs::add or ::leaves).
+template <typename Vec, int kThreads, int kUnroll, int kTopChunk, int kRider>
 __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
 {
   extern __shared__ uint64_t lds[];
   const uint32_t row = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
-  if constexpr (kWithRound) {
+  if constexpr (kRider == kRoundRides) {
     if (row >= a.k) {
       __shared__ uint64_t sh_slot[kThreads], sh_q[kThreads];
       add_round_small_block<Vec>(a.add, row - a.k, gridDim.x - a.k, sh_slot, sh_q);
+      return;
+    }
+  }
+  if constexpr (kRider == kLeavesRide) {
+    if (row >= a.k) {
+      add_leaves_block(a.leaves, row - a.k, gridDim.x - a.k);
       return;
     }
   }

@@ -196,10 +196,10 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
   if (first_set_out) *first_set_out = (uint32_t)(p->step % p->depth);
   const uint64_t per = (uint64_t)p->nb * p->k;
   if (n && fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) {
-    // With a small add round open the last launch is held back: add_end issues it with the round inside.
+    // With an add round open the last launch is held back: add_end issues it with the round (a small one)
+    // or the round's masses (a large one, whose payload the other stream copies) inside.
     APEX_TRY(fused_steps(p->r, n, p->k, beta, rnd, new_prio, p->sets.data(), p->depth,
-                         (uint32_t)(p->step % p->depth), (p->add_open && p->add_deferred) ? &p->held : nullptr,
-                         p->tree));
+                         (uint32_t)(p->step % p->depth), p->add_open ? &p->held : nullptr, p->tree));
     p->step += n;
     return APEX_OK;
   }
@@ -283,8 +283,9 @@ int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out
     }
     APEX_TRY(rc);
   } else {
-    APEX_TRY(issue_held_step(&p->held, p->tree));
-    APEX_TRY(apex_replay_add_publish(p->r, p->add_count, p->add_prio, first_key_out, p->tree));
+    int rc = issue_held_step_with_leaves(p->r, &p->held, p->add_count, p->add_prio, first_key_out, p->tree);
+    if (rc == APEX_ERR_NOT_READY) rc = apex_replay_add_publish(p->r, p->add_count, p->add_prio, first_key_out, p->tree);
+    APEX_TRY(rc);
   }
   p->add_open = false;
   if (evicted_out) *evicted_out = 0;
