@@ -30,8 +30,8 @@ ADD_EVERY, EVICT_EVERY = 25, 100
 # HBM bytes per launch of the learner-step kernel, from two rocprofv3 --pmc runs of this script
 # (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads for a
 # plain 508,032,000-byte copy in the same run (FETCH_SIZE reads half the bytes, WRITE_SIZE all):
-#   (7819.2 * 1.99983 + 14428.8 * 1.0) KiB.   See profiles/learner_step_atari_hbm_traffic.txt.
-MEASURED_STEP_TRAFFIC_BYTES = int((7819.2 * 496125.0 / 248084.0 + 14428.8) * 1024)
+#   (7842.96 * 1.99991 + 14434.31 * 1.0) KiB.   See profiles/learner_step_atari_hbm_traffic.txt.
+MEASURED_STEP_TRAFFIC_BYTES = int((7842.96 * 496125.0 / 248074.2 + 14434.31) * 1024)
 STEP_ALGORITHMIC_BYTES = 512 * 57030   # per learner step of batch 512: gather read + write, sample outputs,
                                        # descent reads, update read-modify-writes (57,030 B per transition)
 
