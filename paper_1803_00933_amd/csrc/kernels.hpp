@@ -1075,7 +1075,7 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
   __builtin_amdgcn_s_setprio(0);
 }
 
-// No barrier anywhere: the waves of a workgroup run independently.
+// No barrier anywhere in the first k workgroups (one per row of the batch): their waves run independently.
 //   wave 0       draws sample `row` of the next batch and writes its change into the written copy;
 //                copies too only when the other waves cannot hold the whole row (its dependent
 //                loads would queue behind the row loads)

@@ -4,6 +4,8 @@
 // A step that draws several batches at once (the learner's prefetch, Section 4.1) is long enough
 // to pay for two more events: its gather then runs on the copy stream, beside the write-back of
 // its priorities and the next draw, which are all that the next step has to wait for.
+// While an add round is open the last launch of a steps call is held back (HeldStep): add_end issues
+// it with the round's tree work in further workgroups; every other entry point issues it first.
 // Included by apex_replay.hip (one translation unit), after the plain entry points.
 
 struct apex_pipeline {
