@@ -659,7 +659,7 @@ def main():
         "hbm_frac_of_step": {name: STEP_ALGORITHMIC_BYTES / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
                              for name, us in (("pipeline_learner_only", dt_pipe_learner / K * 1e6),
                                               ("pipeline_16_batches_per_call_learner_only", us16))},
-        "roofline": {"bound": "hbm", "kernel": "learner_step_kernel<u32x4,512,4> (gather of one batch of frame "
+        "roofline": {"bound": "hbm", "kernel": "learner_step_kernel<u32x4,512,4,1,0> (gather of one batch of frame "
                                                "stacks + IS weights + priority write-back + draw of the next "
                                                "batch; distinct rows every launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

@@ -522,6 +522,92 @@ def test_small_add_round_rides_in_the_last_step_launch(ob):
     pipe.close()
 
 
+@pytest.mark.parametrize("ob,seed", [(64, 1), (64, 2), (4224, 3), (1040, 4), (100, 5), (256, 6), (28224, 7), (7, 8)])
+def test_pipeline_random_call_orders(ob, seed):
+    """Random orders of the pipeline's calls (steps of random length with and without write-back, add rounds
+    opened and closed around them, evictions, joins, plain calls on the joined stream in between) against the
+    oracle applying the same operations in the order of the calls."""
+    from paper_1803_00933_amd import apex, synth
+    rng = np.random.default_rng(seed)
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=ob, capacity=6000, max_slots=8192, streams=5, chunk=20, k=int(rng.integers(40, 130)))
+    g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    add_both(g, o, rng, 5000)
+    depth = int(rng.integers(3, 7))
+    pipe = apex.Pipeline(g, depth, 1, w.k)
+    n_rows = w.streams * w.chunk
+    scratch = [torch.empty(n_rows, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    keep = []               # device inputs stay alive until the next join
+    pending = []            # (buffer set, oracle batch) to compare at the next join
+    open_round = None
+    assert pipe.fork() == 0
+    for it in range(120):
+        op = rng.choice(["steps", "steps", "steps", "begin", "end", "join", "plain"])
+        if op == "steps":
+            n = int(rng.integers(1, depth))          # fewer than the sets, so no set is overwritten before the join
+            if len(pending) + n > depth:
+                op = "join"
+            else:
+                wb = rng.random() < 0.8
+                rnd = rng.integers(0, U64, (n, w.k), dtype=np.uint64)
+                newp = rng.lognormal(0, 1.5, (n, w.k)).astype(F32)
+                d_rnd, d_newp = dev(rnd), dev(newp)
+                keep += [d_rnd, d_newp]
+                rc, first = pipe.steps(n, 0.4, d_rnd, d_newp if wb else None)
+                assert rc == 0
+                for i in range(n):
+                    rco, oo = o.sample(1, w.k, 0.4, rnd[i])
+                    assert rco == 0
+                    if wb:
+                        assert o.update_priorities(oo["key"], newp[i]) == 0
+                    pending.append(((first + i) % depth, oo))
+        if op == "begin" and open_round is None and o.size + n_rows <= w.max_slots:
+            d = synth.actor_round(w, it)
+            d["obs"] = rng.integers(0, 256, (n_rows, w.obs_bytes), dtype=np.uint8)
+            dd = {k2: dev(v) for k2, v in d.items()}
+            keep.append(dd)
+            assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                                  dd["obs"], dd["act"], *scratch) == 0
+            open_round = d
+        elif op == "end" and open_round is not None:
+            d, open_round = open_round, None
+            evict = bool(rng.random() < 0.5)
+            rc, first_key, ev = pipe.add_end(evict)
+            ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                          w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+            rco, fo = o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1), ref[2].reshape(-1))
+            assert (rc, first_key) == (rco, fo)
+            if evict:
+                assert o.evict() == (0, ev)
+        elif op in ("join", "plain") and open_round is None:
+            assert pipe.join() == 0
+            torch.cuda.synchronize()
+            for set_index, oo in pending:
+                assert_sample_equal(pipe.sets[set_index], oo)
+            pending, keep = [], []
+            check_gpu_tree(g, o)
+            if op == "plain":          # calls outside the pipeline change the first tree copy only
+                oo = sample_both(g, o, rng, 1, 48)
+                pr = rng.lognormal(0, 1, len(oo["key"])).astype(F32)
+                assert g.update_priorities(dev(oo["key"]), dev(pr)) == o.update_priorities(oo["key"], pr) == 0
+                if rng.random() < 0.3:
+                    assert g.evict() == o.evict()
+            assert pipe.fork() == 0
+    if open_round is not None:
+        rc, first_key, ev = pipe.add_end(False)
+        d = open_round
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+        assert (rc, first_key) == o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1), ref[2].reshape(-1))
+    assert pipe.join() == 0
+    torch.cuda.synchronize()
+    for set_index, oo in pending:
+        assert_sample_equal(pipe.sets[set_index], oo)
+    check_gpu_tree(g, o)
+    st = g.stats()
+    assert (st["size"], st["n_clamped"], st["n_stale_dropped"]) == (o.size, o.n_clamped, o.n_stale)
+    pipe.close()
+
+
 @pytest.mark.parametrize("nb,k,ob", PIPELINE_STEP_SHAPES)
 def test_pipeline_graph_replays(nb, k, ob):
     """One cycle (an add round beside six learner steps, then eviction) captured as a HIP graph by the
