@@ -67,6 +67,12 @@ def lib():
         L.oracle_replay_nodes.argtypes = [_vp]
         L.oracle_replay_leaves.restype = None
         L.oracle_replay_leaves.argtypes = [_vp, _u64, _u64, _vp]
+        L.oracle_codec_row_bytes.restype = _u64
+        L.oracle_codec_row_bytes.argtypes = [_u32]
+        L.oracle_codec_encode_row.restype = C.c_int
+        L.oracle_codec_encode_row.argtypes = [_vp, _u32, _vp, C.POINTER(_u64)]
+        L.oracle_codec_decode_row.restype = C.c_int
+        L.oracle_codec_decode_row.argtypes = [_vp, _u32, _vp]
         _lib = L
     return _lib
 
@@ -111,6 +117,37 @@ def nstep_priorities(q_online, q_target, action, reward, discount, n, alpha, eps
     lib().oracle_nstep_priorities(S, T, n, A, _p(q_online), _p(q_target), _p(action), _p(reward), _p(discount),
                                   alpha, eps, frac_bits, max_slots, _p(prio), _p(ret), _p(gacc), _p(fx))
     return prio, ret, gacc, fx
+
+
+def codec_row_bytes(raw_bytes):
+    """Stride of an encoded observation row (0: raw_bytes is no positive multiple of 64)."""
+    return int(lib().oracle_codec_row_bytes(int(raw_bytes)))
+
+
+def codec_encode(rows):
+    """rows: uint8 [n, raw_bytes] -> (encoded uint8 [n, codec_row_bytes], bytes that carry data [n])."""
+    rows = _arr(rows, np.uint8)
+    n, raw_bytes = rows.shape
+    cap = codec_row_bytes(raw_bytes)
+    if not cap:
+        raise ValueError("raw_bytes must be a positive multiple of 64")
+    enc = np.empty((n, cap), np.uint8)
+    used = np.empty(n, np.uint64)
+    u = _u64(0)
+    for i in range(n):
+        rc = lib().oracle_codec_encode_row(_p(rows[i]), raw_bytes, _p(enc[i]), C.byref(u))
+        assert rc == OK
+        used[i] = u.value
+    return enc, used
+
+
+def codec_decode(enc, raw_bytes):
+    """enc: uint8 [n, >= codec_row_bytes(raw_bytes)] -> uint8 [n, raw_bytes]."""
+    enc = _arr(enc, np.uint8)
+    out = np.empty((enc.shape[0], raw_bytes), np.uint8)
+    for i in range(enc.shape[0]):
+        assert lib().oracle_codec_decode_row(_p(enc[i]), raw_bytes, _p(out[i])) == OK
+    return out
 
 
 class Replay:

@@ -17,8 +17,9 @@
  *
  * Parity pins: every function here is pinned by tests that do not call it back
  * (closed-form n-step returns, brute-force inverse CDF, exact expected sampling
- * frequencies, double-precision pow, hand-worked fixtures).  Nothing is
- * "parity unpinned".
+ * frequencies, double-precision pow, hand-worked fixtures; the observation codec by a
+ * hand-worked row, closed-form sizes, a second derivation of its mask and counts and the
+ * lossless round trip).  Nothing is "parity unpinned".
  *
  * Build: gcc -O2 -std=c11 -ffp-contract=off -mfma -shared -fPIC apex_oracle.c -lm
  * (-ffp-contract=off: every floating-point rounding below is written out by hand;
@@ -672,3 +673,84 @@ void oracle_pe_nodes(const oracle_pe *r, int which, uint64_t *out)
 uint64_t oracle_pe_tree_leaves(const oracle_pe *r) { return r->P2; }
 void oracle_pe_gen(const oracle_pe *r, uint32_t *out) { memcpy(out, r->gen, r->max_slots * 4); }
 void oracle_pe_free_ring(const oracle_pe *r, uint32_t *out) { memcpy(out, r->free_ring, r->max_slots * 4); }
+
+/* ------------------------------------------------------------------------- */
+/* Lossless codec of stored observations                                       */
+/* ------------------------------------------------------------------------- */
+/*
+ * Section 4.1 (and Appendix "Atari: Additional Details"): observations are kept
+ * compressed in the replay memory and decompressed by the learner as it prefetches
+ * batches; the paper uses PNG and says no more.  The property that matters to the
+ * method is that the codec is lossless.  The reading taken here is a codec that a
+ * GPU can undo at memory speed: a row of raw_bytes = 64 * nb bytes is cut into nb
+ * blocks of 64 bytes; a block whose 64 bytes are all equal ("flat": the background
+ * of a game screen) is stored as that one byte, any other block as it is.
+ *
+ * Encoded row (all offsets and sizes in bytes, integers little-endian):
+ *   0               u32 n_raw = number of blocks that are not flat; 12 zero bytes
+ *   16              mask: bit (b mod 64) of u64 word (b div 64) is 1 iff block b is
+ *                   not flat; ceil(nb/64) words, zero-padded to a multiple of 16
+ *   16 + M          the common byte of every flat block, in block order; a region of
+ *                   nb bytes rounded up to a multiple of 16 (the rest is zero)
+ *   16 + M + V      the 64 bytes of every block that is not flat, in block order
+ * A row takes at most 16 + M + V + 64 * nb bytes; that is the stride of the store.
+ */
+static uint64_t pad16(uint64_t v) { return (v + 15) / 16 * 16; }
+
+uint64_t oracle_codec_row_bytes(uint32_t raw_bytes)
+{
+  if (raw_bytes == 0 || raw_bytes % 64) return 0;
+  const uint64_t nb = raw_bytes / 64;
+  return 16 + pad16(8 * ((nb + 63) / 64)) + pad16(nb) + 64 * nb;
+}
+
+/* enc: oracle_codec_row_bytes(raw_bytes) bytes, all written.  *used: the bytes of it that carry data. */
+int oracle_codec_encode_row(const uint8_t *raw, uint32_t raw_bytes, uint8_t *enc, uint64_t *used)
+{
+  const uint64_t cap = oracle_codec_row_bytes(raw_bytes);
+  if (!cap) return ORACLE_ERR_INVALID_ARG;
+  const uint64_t nb = raw_bytes / 64;
+  const uint64_t M = pad16(8 * ((nb + 63) / 64)), V = pad16(nb);
+  memset(enc, 0, cap);
+  uint8_t *mask = enc + 16, *flat = enc + 16 + M, *blocks = enc + 16 + M + V;
+  uint32_t n_raw = 0, n_flat = 0;
+  for (uint64_t b = 0; b < nb; ++b) {
+    const uint8_t *blk = raw + 64 * b;
+    int is_flat = 1;
+    for (int j = 1; j < 64; ++j)
+      if (blk[j] != blk[0]) is_flat = 0;
+    if (is_flat) {
+      flat[n_flat++] = blk[0];
+    } else {
+      mask[b / 8] |= (uint8_t)(1u << (b % 8)); /* little-endian words: bit b of the bit string */
+      memcpy(blocks + 64 * (uint64_t)n_raw, blk, 64);
+      ++n_raw;
+    }
+  }
+  enc[0] = (uint8_t)n_raw;
+  enc[1] = (uint8_t)(n_raw >> 8);
+  enc[2] = (uint8_t)(n_raw >> 16);
+  enc[3] = (uint8_t)(n_raw >> 24);
+  if (used) *used = 16 + M + n_flat + 64 * (uint64_t)n_raw;
+  return ORACLE_OK;
+}
+
+int oracle_codec_decode_row(const uint8_t *enc, uint32_t raw_bytes, uint8_t *raw_out)
+{
+  const uint64_t cap = oracle_codec_row_bytes(raw_bytes);
+  if (!cap) return ORACLE_ERR_INVALID_ARG;
+  const uint64_t nb = raw_bytes / 64;
+  const uint64_t M = pad16(8 * ((nb + 63) / 64)), V = pad16(nb);
+  const uint8_t *mask = enc + 16, *flat = enc + 16 + M, *blocks = enc + 16 + M + V;
+  uint64_t n_raw = 0, n_flat = 0;
+  for (uint64_t b = 0; b < nb; ++b) {
+    if (mask[b / 8] >> (b % 8) & 1) {
+      memcpy(raw_out + 64 * b, blocks + 64 * n_raw, 64);
+      ++n_raw;
+    } else {
+      memset(raw_out + 64 * b, flat[n_flat], 64);
+      ++n_flat;
+    }
+  }
+  return ORACLE_OK;
+}
