@@ -286,6 +286,39 @@ int apex_replay_resync(apex_replay_t *r, void *hip_stream);
 int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out /*host*/, void *hip_stream);
 
 /* ------------------------------------------------------------------------------------------
+ * Observations stored compressed (Section 4.1 and Appendix "Atari: Additional Details": the
+ * replay memory keeps observations compressed, the learner decompresses them as it fetches
+ * batches; the paper uses PNG).  Here: a lossless codec that is undone at memory speed.  A row
+ * of raw_bytes = 64 * nb bytes is cut into nb blocks of 64 bytes; a block whose bytes are all
+ * equal (flat background) is kept as that byte, any other block as it is.  Encoded row,
+ * integers little-endian:
+ *   0            u32 n_raw = blocks kept as they are, then 12 zero bytes
+ *   16           mask, bit b set iff block b is kept as it is: ceil(nb/64) u64 words, zero-padded
+ *                to a multiple of 16 bytes (M bytes in all)
+ *   16 + M       the byte of every other block, in block order (a region of nb bytes rounded up
+ *                to a multiple of 16, V bytes; what lies beyond the last such byte is unspecified)
+ *   16 + M + V   the blocks kept as they are, in block order (beyond the last: unspecified)
+ * apex_codec_row_bytes = 16 + M + V + 64 * nb is what a row can take; a memory that stores
+ * encoded rows is created with obs_bytes >= that (a multiple of 16).  0 if raw_bytes is 0, no
+ * multiple of 64, or beyond 256 KB.  The ring's row stride stays fixed, so the codec saves HBM
+ * traffic (an add writes, a gather reads only the bytes that carry data), not capacity.
+ *
+ * apex_replay_add_payload_encoded is apex_replay_add_payload with raw_obs [count, raw_bytes]
+ * (device, 16-byte aligned) encoded on its way into the ring; publish with
+ * apex_replay_add_publish.  apex_replay_gather_decoded is apex_replay_gather with obs_out
+ * [count, raw_bytes] (16-byte aligned, may be NULL) decoded on its way out.  Both:
+ * APEX_ERR_INVALID_ARG for a raw_bytes the codec refuses or misaligned rows, APEX_ERR_TOO_LARGE
+ * if the memory's rows are too short for raw_bytes.  The fused learner step of the pipeline
+ * copies rows as they are stored; a caller of the codec draws with apex_replay_sample_begin and
+ * apex_replay_sample_finish (obs_out NULL) and fetches with apex_replay_gather_decoded.
+ * ---------------------------------------------------------------------------------------- */
+size_t apex_codec_row_bytes(uint32_t raw_bytes);
+int apex_replay_add_payload_encoded(apex_replay_t *r, uint64_t count, const void *raw_obs, uint32_t raw_bytes,
+                                    const void *act, const float *ret, const float *gacc, void *hip_stream);
+int apex_replay_gather_decoded(apex_replay_t *r, uint64_t count, const uint32_t *slot, uint32_t raw_bytes,
+                               void *obs_out, void *act_out, float *ret_out, float *gacc_out, void *hip_stream);
+
+/* ------------------------------------------------------------------------------------------
  * Prefetch pipeline.  Section 4.1 and Appendix "Implementation" describe a learner that fetches
  * batches asynchronously, ahead of use, while priorities flow back and actors keep adding.  An
  * apex_pipeline_t issues the same verbs as above on two streams of its own (default priority),

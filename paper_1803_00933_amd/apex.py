@@ -28,7 +28,8 @@ EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_des
            "apex_pipeline_join", "apex_pipeline_steps", "apex_pipeline_add_begin", "apex_pipeline_add_end",
            "apex_pipeline_capture_begin", "apex_pipeline_capture_end", "apex_pipeline_replay",
            "apex_pe_workspace_bytes", "apex_pe_create", "apex_pe_destroy", "apex_pe_layout", "apex_pe_add",
-           "apex_pe_sample", "apex_pe_update_priorities", "apex_pe_evict", "apex_pe_stats"]
+           "apex_pe_sample", "apex_pe_update_priorities", "apex_pe_evict", "apex_pe_stats",
+           "apex_codec_row_bytes", "apex_replay_add_payload_encoded", "apex_replay_gather_decoded"]
 
 
 class Config(C.Structure):
@@ -94,6 +95,10 @@ lib.apex_replay_sample_finish_writeback.argtypes = [_vp, _u32, _u32, _f32, _vp, 
 lib.apex_replay_resync.argtypes = [_vp, _vp]
 lib.apex_replay_gather.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
+lib.apex_codec_row_bytes.restype = C.c_size_t
+lib.apex_codec_row_bytes.argtypes = [_u32]
+lib.apex_replay_add_payload_encoded.argtypes = [_vp, _u64, _vp, _u32, _vp, _vp, _vp, _vp]
+lib.apex_replay_gather_decoded.argtypes = [_vp, _u64, _vp, _u32, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_update_from_q.argtypes = [_vp, _u64, _vp, _u32, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_evict.argtypes = [_vp, C.POINTER(_u64), _vp]
 lib.apex_replay_stats.argtypes = [_vp, C.POINTER(Stats), _vp]
@@ -277,6 +282,16 @@ class Replay:
 
     def update_priorities(self, key, prio, stream=None):
         return lib.apex_replay_update_priorities(self.h, key.shape[0], _ptr(key), _ptr(prio), _stream(stream))
+
+    def add_payload_encoded(self, raw_obs, act=None, ret=None, gacc=None, stream=None):
+        """raw_obs: uint8 [count, raw_bytes], stored through the observation codec."""
+        return lib.apex_replay_add_payload_encoded(self.h, raw_obs.shape[0], _ptr(raw_obs), raw_obs.shape[1], _ptr(act),
+                                                   _ptr(ret), _ptr(gacc), _stream(stream))
+
+    def gather_decoded(self, slot, obs, act=None, ret=None, gacc=None, stream=None):
+        """obs: uint8 [count, raw_bytes] receives the decoded observations of the slots."""
+        return lib.apex_replay_gather_decoded(self.h, slot.shape[0], _ptr(slot), obs.shape[1], _ptr(obs), _ptr(act),
+                                              _ptr(ret), _ptr(gacc), _stream(stream))
 
     def update_from_q(self, key, q_taken, q_online_next, q_target_next, prio_out=None, stream=None):
         return lib.apex_replay_update_from_q(self.h, key.shape[0], _ptr(key), q_online_next.shape[1], _ptr(q_taken),

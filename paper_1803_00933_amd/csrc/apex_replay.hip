@@ -916,3 +916,4 @@ int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out, void *hip_stre
 
 #include "pipeline.inc.hpp"
 #include "evict_prio.inc.hpp"
+#include "codec.inc.hpp"

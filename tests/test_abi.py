@@ -11,7 +11,7 @@ HEADER = os.path.join(ROOT, "include", "apex_replay.h")
 def declared_functions():
     text = open(HEADER).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\bint\s+(apex_\w+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(?:int|size_t)\s+(apex_\w+)\s*\(", text)))
 
 
 def test_header_declares_the_replay_verbs():
