@@ -512,8 +512,85 @@ def next_row_numbers(log):
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps * 1e6
     out["prioritized_evict_memory_control_schedule_us_per_step"] = dt
-    log("next rows: %s" % {k: round(v, 2) for k, v in out.items()})
+    g.close()
+    out["observation_codec"] = codec_numbers(log)
+    log("next rows: %s" % {k: (round(v, 2) if not isinstance(v, dict) else v) for k, v in out.items()})
     return out
+
+
+def frame_like_rows(n, raw_bytes, flat_share, seed):
+    """Stand-in for game screens (no frames of the suite are in the container): every 64-byte block of a row is
+    one of 8 background bytes with probability flat_share, uniform random bytes otherwise."""
+    import torch
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(seed)
+    nb = raw_bytes // 64
+    rows = torch.randint(0, 256, (n, nb, 64), dtype=torch.uint8, device="cuda:0", generator=gen)
+    flat = torch.rand((n, nb, 1), device="cuda:0", generator=gen) < flat_share
+    pal = (torch.randint(0, 8, (n, nb, 1), device="cuda:0", generator=gen) * 31).to(torch.uint8)
+    return torch.where(flat, pal, rows).view(n, raw_bytes)
+
+
+def codec_numbers(log):
+    """The observation codec (Section 4.1: observations are stored compressed) on frame-stack rows: the payload
+    of an add round encoded on its way into the ring, batches decoded on their way out, against the plain
+    copies of the same rows.  Device time from HIP events; a ring of 2^18 rows (7.5 GB) drawn from at random."""
+    import torch
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["atari"]
+    raw, P = w.obs_bytes, 1 << 18
+    stride = int(apex.lib.apex_codec_row_bytes(raw))
+    res = {"raw_bytes": raw, "row_stride": stride}
+    rng = np.random.default_rng(11)
+    slot512 = [dev(rng.integers(0, P - w.add_count, 512).astype(np.int32)) for _ in range(16)]
+    slot8k = [dev(rng.integers(0, P - w.add_count, 8192).astype(np.int32)) for _ in range(4)]
+    out512 = [torch.empty((512, raw), dtype=torch.uint8, device="cuda:0") for _ in range(4)]
+    out8k = torch.empty((8192, raw), dtype=torch.uint8, device="cuda:0")
+    prio = torch.ones(w.add_count, device="cuda:0")
+
+    def timed(fn, n):
+        fn(0)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n * 1e3
+
+    for share in (0.8, 0.0):
+        rows = frame_like_rows(w.add_count, raw, share, seed=3)
+        rep = apex.Replay(P - w.add_count, P, stride, w.act_bytes, w.alpha, w.eps, w.frac_bits)
+        for _ in range((P - w.add_count) // w.add_count):           # fill through the encoder
+            assert rep.add_payload_encoded(rows) == 0
+            assert rep.add_publish(prio)[0] == 0
+        torch.cuda.synchronize()
+        n_raw = rep.obs_view()[:w.add_count, :4].contiguous().view(torch.int32).to(torch.float64).mean().item()
+        nb = raw // 64
+        used = 16 + (stride - 16 - 64 * nb - (nb + 15) // 16 * 16) + (nb - n_raw) + 64 * n_raw
+        tag = "flat_%d%%" % int(share * 100)
+        res[tag] = {
+            "bytes_per_row_that_carry_data": used, "ratio": raw / used,
+            "add_payload_encoded_18000_us": timed(lambda i: rep.add_payload_encoded(rows), 8),
+            "gather_decoded_512_us": timed(lambda i: rep.gather_decoded(slot512[i % 16], out512[i % 4]), 64),
+            "gather_decoded_8192_us": timed(lambda i: rep.gather_decoded(slot8k[i % 4], out8k), 8),
+        }
+        if share == 0.0:       # the plain copies of rows of the same stride, for comparison
+            enc_rows = rep.obs_view()[:w.add_count].clone()
+            out512s = [torch.empty((512, stride), dtype=torch.uint8, device="cuda:0") for _ in range(4)]
+            out8ks = torch.empty((8192, stride), dtype=torch.uint8, device="cuda:0")
+            res["plain_copies"] = {
+                "add_payload_18000_us": timed(lambda i: rep.add_payload(w.add_count, obs=enc_rows), 8),
+                "gather_512_us": timed(lambda i: rep.gather(slot512[i % 16], obs=out512s[i % 4]), 64),
+                "gather_8192_us": timed(lambda i: rep.gather(slot8k[i % 4], obs=out8ks), 8),
+            }
+            del enc_rows, out512s, out8ks
+        rep.close()
+        del rep, rows
+        torch.cuda.empty_cache()
+    log("observation codec: %s" % res)
+    return res
 
 
 def cpu_baseline(w, budget_steps, log):

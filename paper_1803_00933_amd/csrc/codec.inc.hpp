@@ -146,6 +146,55 @@ __global__ __launch_bounds__(kCodecThreads) void codec_decode_rows_kernel(const 
   }
 }
 
+// The same for rows of at most 512 blocks (32 KB raw), without LDS and without a barrier: the mask is at most
+// eight words, which every wave holds in scalar registers; the 64 lanes of a wave work on 16 consecutive
+// blocks, all within one word of the mask, so where a block's bytes come from is a few popcounts.
+__global__ __launch_bounds__(kCodecThreads) void codec_decode_rows_direct_kernel(const uint8_t *__restrict__ ring,
+                                                                                const uint32_t *__restrict__ slot,
+                                                                                uint64_t ring_stride,
+                                                                                uint8_t *__restrict__ out, CodecShape c)
+{
+  const uint64_t i = blockIdx.x;
+  const uint8_t *e = ring + (uint64_t)slot[i] * ring_stride;
+  const uint64_t *mw = reinterpret_cast<const uint64_t *>(e + 16);
+  uint64_t m[8];
+  uint32_t before[8];  // blocks kept as they are in the words before this one
+  uint32_t run = 0;
+#pragma unroll
+  for (int w = 0; w < 8; ++w) {
+    m[w] = (uint32_t)w < c.mask_words ? mw[w] : 0;
+    before[w] = run;
+    run += __popcll(m[w]);
+  }
+  const uint32_t tid = threadIdx.x, nvec = c.raw_bytes / 16;
+  u32x4 *o = reinterpret_cast<u32x4 *>(out + i * c.raw_bytes);
+  u32x4 t[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint32_t v = u * kCodecThreads + tid;  // block v / 4; the wave's blocks share word (tid >> 8) + 2 u
+    uint64_t word = 0;
+    uint32_t base = 0;
+#pragma unroll
+    for (int w = 0; w < 8; ++w)
+      if ((uint32_t)w == (tid >> 8) + 2 * u) word = m[w], base = before[w];
+    if (v < nvec) {
+      const uint32_t b = v / 4, bit = b & 63;
+      const uint32_t rank = base + __popcll(word & ((1ull << bit) - 1));
+      if (word >> bit & 1) {
+        t[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(e + c.raw_off + 64 * rank) + (v & 3));
+      } else {
+        const uint32_t x = e[c.flat_off + (b - rank)] * 0x01010101u;
+        t[u] = u32x4{x, x, x, x};
+      }
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint32_t v = u * kCodecThreads + tid;
+    if (v < nvec) __builtin_nontemporal_store(t[u], o + v);
+  }
+}
+
 }  // namespace apex
 
 extern "C" {
@@ -188,8 +237,13 @@ int apex_replay_gather_decoded(apex_replay_t *r, uint64_t count, const uint32_t 
   if (count == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   if (obs_out) {
-    codec_decode_rows_kernel<<<dim3((uint32_t)count), dim3(kCodecThreads), 0, stream>>>(
-        r->obs(), slot, r->cfg.obs_bytes, static_cast<uint8_t *>(obs_out), codec_shape(raw_bytes));
+    const CodecShape c = codec_shape(raw_bytes);
+    if (c.nb <= kCodecThreads)
+      codec_decode_rows_direct_kernel<<<dim3((uint32_t)count), dim3(kCodecThreads), 0, stream>>>(
+          r->obs(), slot, r->cfg.obs_bytes, static_cast<uint8_t *>(obs_out), c);
+    else
+      codec_decode_rows_kernel<<<dim3((uint32_t)count), dim3(kCodecThreads), 0, stream>>>(
+          r->obs(), slot, r->cfg.obs_bytes, static_cast<uint8_t *>(obs_out), c);
     APEX_HIP(hipGetLastError());
   }
   return apex_replay_gather(r, count, slot, nullptr, act_out, ret_out, gacc_out, hip_stream);
