@@ -101,6 +101,59 @@ __global__ __launch_bounds__(kCodecThreads) void codec_encode_rows_kernel(const 
   }
 }
 
+// The same for rows of at most 512 blocks (32 KB raw) with every load and store 16 bytes per lane in row
+// order: four neighbouring lanes hold a block, agree on whether it is flat with two exchanges, and the first
+// of them enters the block's bit into the mask in LDS; after one barrier every lane knows where its 16 bytes go.
+__global__ __launch_bounds__(kCodecThreads) void codec_encode_rows_direct_kernel(const uint8_t *__restrict__ src,
+                                                                                uint8_t *__restrict__ ring, RowMap to,
+                                                                                uint64_t ring_stride, CodecShape c)
+{
+  __shared__ uint64_t mask[8];  // 512 blocks
+  uint32_t *mask32 = reinterpret_cast<uint32_t *>(mask);
+  const uint64_t i = blockIdx.x;
+  const u32x4 *s = reinterpret_cast<const u32x4 *>(src + i * c.raw_bytes);
+  uint8_t *d = ring + map_row(to, i) * ring_stride;
+  const uint32_t tid = threadIdx.x, nvec = c.raw_bytes / 16;
+  if (tid < 16) mask32[tid] = 0;
+  u32x4 t[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint32_t v = u * kCodecThreads + tid;
+    t[u] = v < nvec ? __builtin_nontemporal_load(s + v) : u32x4{0, 0, 0, 0};
+  }
+  __syncthreads();  // the mask is cleared
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint32_t v = u * kCodecThreads + tid, b = v / 4;
+    const uint32_t x = t[u].x;
+    bool flat = x == (x & 0xffu) * 0x01010101u && t[u].y == x && t[u].z == x && t[u].w == x;
+    // the four lanes of a block: all flat, with the same byte
+    flat = flat && __shfl_xor(x, 1, kWave) == x;
+    flat = __shfl_xor((int)flat, 1, kWave) && flat;
+    flat = flat && __shfl_xor(x, 2, kWave) == x;
+    flat = __shfl_xor((int)flat, 2, kWave) && flat;
+    if (v < nvec && (v & 3) == 0 && !flat) atomicOr(&mask32[b / 32], 1u << (b % 32));
+  }
+  __syncthreads();
+  if (tid == 0) {
+    uint32_t n_raw = 0;
+    for (uint32_t w = 0; w < 16; ++w) n_raw += __popc(mask32[w]);
+    *reinterpret_cast<u32x4 *>(d) = u32x4{n_raw, 0, 0, 0};
+  }
+  if (tid < (c.flat_off - 16) / 8) reinterpret_cast<uint64_t *>(d + 16)[tid] = tid < c.mask_words ? mask[tid] : 0;
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    const uint32_t v = u * kCodecThreads + tid, b = v / 4;
+    if (v >= nvec) break;
+    const bool kept = mask[b / 64] >> (b % 64) & 1;
+    const uint32_t rank = codec_rank(mask, b);
+    if (kept)
+      __builtin_nontemporal_store(t[u], reinterpret_cast<u32x4 *>(d + c.raw_off + 64ull * rank) + (v & 3));
+    else if ((v & 3) == 0)
+      d[c.flat_off + (b - rank)] = (uint8_t)t[u].x;
+  }
+}
+
 // One workgroup per output row: the mask into LDS, one LDS word per block saying where its bytes come
 // from, then the row is written 16 bytes per lane, in order, as a plain gather writes it.
 __global__ __launch_bounds__(kCodecThreads) void codec_decode_rows_kernel(const uint8_t *__restrict__ ring,
@@ -217,8 +270,13 @@ int apex_replay_add_payload_encoded(apex_replay_t *r, uint64_t count, const void
   if (count > 0x7ffffff0ull) return APEX_ERR_TOO_LARGE;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const RowMap ring{nullptr, &r->state()->tail, r->cfg.max_slots};
-  codec_encode_rows_kernel<<<dim3((uint32_t)count), dim3(kCodecThreads), 0, stream>>>(
-      static_cast<const uint8_t *>(raw_obs), r->obs(), ring, r->cfg.obs_bytes, codec_shape(raw_bytes));
+  const CodecShape c = codec_shape(raw_bytes);
+  if (c.nb <= kCodecThreads)
+    codec_encode_rows_direct_kernel<<<dim3((uint32_t)count), dim3(kCodecThreads), 0, stream>>>(
+        static_cast<const uint8_t *>(raw_obs), r->obs(), ring, r->cfg.obs_bytes, c);
+  else
+    codec_encode_rows_kernel<<<dim3((uint32_t)count), dim3(kCodecThreads), 0, stream>>>(
+        static_cast<const uint8_t *>(raw_obs), r->obs(), ring, r->cfg.obs_bytes, c);
   APEX_HIP(hipGetLastError());
   if (act || ret || gacc) {
     const PayloadRing pr{r->obs(), r->act(), r->ret(), r->gacc(), r->cfg.obs_bytes, r->cfg.act_bytes};
