@@ -29,7 +29,8 @@ EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_des
            "apex_pipeline_capture_begin", "apex_pipeline_capture_end", "apex_pipeline_replay",
            "apex_pe_workspace_bytes", "apex_pe_create", "apex_pe_destroy", "apex_pe_layout", "apex_pe_add",
            "apex_pe_sample", "apex_pe_update_priorities", "apex_pe_evict", "apex_pe_stats",
-           "apex_codec_row_bytes", "apex_replay_add_payload_encoded", "apex_replay_gather_decoded"]
+           "apex_codec_row_bytes", "apex_replay_add_payload_encoded", "apex_replay_gather_decoded",
+           "apex_pipeline_set_codec"]
 
 
 class Config(C.Structure):
@@ -108,6 +109,7 @@ lib.apex_pipeline_destroy.argtypes = [_vp]
 lib.apex_pipeline_fork.argtypes = [_vp, _vp]
 lib.apex_pipeline_join.argtypes = [_vp, _vp]
 lib.apex_pipeline_steps.argtypes = [_vp, _u32, _f32, _vp, _vp, C.POINTER(_u32)]
+lib.apex_pipeline_set_codec.argtypes = [_vp, _u32]
 lib.apex_pipeline_add_begin.argtypes = [_vp, _u32, _u32, _u32, _u32] + [_vp] * 10
 lib.apex_pipeline_add_end.argtypes = [_vp, C.c_int, C.POINTER(_u64), C.POINTER(_u64)]
 lib.apex_pipeline_capture_begin.argtypes = [_vp]
@@ -342,6 +344,16 @@ class Pipeline:
 
     def join(self, stream=None):
         return lib.apex_pipeline_join(self.h, _stream(stream))
+
+    def set_codec(self, raw_bytes):
+        """Observations through the block codec: the sets' 'obs' become [nb*k, raw_bytes] views of their buffers."""
+        rc = lib.apex_pipeline_set_codec(self.h, raw_bytes)
+        if rc == OK:
+            for o in self.sets:
+                base = o.setdefault("obs_buffer", o["obs"])
+                n = self.nb * self.k
+                o["obs"] = base.view(-1)[:n * raw_bytes].view(n, raw_bytes) if raw_bytes else base
+        return rc
 
     def steps(self, n, beta, rnd, new_prio=None):
         first = _u32(0)

@@ -217,6 +217,21 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
 
 
 // One launch of the fused learner step (see learner_step_kernel) for vectors of sizeof(Vec) bytes.
+// Steps whose rows are decoded on their way out (16-byte vectors; riders: none, or the masses of an add round).
+void launch_step_codec(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds, int rider,
+                       hipStream_t stream)
+{
+  const dim3 grid(wgs), block(threads);
+  if (rider == kLeavesRide)
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1, kLeavesRide, true><<<grid, block, lds, stream>>>(a);
+  else if (n_top <= 8 * kWave)
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1, kNoRider, true><<<grid, block, lds, stream>>>(a);
+  else if (n_top <= 16 * kWave)
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 2, kNoRider, true><<<grid, block, lds, stream>>>(a);
+  else
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 4, kNoRider, true><<<grid, block, lds, stream>>>(a);
+}
+
 template <typename Vec>
 void launch_step_t(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds, int rider,
                    hipStream_t stream)
@@ -621,6 +636,7 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
 void launch_step(const StepArgs &a, uint32_t vector_bytes, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds,
                  hipStream_t stream, int rider = kNoRider)
 {
+  if (a.codec.raw_bytes && a.slot) return launch_step_codec(a, n_top, wgs, threads, lds, rider, stream);
   if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, wgs, threads, lds, rider, stream);
   else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, wgs, threads, lds, rider, stream);
   else launch_step_t<uint8_t>(a, n_top, wgs, threads, lds, rider, stream);
@@ -651,7 +667,8 @@ int issue_held_step_with_round(apex_replay *r, HeldStep *h, const NstepArgs &ns,
 {
   const uint64_t count = (uint64_t)ns.S * ns.T;
   uint32_t vb = 0, blocks = 0;
-  if (!h->valid || !add_round_small_fits(r, ns, obs, &vb) || vb < h->vector_bytes) return APEX_ERR_NOT_READY;
+  if (!h->valid || h->a.codec.raw_bytes || !add_round_small_fits(r, ns, obs, &vb) || vb < h->vector_bytes)
+    return APEX_ERR_NOT_READY;
   if ((r->tail - r->head) + count > r->cfg.max_slots) return APEX_ERR_FULL;
   const bool both = r->second_version == r->tree_version;
   const int rc = add_round_args(r, ns, obs, act, h->vector_bytes, kStepThreads, both, &h->a.add, &blocks);
@@ -682,7 +699,7 @@ int issue_held_step_with_leaves(apex_replay *r, HeldStep *h, uint64_t count, con
 
 int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64_t *rnd, const float *new_prio,
                 const apex_batch_buffers_t *sets, uint32_t depth, uint32_t first_set, HeldStep *hold,
-                hipStream_t stream)
+                uint32_t codec_raw_bytes, hipStream_t stream)
 {
   const auto idx = [&](uint32_t i) { return (first_set + i) % depth; };
   const auto set = [&](uint32_t i) -> const apex_batch_buffers_t & { return sets[idx(i)]; };
@@ -724,6 +741,10 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
     a.dst = static_cast<uint8_t *>(b.obs);
     a.row_bytes = r->cfg.obs_bytes;
     a.vecs_per_row = (uint32_t)(a.row_bytes / vb);
+    if (codec_raw_bytes) {  // rows decoded on their way out: the set's obs buffer is [k, raw bytes]
+      a.codec = codec_shape(codec_raw_bytes);
+      a.vecs_per_row = codec_raw_bytes / 16;
+    }
     a.act = r->act();
     a.act_bytes = r->cfg.act_bytes;
     a.ret = r->ret();

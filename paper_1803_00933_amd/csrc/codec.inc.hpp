@@ -15,25 +15,6 @@ namespace apex {
 constexpr uint32_t kCodecThreads = 512;
 constexpr uint32_t kCodecMaxBlocks = 4096;  // 256 KB of raw row; one LDS word per block
 
-struct CodecShape {
-  uint32_t raw_bytes, nb, mask_words;
-  uint32_t flat_off, raw_off;  // 16 + M, 16 + M + V
-  uint64_t stride;             // 16 + M + V + 64 nb
-};
-
-__host__ __device__ inline CodecShape codec_shape(uint32_t raw_bytes)
-{
-  CodecShape c{};
-  c.raw_bytes = raw_bytes;
-  c.nb = raw_bytes / 64;
-  c.mask_words = (c.nb + 63) / 64;
-  const uint32_t M = (8 * c.mask_words + 15) / 16 * 16, V = (c.nb + 15) / 16 * 16;
-  c.flat_off = 16 + M;
-  c.raw_off = 16 + M + V;
-  c.stride = (uint64_t)c.raw_off + 64ull * c.nb;
-  return c;
-}
-
 // Blocks kept as they are before block b (mask words in LDS).
 __device__ __forceinline__ uint32_t codec_rank(const uint64_t *mask, uint32_t b)
 {
@@ -208,38 +189,14 @@ __global__ __launch_bounds__(kCodecThreads) void codec_decode_rows_direct_kernel
                                                                                 uint8_t *__restrict__ out, CodecShape c)
 {
   const uint64_t i = blockIdx.x;
-  const uint8_t *e = ring + (uint64_t)slot[i] * ring_stride;
-  const uint64_t *mw = reinterpret_cast<const uint64_t *>(e + 16);
-  uint64_t m[8];
-  uint32_t before[8];  // blocks kept as they are in the words before this one
-  uint32_t run = 0;
-#pragma unroll
-  for (int w = 0; w < 8; ++w) {
-    m[w] = (uint32_t)w < c.mask_words ? mw[w] : 0;
-    before[w] = run;
-    run += __popcll(m[w]);
-  }
+  const CodecRow enc = codec_open_row(ring + (uint64_t)slot[i] * ring_stride, c);
   const uint32_t tid = threadIdx.x, nvec = c.raw_bytes / 16;
   u32x4 *o = reinterpret_cast<u32x4 *>(out + i * c.raw_bytes);
   u32x4 t[4];
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
-    const uint32_t v = u * kCodecThreads + tid;  // block v / 4; the wave's blocks share word (tid >> 8) + 2 u
-    uint64_t word = 0;
-    uint32_t base = 0;
-#pragma unroll
-    for (int w = 0; w < 8; ++w)
-      if ((uint32_t)w == (tid >> 8) + 2 * u) word = m[w], base = before[w];
-    if (v < nvec) {
-      const uint32_t b = v / 4, bit = b & 63;
-      const uint32_t rank = base + __popcll(word & ((1ull << bit) - 1));
-      if (word >> bit & 1) {
-        t[u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(e + c.raw_off + 64 * rank) + (v & 3));
-      } else {
-        const uint32_t x = e[c.flat_off + (b - rank)] * 0x01010101u;
-        t[u] = u32x4{x, x, x, x};
-      }
-    }
+    const uint32_t v = u * kCodecThreads + tid;
+    t[u] = codec_fetch(enc, c, v);
   }
 #pragma unroll
   for (int u = 0; u < 4; ++u) {

@@ -173,6 +173,75 @@ __device__ __forceinline__ uint64_t map_row(const RowMap &m, uint64_t i)
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
+// --------------------------------------------------------------------------------------------
+// Observations stored through the block codec (Section 4.1: observations are kept compressed in the
+// replay memory): shape of an encoded row, and how a wave fetches 16-byte pieces of the raw row
+// out of it.  The format is described in codec.inc.hpp.
+// --------------------------------------------------------------------------------------------
+struct CodecShape {
+  uint32_t raw_bytes, nb, mask_words;  // raw_bytes == 0: no codec
+  uint32_t flat_off, raw_off;          // 16 + M, 16 + M + V
+  uint64_t stride;                     // 16 + M + V + 64 nb
+};
+
+__host__ __device__ inline CodecShape codec_shape(uint32_t raw_bytes)
+{
+  CodecShape c{};
+  c.raw_bytes = raw_bytes;
+  c.nb = raw_bytes / 64;
+  c.mask_words = (c.nb + 63) / 64;
+  const uint32_t M = (8 * c.mask_words + 15) / 16 * 16, V = (c.nb + 15) / 16 * 16;
+  c.flat_off = 16 + M;
+  c.raw_off = 16 + M + V;
+  c.stride = (uint64_t)c.raw_off + 64ull * c.nb;
+  return c;
+}
+
+// An encoded row of at most 512 blocks, opened by a wave: its mask (at most eight words, the same for every
+// lane) and, per word, the number of blocks kept as they are in the words before it.
+struct CodecRow {
+  const uint8_t *e;
+  uint64_t m[8];
+  uint32_t before[8];
+};
+
+__device__ __forceinline__ CodecRow codec_open_row(const uint8_t *e, const CodecShape &c)
+{
+  CodecRow r;
+  r.e = e;
+  const uint64_t *mw = reinterpret_cast<const uint64_t *>(e + 16);
+  uint32_t run = 0;
+#pragma unroll
+  for (int w = 0; w < 8; ++w) {
+    r.m[w] = (uint32_t)w < c.mask_words ? mw[w] : 0;
+    r.before[w] = run;
+    run += __popcll(r.m[w]);
+  }
+  return r;
+}
+
+// 16-byte piece v of the raw row.  The 64 lanes of the calling wave (all of them call) pass 64 consecutive
+// values of v that start at a multiple of 64: their 16 blocks lie within one word of the mask.  Lanes
+// whose v lies beyond the row fetch the wave's first piece instead (and drop it).
+__device__ __forceinline__ u32x4 codec_fetch(const CodecRow &r, const CodecShape &c, uint32_t v)
+{
+  const uint32_t nvec = c.raw_bytes / 16;
+  const uint32_t v_first = __builtin_amdgcn_readfirstlane(v);
+  if (v >= nvec) v = v_first < nvec ? v_first : 0;
+  const uint32_t w = __builtin_amdgcn_readfirstlane(v >> 8);
+  uint64_t word = 0;
+  uint32_t base = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    if ((uint32_t)i == w) word = r.m[i], base = r.before[i];
+  const uint32_t b = v / 4, bit = b & 63;
+  const uint32_t rank = base + __popcll(word & ((1ull << bit) - 1));
+  if (word >> bit & 1)
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(r.e + c.raw_off + 64 * rank) + (v & 3));
+  const uint32_t x = r.e[c.flat_off + (b - rank)] * 0x01010101u;
+  return u32x4{x, x, x, x};
+}
+
 // A learner batch (m <= blockDim) handled by one workgroup: duplicates are resolved in an LDS hash
 // table keyed by slot (the highest position wins), so no pass over global memory is needed for
 // it, and the old mass is fetched while the table is being filled.
@@ -988,6 +1057,10 @@ struct StepArgs {
   // with the write-back of this batch, not with a draw.
   AddRoundArgs add;
   AddLeavesArgs leaves;
+  // Rows stored through the block codec (kCodec launches only): row_bytes is then the stride of the
+  // encoded rows in src, the rows written to dst are codec.raw_bytes long, vecs_per_row counts their
+  // 16-byte pieces, and rows have at most 512 blocks.
+  CodecShape codec;
 };
 
 enum StepRider { kNoRider = 0, kRoundRides = 1, kLeavesRide = 2 };
@@ -1087,7 +1160,8 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
 // kTopChunk: passes of 512 top-level nodes whose loads the drawing wave issues together (1 for tops of at
 // most 512 nodes, 2 up to 1024, 4 beyond: more registers, fewer memory round trips).
 // kRider: what the workgroups beyond the first k carry (StepArgs::add or ::leaves).
-template <typename Vec, int kThreads, int kUnroll, int kTopChunk, int kRider>
+// kCodec: the rows are decoded on their way out (StepArgs::codec; Vec is 16 bytes wide).
+template <typename Vec, int kThreads, int kUnroll, int kTopChunk, int kRider, bool kCodec = false>
 __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
 {
   extern __shared__ uint64_t lds[];
@@ -1156,12 +1230,19 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   // ---- the row
   const uint32_t copiers = nthr - first;
   const Vec *s = reinterpret_cast<const Vec *>(a.src + (uint64_t)my_slot * a.row_bytes);
-  Vec *d = reinterpret_cast<Vec *>(a.dst + (uint64_t)row * a.row_bytes);
+  Vec *d = reinterpret_cast<Vec *>(a.dst + (uint64_t)row * (kCodec ? (uint64_t)a.codec.raw_bytes : a.row_bytes));
   Vec tmp[kUnroll];
+  CodecRow enc;
+  if constexpr (kCodec) enc = codec_open_row(reinterpret_cast<const uint8_t *>(s), a.codec);
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = tid - first + u * copiers;
-    if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+    if constexpr (kCodec) {
+      const u32x4 piece = codec_fetch(enc, a.codec, v);
+      __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
+    } else {
+      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+    }
   }
 
   if (carrier) add_delta(a.wr, my_slot, pc_dq);
@@ -1190,7 +1271,12 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint32_t v = base + tid - first + u * copiers;
-      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+      if constexpr (kCodec) {
+        const u32x4 piece = codec_fetch(enc, a.codec, v);
+        __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
+      } else {
+        if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+      }
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {

@@ -36,6 +36,7 @@ struct apex_pipeline {
   bool tail_unmarked = false; // the tail has moved since tail_ready was last recorded
   bool add_deferred = false;  // the open round is issued as one launch by add_end
   HeldStep held;              // the last step launch of the latest steps call, if it waits for that launch
+  uint32_t codec_raw_bytes = 0;  // != 0: observations pass through the block codec (apex_pipeline_set_codec)
   NstepArgs add_ns{};
   const void *add_obs = nullptr, *add_act = nullptr;
   uint64_t add_count = 0;
@@ -190,6 +191,24 @@ int apex_pipeline_join(apex_pipeline_t *p, void *stream)
   return APEX_OK;
 }
 
+int apex_pipeline_set_codec(apex_pipeline_t *p, uint32_t raw_bytes)
+{
+  if (!p || p->capturing || p->add_open) return APEX_ERR_INVALID_ARG;
+  APEX_TRY(issue_held_step(&p->held, p->tree));
+  if (raw_bytes == 0) {
+    p->codec_raw_bytes = 0;
+    return APEX_OK;
+  }
+  const size_t stride = apex_codec_row_bytes(raw_bytes);
+  if (!stride || raw_bytes / 64 > 512 || (p->r->cfg.obs_bytes & 15)) return APEX_ERR_INVALID_ARG;
+  if (stride > p->r->cfg.obs_bytes) return APEX_ERR_TOO_LARGE;
+  if (!fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) return APEX_ERR_INVALID_ARG;
+  for (const apex_batch_buffers_t &b : p->sets)
+    if ((uintptr_t)b.obs & 15) return APEX_ERR_INVALID_ARG;
+  p->codec_raw_bytes = raw_bytes;
+  return APEX_OK;
+}
+
 int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64_t *rnd, const float *new_prio,
                         uint32_t *first_set_out)
 {
@@ -201,10 +220,12 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
     // With an add round open the last launch is held back: add_end issues it with the round (a small one)
     // or the round's masses (a large one, whose payload the other stream copies) inside.
     APEX_TRY(fused_steps(p->r, n, p->k, beta, rnd, new_prio, p->sets.data(), p->depth,
-                         (uint32_t)(p->step % p->depth), p->add_open ? &p->held : nullptr, p->tree));
+                         (uint32_t)(p->step % p->depth), p->add_open ? &p->held : nullptr, p->codec_raw_bytes,
+                         p->tree));
     p->step += n;
     return APEX_OK;
   }
+  if (n && p->codec_raw_bytes) return APEX_ERR_INVALID_ARG;  // set_codec has checked that steps are fused
   for (uint32_t i = 0; i < n; ++i) {
     const uint32_t set = (uint32_t)(p->step % p->depth);
     const apex_batch_buffers_t &b = p->sets[set];
@@ -246,7 +267,7 @@ int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t
   if (!S || !T || !n || !A || !q_online || !q_target || !action || !reward || !discount || !prio || !ret || !gacc)
     return APEX_ERR_INVALID_ARG;
   p->add_on_tree = count * r->cfg.obs_bytes < kSmallPayloadBytes;
-  p->add_deferred = p->add_on_tree && obs && r->cfg.obs_bytes <= 1024;
+  p->add_deferred = p->add_on_tree && obs && r->cfg.obs_bytes <= 1024 && !p->codec_raw_bytes;
   if (p->add_deferred) {
     // a small round of short rows is one launch, issued by add_end (the inputs stay untouched until then)
     p->add_ns = NstepArgs{S, T, n, A, q_online, q_target, action, reward, discount};
@@ -263,7 +284,10 @@ int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t
     }
     APEX_TRY(apex_nstep_priorities(S, T, n, A, q_online, q_target, action, reward, discount, r->cfg.alpha, r->cfg.eps,
                                    r->cfg.frac_bits, r->cfg.max_slots, prio, ret, gacc, nullptr, s));
-    APEX_TRY(apex_replay_add_payload(r, count, obs, act, ret, gacc, s));
+    if (p->codec_raw_bytes && obs)
+      APEX_TRY(apex_replay_add_payload_encoded(r, count, obs, p->codec_raw_bytes, act, ret, gacc, s));
+    else
+      APEX_TRY(apex_replay_add_payload(r, count, obs, act, ret, gacc, s));
     if (!p->add_on_tree) APEX_TRY(mark_record(p, p->payload_done, p->add));
   }
   p->add_open = true;
