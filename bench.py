@@ -531,6 +531,92 @@ def frame_like_rows(n, raw_bytes, flat_share, seed):
     return torch.where(flat, pal, rows).view(n, raw_bytes)
 
 
+def codec_schedule_us(job, K, log, flat_share=0.8):
+    """The headline schedule (one batch of 512 per learner step, an add round of 360 x 50 every 25 steps, FIFO
+    eviction every 100) on a memory that stores its observations through the codec, fed with frame-like rows:
+    add rounds are encoded on the copy stream, the step launch decodes as it gathers."""
+    import torch
+    from paper_1803_00933_amd import apex
+    w = job.w
+    stride = int(apex.lib.apex_codec_row_bytes(w.obs_bytes))
+    rep = apex.Replay(w.capacity, w.max_slots, stride, w.act_bytes, w.alpha, w.eps, w.frac_bits)
+    pipe = apex.Pipeline(rep, 8, 1, w.k)
+    assert pipe.set_codec(w.obs_bytes) == 0
+    stage = frame_like_rows(w.add_count, w.obs_bytes, flat_share, seed=5)
+
+    def add_begin(i):
+        t = job.rounds[i % job.n_pool]
+        prio, ret, gacc, _ = t["out"]
+        assert pipe.add_begin(t["q_online"], t["q_target"], t["action"], t["reward"], t["discount"], w.n, stage,
+                              t["act"], prio, ret, gacc) == 0
+
+    assert pipe.fork() == 0
+    n_fill = -(-w.capacity // w.add_count)
+    for i in range(n_fill):
+        add_begin(i)
+        assert pipe.add_end(i == n_fill - 1)[0] == 0
+    assert pipe.join() == 0
+    torch.cuda.synchronize()
+    assert rep.stats()["size"] == w.capacity
+
+    def run(first, count):
+        assert pipe.fork() == 0
+        for f in range(first, first + count, ADD_EVERY):
+            add_begin(f // ADD_EVERY)
+            assert pipe.steps(ADD_EVERY, w.beta, job.rnd[f:f + ADD_EVERY], job.td[f:f + ADD_EVERY])[0] == 0
+            assert pipe.add_end((f + ADD_EVERY) % EVICT_EVERY == 0)[0] == 0
+        assert pipe.join() == 0
+
+    def learner_only(count):
+        assert pipe.fork() == 0
+        assert pipe.steps(count, w.beta, job.rnd[:count], job.td[:count])[0] == 0
+        assert pipe.join() == 0
+
+    run(0, EVICT_EVERY)
+    dt, _, _ = job.timed_median(lambda: run(0, K), reps=3)
+    assert rep.stats()["size"] == w.capacity
+    dt_learner, _, _ = job.timed_median(lambda: learner_only(K), reps=3)
+    pipe.close()
+    # the paper's prefetch depth as the unit of work: 16 batches per call, fetched through the decoder
+    nb = 16
+    calls = K // nb
+    pipe16 = apex.Pipeline(rep, 2, nb, w.k)
+    assert pipe16.set_codec(w.obs_bytes) == 0
+    rnd = job.rnd[:calls * nb].reshape(calls, nb * w.k)
+    td = job.td[:calls * nb].reshape(calls, nb * w.k)
+
+    def go16(with_actors):
+        assert pipe16.fork() == 0
+        for c in range(calls):
+            done, due = c * nb // ADD_EVERY, (c + 1) * nb // ADD_EVERY
+            if with_actors and due > done:
+                t = job.rounds[done % job.n_pool]
+                prio, ret, gacc, _ = t["out"]
+                assert pipe16.add_begin(t["q_online"], t["q_target"], t["action"], t["reward"], t["discount"], w.n,
+                                        stage, t["act"], prio, ret, gacc) == 0
+            assert pipe16.steps(1, w.beta, rnd[c], td[c])[0] == 0
+            if with_actors and due > done:
+                assert pipe16.add_end((c + 1) * nb // EVICT_EVERY > c * nb // EVICT_EVERY)[0] == 0
+        assert pipe16.join() == 0
+        if with_actors:
+            assert rep.evict(stream=torch.cuda.current_stream())[0] == 0
+
+    go16(True)
+    dt16, _, _ = job.timed_median(lambda: go16(True), reps=3)
+    dt16_learner, _, _ = job.timed_median(lambda: go16(False), reps=3)
+    pipe16.close()
+    rep.close()
+    del rep, stage
+    torch.cuda.empty_cache()
+    res = {"flat_blocks_share": flat_share,
+           "per_batch_steps_us_per_step": dt / K * 1e6, "per_batch_steps_learner_only_us_per_step": dt_learner / K * 1e6,
+           "16_batches_per_call_us_per_batch": dt16 / (calls * nb) * 1e6,
+           "16_batches_per_call_learner_only_us_per_batch": dt16_learner / (calls * nb) * 1e6}
+    log("pipeline with the observation codec, frame-like rows (%d %% flat blocks): %s"
+        % (int(flat_share * 100), {k2: round(v, 2) for k2, v in res.items()}))
+    return res
+
+
 def codec_numbers(log):
     """The observation codec (Section 4.1: observations are stored compressed) on frame-stack rows: the payload
     of an add round encoded on its way into the ring, batches decoded on their way out, against the plain
@@ -672,6 +758,7 @@ def main():
     dt_in_place, _, _ = job.timed_median(lambda: job.run_pipelined(W, K, in_place=True))
     log("pipeline, observations of the add rounds written in place by their producer (no copy): %.2f us/step"
         % (dt_in_place / K * 1e6))
+    us_codec = codec_schedule_us(job, K, log) if not args.no_control else None
     us16 = job.prefetch16_us_per_batch(K, with_actors=False)
     us16_full = job.prefetch16_us_per_batch(K, with_actors=True)
     log("pipeline, 16 batches of 512 per call: %.2f us per batch learner only, %.2f with adds and eviction"
@@ -725,6 +812,7 @@ def main():
         "adds_per_s": w.add_count * (K // ADD_EVERY) / dt,
         "nstep_priorities_per_s": w.add_count / (ops["nstep_priorities_18000"] * 1e-6),
         "ops_us": ops,
+        "observation_codec_schedule": us_codec,
         "repetitions": {"n": 5, "value_is": "median",
                         "pipeline_us_per_step": [t / K * 1e6 for t in reps_pipe],
                         "pipeline_graph_us_per_step": [t / K * 1e6 for t in reps_graph]},

@@ -399,10 +399,11 @@ int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out
  * Observations through the block codec (see apex_codec_row_bytes) on the pipeline's fast path: from
  * this call on the obs argument of apex_pipeline_add_begin is [S*T, raw_bytes] and is encoded on its
  * way into the ring, and the obs buffers of the sets are [k, raw_bytes] and receive decoded rows (the
- * step launch decodes as it copies).  raw_bytes == 0 switches back.  Only for pipelines whose steps
- * are single launches (one batch per step, at least three sets) and rows of at most 512 blocks (32 KB):
- * APEX_ERR_INVALID_ARG otherwise, APEX_ERR_TOO_LARGE if the memory's rows are too short.  Not while a
- * round is open or a capture is running.
+ * step launch decodes as it copies; steps of several batches fetch theirs through the decoder on the
+ * copy stream).  raw_bytes == 0 switches back.  Only for pipelines whose steps are single launches (one
+ * batch per step, at least three sets) or go to the copy stream (many batches per step), and rows of at
+ * most 512 blocks (32 KB): APEX_ERR_INVALID_ARG otherwise, APEX_ERR_TOO_LARGE if the memory's rows are
+ * too short.  Not while a round is open or a capture is running.
  */
 int apex_pipeline_set_codec(apex_pipeline_t *p, uint32_t raw_bytes);
 

@@ -192,12 +192,12 @@ __global__ __launch_bounds__(kCodecThreads) void codec_decode_rows_direct_kernel
   const CodecRow enc = codec_open_row(ring + (uint64_t)slot[i] * ring_stride, c);
   const uint32_t tid = threadIdx.x, nvec = c.raw_bytes / 16;
   u32x4 *o = reinterpret_cast<u32x4 *>(out + i * c.raw_bytes);
+  CodecFetched f[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) f[u] = codec_fetch(enc, c, u * kCodecThreads + tid);
   u32x4 t[4];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const uint32_t v = u * kCodecThreads + tid;
-    t[u] = codec_fetch(enc, c, v);
-  }
+  for (int u = 0; u < 4; ++u) t[u] = codec_piece(f[u]);
 #pragma unroll
   for (int u = 0; u < 4; ++u) {
     const uint32_t v = u * kCodecThreads + tid;

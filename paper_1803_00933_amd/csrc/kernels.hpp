@@ -220,10 +220,18 @@ __device__ __forceinline__ CodecRow codec_open_row(const uint8_t *e, const Codec
   return r;
 }
 
-// 16-byte piece v of the raw row.  The 64 lanes of the calling wave (all of them call) pass 64 consecutive
-// values of v that start at a multiple of 64: their 16 blocks lie within one word of the mask.  Lanes
-// whose v lies beyond the row fetch the wave's first piece instead (and drop it).
-__device__ __forceinline__ u32x4 codec_fetch(const CodecRow &r, const CodecShape &c, uint32_t v)
+// 16-byte piece v of the raw row, in two halves so that a lane can have several pieces on their way before
+// it looks at the first: codec_fetch issues the load (of the piece itself, or of its block's byte),
+// codec_piece turns what arrived into the 16 bytes.  The 64 lanes of the calling wave (all of them call)
+// pass 64 consecutive values of v that start at a multiple of 64: their 16 blocks lie within one word of the
+// mask.  Lanes whose v lies beyond the row fetch the wave's first piece instead (and drop it).
+struct CodecFetched {
+  u32x4 data;    // kept block: the piece
+  uint32_t byte; // flat block: its byte
+  bool kept;
+};
+
+__device__ __forceinline__ CodecFetched codec_fetch(const CodecRow &r, const CodecShape &c, uint32_t v)
 {
   const uint32_t nvec = c.raw_bytes / 16;
   const uint32_t v_first = __builtin_amdgcn_readfirstlane(v);
@@ -236,10 +244,68 @@ __device__ __forceinline__ u32x4 codec_fetch(const CodecRow &r, const CodecShape
     if ((uint32_t)i == w) word = r.m[i], base = r.before[i];
   const uint32_t b = v / 4, bit = b & 63;
   const uint32_t rank = base + __popcll(word & ((1ull << bit) - 1));
-  if (word >> bit & 1)
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(r.e + c.raw_off + 64 * rank) + (v & 3));
-  const uint32_t x = r.e[c.flat_off + (b - rank)] * 0x01010101u;
-  return u32x4{x, x, x, x};
+  CodecFetched f;
+  f.kept = word >> bit & 1;
+  f.byte = 0;
+  f.data = u32x4{0, 0, 0, 0};
+  if (f.kept)
+    f.data = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(r.e + c.raw_off + 64 * rank) + (v & 3));
+  else
+    f.byte = r.e[c.flat_off + (b - rank)];
+  return f;
+}
+
+__device__ __forceinline__ u32x4 codec_piece(const CodecFetched &f)
+{
+  const uint32_t x = f.byte * 0x01010101u;
+  return f.kept ? f.data : u32x4{x, x, x, x};
+}
+
+// The same with a whole block per lane (a flat block then costs its lane one load instead of four): the 64
+// lanes of the calling wave (all of them call) pass 64 consecutive block numbers that start at a multiple of
+// 64.  Lanes whose block lies beyond the row fetch nothing.
+struct CodecBlock {
+  u32x4 q[4];
+  uint32_t byte;
+  bool kept, valid;
+};
+
+__device__ __forceinline__ CodecBlock codec_fetch_block(const CodecRow &r, const CodecShape &c, uint32_t b)
+{
+  const uint32_t w = __builtin_amdgcn_readfirstlane(b >> 6);
+  uint64_t word = 0;
+  uint32_t base = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+    if ((uint32_t)i == w) word = r.m[i], base = r.before[i];
+  const uint32_t bit = b & 63;
+  const uint32_t rank = base + __popcll(word & ((1ull << bit) - 1));
+  CodecBlock f;
+  f.valid = b < c.nb;
+  f.kept = word >> bit & 1;
+  f.byte = 0;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) f.q[q] = u32x4{0, 0, 0, 0};
+  if (f.valid) {
+    if (f.kept) {
+      const u32x4 *p = reinterpret_cast<const u32x4 *>(r.e + c.raw_off + 64 * rank);
+#pragma unroll
+      for (int q = 0; q < 4; ++q) f.q[q] = __builtin_nontemporal_load(p + q);
+    } else {
+      f.byte = r.e[c.flat_off + (b - rank)];
+    }
+  }
+  return f;
+}
+
+// Writes the block to its place in the raw row `out`.
+__device__ __forceinline__ void codec_store_block(const CodecBlock &f, uint8_t *out, uint32_t b)
+{
+  if (!f.valid) return;
+  const uint32_t x = f.byte * 0x01010101u;
+  u32x4 *o = reinterpret_cast<u32x4 *>(out + 64ull * b);
+#pragma unroll
+  for (int q = 0; q < 4; ++q) __builtin_nontemporal_store(f.kept ? f.q[q] : u32x4{x, x, x, x}, o + q);
 }
 
 // A learner batch (m <= blockDim) handled by one workgroup: duplicates are resolved in an LDS hash
@@ -1233,14 +1299,14 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   Vec *d = reinterpret_cast<Vec *>(a.dst + (uint64_t)row * (kCodec ? (uint64_t)a.codec.raw_bytes : a.row_bytes));
   Vec tmp[kUnroll];
   CodecRow enc;
-  if constexpr (kCodec) enc = codec_open_row(reinterpret_cast<const uint8_t *>(s), a.codec);
+  CodecBlock blk;
+  if constexpr (kCodec) {  // a block per lane; rows of at most 512 blocks take at most two passes
+    enc = codec_open_row(reinterpret_cast<const uint8_t *>(s), a.codec);
+    blk = codec_fetch_block(enc, a.codec, tid - first);
+  } else {
 #pragma unroll
-  for (int u = 0; u < kUnroll; ++u) {
-    const uint32_t v = tid - first + u * copiers;
-    if constexpr (kCodec) {
-      const u32x4 piece = codec_fetch(enc, a.codec, v);
-      __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
-    } else {
+    for (int u = 0; u < kUnroll; ++u) {
+      const uint32_t v = tid - first + u * copiers;
       if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
     }
   }
@@ -1261,22 +1327,25 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
     if (j < a.k) a.wa.weight_out[j] = pow_fixed_sequence(fmn / (float)mass_mine, a.wa.beta);
   }
 
+  if constexpr (kCodec) {
+    codec_store_block(blk, reinterpret_cast<uint8_t *>(d), tid - first);
+    for (uint32_t b0 = copiers; b0 < a.codec.nb; b0 += copiers) {
+      blk = codec_fetch_block(enc, a.codec, b0 + tid - first);
+      codec_store_block(blk, reinterpret_cast<uint8_t *>(d), b0 + tid - first);
+    }
+  } else {
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = tid - first + u * copiers;
     if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
   }
+  }
   // rows longer than one pass of the workgroup (more than 32 KB, or narrow vectors)
-  for (uint32_t base = copiers * kUnroll; base < a.vecs_per_row; base += copiers * kUnroll) {
+  for (uint32_t base = copiers * kUnroll; !kCodec && base < a.vecs_per_row; base += copiers * kUnroll) {
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint32_t v = base + tid - first + u * copiers;
-      if constexpr (kCodec) {
-        const u32x4 piece = codec_fetch(enc, a.codec, v);
-        __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
-      } else {
-        if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
-      }
+      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {

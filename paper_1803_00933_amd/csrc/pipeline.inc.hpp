@@ -202,7 +202,7 @@ int apex_pipeline_set_codec(apex_pipeline_t *p, uint32_t raw_bytes)
   const size_t stride = apex_codec_row_bytes(raw_bytes);
   if (!stride || raw_bytes / 64 > 512 || (p->r->cfg.obs_bytes & 15)) return APEX_ERR_INVALID_ARG;
   if (stride > p->r->cfg.obs_bytes) return APEX_ERR_TOO_LARGE;
-  if (!fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) return APEX_ERR_INVALID_ARG;
+  if (!p->wide && !fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) return APEX_ERR_INVALID_ARG;
   for (const apex_batch_buffers_t &b : p->sets)
     if ((uintptr_t)b.obs & 15) return APEX_ERR_INVALID_ARG;
   p->codec_raw_bytes = raw_bytes;
@@ -225,7 +225,7 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
     p->step += n;
     return APEX_OK;
   }
-  if (n && p->codec_raw_bytes) return APEX_ERR_INVALID_ARG;  // set_codec has checked that steps are fused
+  if (n && p->codec_raw_bytes && !p->wide) return APEX_ERR_INVALID_ARG;  // set_codec has checked the step mode
   for (uint32_t i = 0; i < n; ++i) {
     const uint32_t set = (uint32_t)(p->step % p->depth);
     const apex_batch_buffers_t &b = p->sets[set];
@@ -235,7 +235,13 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
                                         p->tree));
       APEX_TRY(mark_record(p, p->drawn, p->tree));
       APEX_TRY(mark_wait(p->drawn, p->add));
-      APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs, p->add));
+      if (p->codec_raw_bytes) {  // weights, then the rows through the decoder
+        APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, nullptr, p->add));
+        APEX_TRY(apex_replay_gather_decoded(p->r, per, b.slot, p->codec_raw_bytes, b.obs, nullptr, nullptr, nullptr,
+                                            p->add));
+      } else {
+        APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs, p->add));
+      }
       APEX_TRY(mark_record(p, p->gathered[set], p->add));
       if (new_prio) APEX_TRY(apex_replay_update_priorities(p->r, per, b.key, new_prio + i * per, p->tree));
       ++p->step;

@@ -71,15 +71,18 @@ def test_rows_through_the_codec(raw_bytes, extra, flat_share):
 
 
 @pytest.mark.gpu
-@pytest.mark.parametrize("raw_bytes,flat_share", [(4160, 0.7), (28224, 0.8), (28224, 0.0), (256, 0.5), (32768, 0.9)])
-def test_pipeline_with_the_codec(raw_bytes, flat_share):
+@pytest.mark.parametrize("raw_bytes,flat_share,nb,k,depth", [
+    (4160, 0.7, 1, 80, 4), (28224, 0.8, 1, 80, 4), (28224, 0.0, 1, 80, 4), (256, 0.5, 1, 80, 4), (32768, 0.9, 1, 80, 4),
+    (4160, 0.7, 4, 512, 2),          # steps of several batches: fetched through the decoder on the copy stream
+])
+def test_pipeline_with_the_codec(raw_bytes, flat_share, nb, k, depth):
     """The pipeline's fast path with observations stored encoded: add rounds encoded on the copy stream (or on
     the learner's stream when small), learner steps that decode while they gather, against the oracle that
     stores the raw rows."""
     from paper_1803_00933_amd import apex, synth
     rng = np.random.default_rng(raw_bytes + 7)
     stride = oracle.codec_row_bytes(raw_bytes)
-    small = synth.WORKLOADS["tiny"].scaled(obs_bytes=stride, capacity=2500, max_slots=4096, streams=4, chunk=25, k=80)
+    small = synth.WORKLOADS["tiny"].scaled(obs_bytes=stride, capacity=2500, max_slots=4096, streams=4, chunk=25, k=k)
     large = small.scaled(streams=48)
     g = apex.Replay(small.capacity, small.max_slots, stride, small.act_bytes)
     o = oracle.Replay(small.capacity, small.max_slots, raw_bytes, small.act_bytes)
@@ -90,9 +93,9 @@ def test_pipeline_with_the_codec(raw_bytes, flat_share):
     prio = rng.lognormal(0, 1, cnt).astype(F32)
     assert g.add_payload_encoded(dev(raw), dev(act), dev(ret), dev(gacc)) == 0
     assert g.add_publish(dev(prio)) == o.add(prio, raw, act, ret, gacc)
-    depth = 4
-    pipe = apex.Pipeline(g, depth, 1, small.k)
+    pipe = apex.Pipeline(g, depth, nb, small.k)
     assert pipe.set_codec(raw_bytes) == 0
+    n_steps = min(3, depth - 1)
     assert pipe.fork() == 0
     for i, w in enumerate([small, large, small, large, large]):
         d = synth.actor_round(w, i)
@@ -100,17 +103,17 @@ def test_pipeline_with_the_codec(raw_bytes, flat_share):
         d["obs"] = frame_like(rng, n_rows, raw_bytes, flat_share)
         dd = {k2: dev(v) for k2, v in d.items()}
         scratch = [torch.empty(n_rows, dtype=torch.float32, device="cuda:0") for _ in range(3)]
-        rnd = rng.integers(0, U64, (3, w.k), dtype=np.uint64)
-        newp = rng.lognormal(0, 1, (3, w.k)).astype(F32)
+        rnd = rng.integers(0, U64, (n_steps, nb * w.k), dtype=np.uint64)
+        newp = rng.lognormal(0, 1, (n_steps, nb * w.k)).astype(F32)
         d_rnd, d_newp = dev(rnd), dev(newp)
         assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
                               dd["obs"], dd["act"], *scratch) == 0
-        rc, first = pipe.steps(3, 0.4, d_rnd, d_newp)
+        rc, first = pipe.steps(n_steps, 0.4, d_rnd, d_newp)
         assert rc == 0
         rc, first_key, ev = pipe.add_end(True)
         refs = []
-        for s_ in range(3):
-            refs.append(o.sample(1, w.k, 0.4, rnd[s_])[1])
+        for s_ in range(n_steps):
+            refs.append(o.sample(nb, w.k, 0.4, rnd[s_])[1])
             o.update_priorities(refs[-1]["key"], newp[s_])
         ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
                                       w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
@@ -118,7 +121,7 @@ def test_pipeline_with_the_codec(raw_bytes, flat_share):
         assert o.evict() == (0, ev)
         assert pipe.join() == 0
         torch.cuda.synchronize()
-        for s_ in range(3):
+        for s_ in range(n_steps):
             assert_sample_equal(pipe.sets[(first + s_) % depth], refs[s_])
         check_gpu_tree(g, o)
         assert pipe.fork() == 0
