@@ -65,6 +65,106 @@ __global__ __launch_bounds__(256) void pe_add_kernel(PeView v, PeState *__restri
   }
 }
 
+// The same with the payload of short observation rows in the same launch: 2^lanes_log2 lanes per transition
+// copy its observation and action bytes into the slot, the first of them does the rest.  act, ret, gacc may
+// be null.
+template <typename Vec>
+__global__ __launch_bounds__(256) void pe_add_short_kernel(PeView v, PeState *__restrict__ st, uint64_t count,
+                                                           const float *__restrict__ prio,
+                                                           const uint8_t *__restrict__ obs,
+                                                           const uint8_t *__restrict__ act,
+                                                           const float *__restrict__ ret,
+                                                           const float *__restrict__ gacc,
+                                                           uint8_t *__restrict__ obs_ring,
+                                                           uint8_t *__restrict__ act_ring,
+                                                           float *__restrict__ ret_ring, float *__restrict__ gacc_ring,
+                                                           uint32_t vecs_per_row, uint32_t lanes_log2,
+                                                           uint64_t obs_bytes, uint32_t act_bytes)
+{
+  const uint32_t rows_per_block = blockDim.x >> lanes_log2, lanes = 1u << lanes_log2;
+  const uint64_t i = (uint64_t)blockIdx.x * rows_per_block + (threadIdx.x >> lanes_log2);
+  const uint32_t vv = threadIdx.x & (lanes - 1);
+  uint32_t nclamp = 0;
+  if (i < count) {
+    const uint64_t slot = v.free_ring[(st->free_head + i) % v.ts.P];
+    if (vv < vecs_per_row)
+      reinterpret_cast<Vec *>(obs_ring + slot * obs_bytes)[vv] = reinterpret_cast<const Vec *>(obs + i * obs_bytes)[vv];
+    if (act)
+      for (uint32_t by = vv; by < act_bytes; by += lanes) act_ring[slot * act_bytes + by] = act[i * act_bytes + by];
+    if (vv == 0) {
+      if (ret) ret_ring[slot] = ret[i];
+      if (gacc) gacc_ring[slot] = gacc[i];
+      v.gen[slot] += 1;
+      bool c1, c2;
+      const float p = prio[i];
+      const uint64_t q1 = quantise_priority(p, v.qs, &c1), q2 = quantise_priority(p, v.qe, &c2);
+      v.ts.level[0][slot] = q1;  // a free slot weighs nothing in either tree
+      v.te.level[0][slot] = q2;
+      add_to_ancestors(v.ts, slot, q1);
+      add_to_ancestors(v.te, slot, q2);
+      nclamp = (uint32_t)c1 + (uint32_t)c2;
+    }
+  }
+  const uint64_t nc = wave_sum(nclamp);
+  if (nc && lane_id() == 0) atomic_add_u64(&st->base.n_clamped, nc);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t t = __hip_atomic_fetch_add(&st->base.ticket_add, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == gridDim.x - 1) {
+      st->base.ticket_add = 0;
+      st->free_head += count;
+      st->base.tail += count;
+    }
+  }
+}
+
+// A learner batch of at most 1024 pairs in one workgroup: pairs naming one slot are resolved in an LDS hash
+// table (the highest position wins), so the two passes below shrink to one launch.
+__global__ __launch_bounds__(1024) void pe_update_small_kernel(PeView v, PeState *__restrict__ st, uint32_t m,
+                                                               const uint64_t *__restrict__ key,
+                                                               const float *__restrict__ prio)
+{
+  __shared__ uint32_t h_slot[kDedupeSlots];
+  __shared__ uint32_t h_pos[kDedupeSlots];
+  const uint32_t i = threadIdx.x;
+  for (uint32_t t = i; t < kDedupeSlots; t += blockDim.x) {
+    h_slot[t] = 0xffffffffu;
+    h_pos[t] = 0;
+  }
+  __syncthreads();
+  uint32_t slot = 0, h = 0, nclamp = 0;
+  uint64_t q1 = 0, q2 = 0;
+  const bool valid = i < m && pe_key_valid(v, key[i], &slot);
+  const bool stale = i < m && !valid;
+  if (valid) {
+    h = (slot * 2654435761u) >> 21;  // top 11 bits
+    for (;;) {
+      const uint32_t prev = atomicCAS(&h_slot[h], 0xffffffffu, slot);
+      if (prev == 0xffffffffu || prev == slot) break;
+      h = (h + 1) & (kDedupeSlots - 1);
+    }
+    atomicMax(&h_pos[h], i + 1);
+    bool c1, c2;
+    const float p = prio[i];
+    q1 = quantise_priority(p, v.qs, &c1);
+    q2 = quantise_priority(p, v.qe, &c2);
+    nclamp = (uint32_t)c1 + (uint32_t)c2;
+  }
+  __syncthreads();
+  if (valid && h_pos[h] == i + 1) {
+    const uint64_t o1 = v.ts.level[0][slot], o2 = v.te.level[0][slot];
+    v.ts.level[0][slot] = q1;
+    v.te.level[0][slot] = q2;
+    add_to_ancestors(v.ts, slot, q1 - o1);
+    add_to_ancestors(v.te, slot, q2 - o2);
+  }
+  const uint64_t ns = __popcll(__ballot(stale)), nc = wave_sum(nclamp);
+  if (lane_id() == 0) {
+    if (ns) atomic_add_u64(&st->base.n_stale, ns);
+    if (nc) atomic_add_u64(&st->base.n_clamped, nc);
+  }
+}
+
 __global__ __launch_bounds__(256) void pe_update_claim_kernel(PeView v, PeState *__restrict__ st, uint32_t m,
                                                               const uint64_t *__restrict__ key,
                                                               uint32_t *__restrict__ claim)
@@ -167,30 +267,32 @@ __global__ __launch_bounds__(kPeScanThreads) void pe_scan_blocks_kernel(uint32_t
   if (t == 0) st->round_total = total;
 }
 
-__global__ __launch_bounds__(kPeScanThreads) void pe_remove_kernel(PeView v, const PeState *__restrict__ st,
+__global__ __launch_bounds__(kPeScanThreads) void pe_remove_kernel(PeView v, PeState *__restrict__ st,
                                                                    const uint32_t *__restrict__ cand,
                                                                    const uint32_t *__restrict__ pos,
                                                                    const uint32_t *__restrict__ block_offsets)
 {
   const uint64_t j = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (j >= st->remaining) return;
-  const uint32_t p = pos[j];
-  if (p == 0xffffffffu) return;
-  const uint32_t slot = cand[j];
-  const uint64_t o1 = v.ts.level[0][slot], o2 = v.te.level[0][slot];
-  v.ts.level[0][slot] = 0;
-  v.te.level[0][slot] = 0;
-  add_to_ancestors(v.ts, slot, 0 - o1);
-  add_to_ancestors(v.te, slot, 0 - o2);
-  v.free_ring[(st->free_tail + block_offsets[blockIdx.x] + p) % v.ts.P] = slot;
-}
-
-__global__ void pe_round_end_kernel(PeState *st)
-{
-  if (threadIdx.x == 0 && blockIdx.x == 0) {
-    st->free_tail += st->round_total;
-    st->base.head += st->round_total;
-    st->remaining -= st->round_total;
+  const uint32_t p = j < st->remaining ? pos[j] : 0xffffffffu;
+  if (p != 0xffffffffu) {
+    const uint32_t slot = cand[j];
+    const uint64_t o1 = v.ts.level[0][slot], o2 = v.te.level[0][slot];
+    v.ts.level[0][slot] = 0;
+    v.te.level[0][slot] = 0;
+    add_to_ancestors(v.ts, slot, 0 - o1);
+    add_to_ancestors(v.te, slot, 0 - o2);
+    v.free_ring[(st->free_tail + block_offsets[blockIdx.x] + p) % v.ts.P] = slot;
+  }
+  // the last workgroup to have read the round's counters closes the round
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const uint32_t t = __hip_atomic_fetch_add(&st->base.ticket_evict, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (t == gridDim.x - 1) {
+      st->base.ticket_evict = 0;
+      st->free_tail += st->round_total;
+      st->base.head += st->round_total;
+      st->remaining -= st->round_total;
+    }
   }
 }
 
@@ -378,9 +480,29 @@ int apex_pe_add(apex_pe_replay_t *r, uint64_t count, const void *obs, const void
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
   const RowMap freed{r->v.free_ring, &r->state()->free_head, r->cfg.max_slots};  // the next free slots, in order
   const PayloadRing pr{r->obs(), r->act(), r->ret(), r->gacc(), r->cfg.obs_bytes, r->cfg.act_bytes};
-  const int rc = add_payload_rows(pr, count, obs, act, ret, gacc, freed, stream);
-  if (rc != APEX_OK) return rc;
-  pe_add_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->v, r->state(), count, prio);
+  const uintptr_t mis = (uintptr_t)obs | (uintptr_t)r->obs() | (uintptr_t)r->cfg.obs_bytes;
+  const uint32_t vb = (mis & 15) == 0 ? 16 : (mis & 3) == 0 ? 4 : 1;
+  const uint32_t vpr = r->cfg.obs_bytes / vb;
+  if (obs && vpr <= 256) {  // short rows: payload and masses in one launch
+    uint32_t lanes_log2 = 0;
+    while ((1u << lanes_log2) < vpr) ++lanes_log2;
+    const uint64_t rows_per_block = 256u >> lanes_log2;
+    const uint64_t blocks = (count + rows_per_block - 1) / rows_per_block;
+    if (blocks > 0x7fffffffull) return APEX_ERR_TOO_LARGE;
+    const dim3 grid((uint32_t)blocks), block(256);
+    const uint8_t *o8 = static_cast<const uint8_t *>(obs), *a8 = static_cast<const uint8_t *>(act);
+#define APEX_PE_ADD_SHORT(Vec)                                                                                          \
+  pe_add_short_kernel<Vec><<<grid, block, 0, stream>>>(r->v, r->state(), count, prio, o8, a8, ret, gacc, pr.obs, pr.act, \
+                                                       pr.ret, pr.gacc, vpr, lanes_log2, pr.obs_bytes, pr.act_bytes)
+    if (vb == 16) APEX_PE_ADD_SHORT(u32x4);
+    else if (vb == 4) APEX_PE_ADD_SHORT(uint32_t);
+    else APEX_PE_ADD_SHORT(uint8_t);
+#undef APEX_PE_ADD_SHORT
+  } else {
+    const int rc = add_payload_rows(pr, count, obs, act, ret, gacc, freed, stream);
+    if (rc != APEX_OK) return rc;
+    pe_add_kernel<<<dim3(blocks_for(count, 256)), dim3(256), 0, stream>>>(r->v, r->state(), count, prio);
+  }
   APEX_HIP(hipGetLastError());
   r->inserted += count;
   return APEX_OK;
@@ -438,6 +560,11 @@ int apex_pe_update_priorities(apex_pe_replay_t *r, uint64_t m, const uint64_t *k
   if (m >= 0xffffffffull) return APEX_ERR_TOO_LARGE;
   if (m == 0) return APEX_OK;
   hipStream_t stream = static_cast<hipStream_t>(hip_stream);
+  if (m <= 1024) {
+    pe_update_small_kernel<<<dim3(1), dim3((uint32_t)round_up(m, kWave)), 0, stream>>>(r->v, r->state(), (uint32_t)m, key, prio);
+    APEX_HIP(hipGetLastError());
+    return APEX_OK;
+  }
   const dim3 grid(blocks_for(m, 256)), block(256);
   pe_update_claim_kernel<<<grid, block, 0, stream>>>(r->v, r->state(), (uint32_t)m, key, r->claim());
   pe_update_apply_kernel<<<grid, block, 0, stream>>>(r->v, r->state(), (uint32_t)m, key, prio, r->claim());
@@ -480,7 +607,6 @@ int apex_pe_evict(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uin
     pe_flag_scan_kernel<<<dim3(scan_blocks), dim3(kPeScanThreads), 0, stream>>>(r->cand(), st, r->pos(), r->sums());
     pe_scan_blocks_kernel<<<dim3(1), dim3(kPeScanThreads), 0, stream>>>(r->sums(), scan_blocks, st);
     pe_remove_kernel<<<dim3(scan_blocks), dim3(kPeScanThreads), 0, stream>>>(r->v, st, r->cand(), r->pos(), r->sums());
-    pe_round_end_kernel<<<dim3(1), dim3(64), 0, stream>>>(st);
   }
   APEX_HIP(hipGetLastError());
   PeState h;

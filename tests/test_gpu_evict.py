@@ -62,6 +62,15 @@ def test_random_sequences_with_prioritized_eviction(P, C, ob, ab):
         assert o.update_priorities(keys, newp) == 0
         assert g.update_priorities(dev(keys), dev(newp)) == 0
         check(g, o)
+        # more than 1024 pairs: the two-pass update (batches of up to 1024 take one workgroup)
+        rnd = rng.integers(0, U64, 4 * 400, dtype=np.uint64)
+        rco, oo4 = o.sample(4, 400, 0.5, rnd, payload=False)
+        assert rco == 0
+        keys4 = np.concatenate([oo4["key"], oo4["key"][:200]])
+        newp4 = rng.lognormal(0, 1.5, len(keys4)).astype(F32)
+        assert o.update_priorities(keys4, newp4) == 0
+        assert g.update_priorities(dev(keys4), dev(newp4)) == 0
+        check(g, o)
         e = max(0, o.size - C)
         rnd = rng.integers(0, U64, (rounds, max(e, 1)), dtype=np.uint64)
         rco, eo = o.evict(rounds, rnd)
