@@ -148,6 +148,27 @@ def obs_rows(seed: int, first_key: int, count: int, obs_bytes: int):
     return np.ascontiguousarray(z.view(np.uint8).reshape(count, words * 8)[:, :obs_bytes])
 
 
+def frame_rows(seed: int, first_key: int, count: int, obs_bytes: int, flat_per_256: int = 205):
+    """Frame-like rows as a function of the key (a stand-in for game screens): the bytes of :func:`obs_rows`,
+    except that a 64-byte block whose first byte is below flat_per_256 (about 80 % of them) is flat, filled with
+    one of 8 background values chosen by its second byte.  obs_bytes must be a multiple of 64."""
+    assert obs_bytes % 64 == 0
+    rows = obs_rows(seed, first_key, count, obs_bytes).reshape(count, obs_bytes // 64, 64)
+    flat = rows[:, :, 0] < flat_per_256
+    value = (rows[:, :, 1] & 7) * 31
+    return np.where(flat[:, :, None], value[:, :, None], rows).astype(np.uint8).reshape(count, obs_bytes)
+
+
+def frame_rows_torch(seed: int, first_key: int, count: int, obs_bytes: int, device, flat_per_256: int = 205):
+    """Same bytes as :func:`frame_rows`, produced on ``device``."""
+    import torch
+    assert obs_bytes % 64 == 0
+    rows = obs_rows_torch(seed, first_key, count, obs_bytes, device).reshape(count, obs_bytes // 64, 64)
+    flat = rows[:, :, 0] < flat_per_256
+    value = (rows[:, :, 1] & 7) * 31
+    return torch.where(flat[:, :, None], value[:, :, None], rows).reshape(count, obs_bytes).contiguous()
+
+
 def _s64(v):
     return v - (1 << 64) if v >= (1 << 63) else v
 

@@ -355,3 +355,92 @@ def test_scale_stress_full_size():
                   check_obs_every=150)
     st = final_checks(p)
     assert st["n_clamped"] == p.o.n_clamped
+
+
+def test_atari_shape_full_size_through_the_observation_codec():
+    """The Atari-shaped memory (2,000,000 rows, 60 GB ring) storing frame-like rows through the block codec:
+    filled through the encoder, then the launch configurations the benchmark times on it - pipeline windows of
+    25 one-batch steps beside an add round, and calls of 16 batches - against the oracle (indices, keys, weights)
+    and against the rows' definition as a function of the key (decoded observations)."""
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["atari"]
+    stride = int(apex.lib.apex_codec_row_bytes(w.obs_bytes))
+    g = apex.Replay(w.capacity, w.max_slots, stride, w.act_bytes, w.alpha, w.eps, w.frac_bits)
+    o = oracle.Replay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes, w.alpha, w.eps, w.frac_bits, payload_slots=0)
+    key0 = 0
+    while key0 < w.capacity:
+        prio = synth.priorities("lognormal1", w.seed, key0 // w.add_count, w.add_count, tag="bulk")
+        rows = synth.frame_rows_torch(w.seed, key0, w.add_count, w.obs_bytes, "cuda:0")
+        assert g.add_payload_encoded(rows) == 0
+        assert g.add_publish(dev(prio)) == o.add(prio)
+        key0 += w.add_count
+    assert g.evict() == o.evict()
+    check_gpu_tree(g, o)
+
+    def check_rows(keys, obs_out, n_check=24):
+        keys = np.asarray(keys)
+        for i in np.linspace(0, len(keys) - 1, min(len(keys), n_check)).astype(int):
+            exp = synth.frame_rows(w.seed, int(keys[i]), 1, w.obs_bytes)[0]
+            assert np.array_equal(host(obs_out[i]), exp), (i, int(keys[i]))
+
+    d = synth.actor_round(w, 4242)
+    dd = {k2: dev(v) for k2, v in d.items()}
+    scratch = [torch.empty(w.add_count, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    ref_n = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                    w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+
+    # windows of 25 one-batch steps, each beside an add round that is encoded on the copy stream
+    depth, steps = 32, 25
+    pipe = apex.Pipeline(g, depth, 1, w.k)
+    assert pipe.set_codec(w.obs_bytes) == 0
+    for window in range(3):
+        rnd = np.stack([synth.uniforms(w.seed, 5000 + 100 * window + s, 1, w.k).reshape(-1) for s in range(steps)])
+        newp = np.stack([synth.priorities(w.td_dist, w.seed, 5000 + 100 * window + s, w.k) for s in range(steps)])
+        d_rnd, d_newp = dev(rnd), dev(newp)
+        rows = synth.frame_rows_torch(w.seed, key0, w.add_count, w.obs_bytes, "cuda:0")
+        assert pipe.fork() == 0
+        assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                              rows, dd["act"], *scratch) == 0
+        rc, first = pipe.steps(steps, w.beta, d_rnd, d_newp)
+        assert rc == 0
+        rc, first_key, ev = pipe.add_end(True)
+        assert pipe.join() == 0
+        res = []
+        for s in range(steps):
+            res.append(o.sample(1, w.k, w.beta, rnd[s], payload=False)[1])
+            o.update_priorities(res[-1]["key"], newp[s])
+        assert (rc, first_key) == o.add(ref_n[0].reshape(-1)) == (0, key0)
+        assert o.evict() == (0, ev)
+        key0 += w.add_count
+        torch.cuda.synchronize()
+        for s in range(steps):
+            o_, g_ = res[s], pipe.sets[(first + s) % depth]
+            assert np.array_equal(host(g_["slot"], np.uint32), o_["slot"])
+            assert np.array_equal(host(g_["key"], np.uint64), o_["key"])
+            assert_close(host(g_["weight"]), o_["weight"], "weight")
+            check_rows(o_["key"], g_["obs"], 6)
+        check_gpu_tree(g, o)
+    # the round added by the last window is sampled from as well: its rows went through the encoder on the copy stream
+    pipe.close()
+
+    # calls of 16 batches: fetched through the decoder on the copy stream
+    nb = 16
+    pipe = apex.Pipeline(g, 2, nb, w.k)
+    assert pipe.set_codec(w.obs_bytes) == 0
+    for call in range(2):
+        rnd = synth.uniforms(w.seed, 7000 + call, nb, w.k).reshape(-1)
+        newp = synth.priorities(w.td_dist, w.seed, 7000 + call, nb * w.k)
+        d_rnd, d_newp = dev(rnd[None]), dev(newp[None])
+        assert pipe.fork() == 0
+        rc, first = pipe.steps(1, w.beta, d_rnd, d_newp)
+        assert rc == 0 and pipe.join() == 0
+        oo = o.sample(nb, w.k, w.beta, rnd, payload=False)[1]
+        o.update_priorities(oo["key"], newp)
+        torch.cuda.synchronize()
+        g_ = pipe.sets[first]
+        assert np.array_equal(host(g_["slot"], np.uint32), oo["slot"])
+        assert np.array_equal(host(g_["key"], np.uint64), oo["key"])
+        assert_close(host(g_["weight"]), oo["weight"], "weight")
+        check_rows(oo["key"], g_["obs"], 48)
+    check_gpu_tree(g, o)
+    pipe.close()
