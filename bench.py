@@ -652,9 +652,10 @@ def codec_numbers(log):
             assert rep.add_payload_encoded(rows) == 0
             assert rep.add_publish(prio)[0] == 0
         torch.cuda.synchronize()
-        n_raw = rep.obs_view()[:w.add_count, :4].contiguous().view(torch.int32).to(torch.float64).mean().item()
         nb = raw // 64
-        used = 16 + (stride - 16 - 64 * nb - (nb + 15) // 16 * 16) + (nb - n_raw) + 64 * n_raw
+        blocks = rows.view(w.add_count, nb, 64)
+        n_raw = (blocks != blocks[:, :, :1]).any(dim=2).sum(dim=1).to(torch.float64).mean().item()
+        used = (stride - 64 * nb - (nb + 15) // 16 * 16) + (nb - n_raw) + 64 * n_raw
         tag = "flat_%d%%" % int(share * 100)
         res[tag] = {
             "bytes_per_row_that_carry_data": used, "ratio": raw / used,

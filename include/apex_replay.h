@@ -290,18 +290,19 @@ int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out /*host*/, void 
  * replay memory keeps observations compressed, the learner decompresses them as it fetches
  * batches; the paper uses PNG).  Here: a lossless codec that is undone at memory speed.  A row
  * of raw_bytes = 64 * nb bytes is cut into nb blocks of 64 bytes; a block whose bytes are all
- * equal (flat background) is kept as that byte, any other block as it is.  Encoded row,
+ * equal (flat background) is kept as that byte, any other block as it is, and every part has a
+ * fixed place, so that nothing has to be looked up before it can be fetched.  Encoded row,
  * integers little-endian:
- *   0            u32 n_raw = blocks kept as they are, then 12 zero bytes
- *   16           mask, bit b set iff block b is kept as it is: ceil(nb/64) u64 words, zero-padded
- *                to a multiple of 16 bytes (M bytes in all)
- *   16 + M       the byte of every other block, in block order (a region of nb bytes rounded up
- *                to a multiple of 16, V bytes; what lies beyond the last such byte is unspecified)
- *   16 + M + V   the blocks kept as they are, in block order (beyond the last: unspecified)
- * apex_codec_row_bytes = 16 + M + V + 64 * nb is what a row can take; a memory that stores
- * encoded rows is created with obs_bytes >= that (a multiple of 16).  0 if raw_bytes is 0, no
- * multiple of 64, or beyond 256 KB.  The ring's row stride stays fixed, so the codec saves HBM
- * traffic (an add writes, a gather reads only the bytes that carry data), not capacity.
+ *   0        mask, bit b set iff block b is kept as it is: ceil(nb/64) u64 words, zero-padded to a
+ *            multiple of 16 bytes (M bytes in all)
+ *   M        one byte per block: the byte of block b if it is not kept as it is (else unspecified);
+ *            nb bytes, rounded up to a multiple of 16 (V bytes)
+ *   M + V    the image of the row: bytes [64 b, 64 b + 64) hold block b if it is kept as it is (else
+ *            unspecified)
+ * apex_codec_row_bytes = M + V + 64 * nb is what a row takes; a memory that stores encoded rows
+ * is created with obs_bytes >= that (a multiple of 16).  0 if raw_bytes is 0 or no multiple of 64.
+ * The ring's row stride stays fixed, so the codec saves HBM traffic (an add writes, a fetch reads
+ * only the parts that carry data), not capacity.
  *
  * apex_replay_add_payload_encoded is apex_replay_add_payload with raw_obs [count, raw_bytes]
  * (device, 16-byte aligned) encoded on its way into the ring; publish with
@@ -401,9 +402,9 @@ int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out
  * way into the ring, and the obs buffers of the sets are [k, raw_bytes] and receive decoded rows (the
  * step launch decodes as it copies; steps of several batches fetch theirs through the decoder on the
  * copy stream).  raw_bytes == 0 switches back.  Only for pipelines whose steps are single launches (one
- * batch per step, at least three sets) or go to the copy stream (many batches per step), and rows of at
- * most 512 blocks (32 KB): APEX_ERR_INVALID_ARG otherwise, APEX_ERR_TOO_LARGE if the memory's rows are
- * too short.  Not while a round is open or a capture is running.
+ * batch per step, at least three sets) or go to the copy stream (many batches per step):
+ * APEX_ERR_INVALID_ARG otherwise, APEX_ERR_TOO_LARGE if the memory's rows are too short.  Not while a
+ * round is open or a capture is running.
  */
 int apex_pipeline_set_codec(apex_pipeline_t *p, uint32_t raw_bytes);
 

@@ -684,16 +684,21 @@ void oracle_pe_free_ring(const oracle_pe *r, uint32_t *out) { memcpy(out, r->fre
  * method is that the codec is lossless.  The reading taken here is a codec that a
  * GPU can undo at memory speed: a row of raw_bytes = 64 * nb bytes is cut into nb
  * blocks of 64 bytes; a block whose 64 bytes are all equal ("flat": the background
- * of a game screen) is stored as that one byte, any other block as it is.
+ * of a game screen) is stored as that one byte, any other block as it is, and
+ * every part of a block has a fixed place, so that nothing has to be looked up
+ * before it can be fetched.
  *
  * Encoded row (all offsets and sizes in bytes, integers little-endian):
- *   0               u32 n_raw = number of blocks that are not flat; 12 zero bytes
- *   16              mask: bit (b mod 64) of u64 word (b div 64) is 1 iff block b is
- *                   not flat; ceil(nb/64) words, zero-padded to a multiple of 16
- *   16 + M          the common byte of every flat block, in block order; a region of
- *                   nb bytes rounded up to a multiple of 16 (the rest is zero)
- *   16 + M + V      the 64 bytes of every block that is not flat, in block order
- * A row takes at most 16 + M + V + 64 * nb bytes; that is the stride of the store.
+ *   0           mask: bit (b mod 64) of u64 word (b div 64) is 1 iff block b is not
+ *               flat; ceil(nb/64) words, zero-padded to a multiple of 16 (M bytes)
+ *   M           one byte per block, in block order: the common byte of block b if it
+ *               is flat (else unspecified; the oracle writes 0); nb bytes, zero-padded
+ *               to a multiple of 16 (V bytes)
+ *   M + V       the image of the row: bytes [64 b, 64 b + 64) hold block b if it is not
+ *               flat (else unspecified; the oracle writes 0)
+ * A row takes M + V + 64 * nb bytes; that is the stride of the store.  What an encoder
+ * has to write and a decoder to read is the mask, the bytes of the flat blocks and
+ * the other blocks: M + (flat blocks) + 64 * (other blocks) bytes.
  */
 static uint64_t pad16(uint64_t v) { return (v + 15) / 16 * 16; }
 
@@ -701,7 +706,7 @@ uint64_t oracle_codec_row_bytes(uint32_t raw_bytes)
 {
   if (raw_bytes == 0 || raw_bytes % 64) return 0;
   const uint64_t nb = raw_bytes / 64;
-  return 16 + pad16(8 * ((nb + 63) / 64)) + pad16(nb) + 64 * nb;
+  return pad16(8 * ((nb + 63) / 64)) + pad16(nb) + 64 * nb;
 }
 
 /* enc: oracle_codec_row_bytes(raw_bytes) bytes, all written.  *used: the bytes of it that carry data. */
@@ -712,26 +717,22 @@ int oracle_codec_encode_row(const uint8_t *raw, uint32_t raw_bytes, uint8_t *enc
   const uint64_t nb = raw_bytes / 64;
   const uint64_t M = pad16(8 * ((nb + 63) / 64)), V = pad16(nb);
   memset(enc, 0, cap);
-  uint8_t *mask = enc + 16, *flat = enc + 16 + M, *blocks = enc + 16 + M + V;
-  uint32_t n_raw = 0, n_flat = 0;
+  uint8_t *mask = enc, *flat = enc + M, *image = enc + M + V;
+  uint64_t n_kept = 0;
   for (uint64_t b = 0; b < nb; ++b) {
     const uint8_t *blk = raw + 64 * b;
     int is_flat = 1;
     for (int j = 1; j < 64; ++j)
       if (blk[j] != blk[0]) is_flat = 0;
     if (is_flat) {
-      flat[n_flat++] = blk[0];
+      flat[b] = blk[0];
     } else {
       mask[b / 8] |= (uint8_t)(1u << (b % 8)); /* little-endian words: bit b of the bit string */
-      memcpy(blocks + 64 * (uint64_t)n_raw, blk, 64);
-      ++n_raw;
+      memcpy(image + 64 * b, blk, 64);
+      ++n_kept;
     }
   }
-  enc[0] = (uint8_t)n_raw;
-  enc[1] = (uint8_t)(n_raw >> 8);
-  enc[2] = (uint8_t)(n_raw >> 16);
-  enc[3] = (uint8_t)(n_raw >> 24);
-  if (used) *used = 16 + M + n_flat + 64 * (uint64_t)n_raw;
+  if (used) *used = M + (nb - n_kept) + 64 * n_kept;
   return ORACLE_OK;
 }
 
@@ -741,16 +742,12 @@ int oracle_codec_decode_row(const uint8_t *enc, uint32_t raw_bytes, uint8_t *raw
   if (!cap) return ORACLE_ERR_INVALID_ARG;
   const uint64_t nb = raw_bytes / 64;
   const uint64_t M = pad16(8 * ((nb + 63) / 64)), V = pad16(nb);
-  const uint8_t *mask = enc + 16, *flat = enc + 16 + M, *blocks = enc + 16 + M + V;
-  uint64_t n_raw = 0, n_flat = 0;
+  const uint8_t *mask = enc, *flat = enc + M, *image = enc + M + V;
   for (uint64_t b = 0; b < nb; ++b) {
-    if (mask[b / 8] >> (b % 8) & 1) {
-      memcpy(raw_out + 64 * b, blocks + 64 * n_raw, 64);
-      ++n_raw;
-    } else {
-      memset(raw_out + 64 * b, flat[n_flat], 64);
-      ++n_flat;
-    }
+    if (mask[b / 8] >> (b % 8) & 1)
+      memcpy(raw_out + 64 * b, image + 64 * b, 64);
+    else
+      memset(raw_out + 64 * b, flat[b], 64);
   }
   return ORACLE_OK;
 }

@@ -175,13 +175,14 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // --------------------------------------------------------------------------------------------
 // Observations stored through the block codec (Section 4.1: observations are kept compressed in the
-// replay memory): shape of an encoded row, and how a wave fetches 16-byte pieces of the raw row
-// out of it.  The format is described in codec.inc.hpp.
+// replay memory): shape of an encoded row, and how a lane fetches a 16-byte piece of the raw row
+// out of it.  The format is described in codec.inc.hpp: every part has a fixed place, so the three
+// loads below depend on nothing but the row's address.
 // --------------------------------------------------------------------------------------------
 struct CodecShape {
   uint32_t raw_bytes, nb, mask_words;  // raw_bytes == 0: no codec
-  uint32_t flat_off, raw_off;          // 16 + M, 16 + M + V
-  uint64_t stride;                     // 16 + M + V + 64 nb
+  uint32_t flat_off, image_off;        // M, M + V
+  uint64_t stride;                     // M + V + 64 nb
 };
 
 __host__ __device__ inline CodecShape codec_shape(uint32_t raw_bytes)
@@ -191,121 +192,69 @@ __host__ __device__ inline CodecShape codec_shape(uint32_t raw_bytes)
   c.nb = raw_bytes / 64;
   c.mask_words = (c.nb + 63) / 64;
   const uint32_t M = (8 * c.mask_words + 15) / 16 * 16, V = (c.nb + 15) / 16 * 16;
-  c.flat_off = 16 + M;
-  c.raw_off = 16 + M + V;
-  c.stride = (uint64_t)c.raw_off + 64ull * c.nb;
+  c.flat_off = M;
+  c.image_off = M + V;
+  c.stride = (uint64_t)c.image_off + 64ull * c.nb;
   return c;
 }
 
-// An encoded row of at most 512 blocks, opened by a wave: its mask (at most eight words, the same for every
-// lane) and, per word, the number of blocks kept as they are in the words before it.
-struct CodecRow {
-  const uint8_t *e;
-  uint64_t m[8];
-  uint32_t before[8];
+// What a lane has asked for of piece v (16 bytes) of the raw row: the piece as the image holds it, its
+// block's byte, and the word of the mask that says which of the two counts.
+struct CodecFetched {
+  u32x4 data;
+  uint64_t word;
+  uint32_t byte, bit;
 };
 
-__device__ __forceinline__ CodecRow codec_open_row(const uint8_t *e, const CodecShape &c)
+// All three at once (for paths bound by latency: nothing waits for the mask).  v < raw_bytes / 16.
+__device__ __forceinline__ CodecFetched codec_fetch_all(const uint8_t *e, const CodecShape &c, uint32_t v)
 {
-  CodecRow r;
-  r.e = e;
-  const uint64_t *mw = reinterpret_cast<const uint64_t *>(e + 16);
-  uint32_t run = 0;
-#pragma unroll
-  for (int w = 0; w < 8; ++w) {
-    r.m[w] = (uint32_t)w < c.mask_words ? mw[w] : 0;
-    r.before[w] = run;
-    run += __popcll(r.m[w]);
-  }
-  return r;
+  CodecFetched f;
+  const uint32_t b = v / 4;
+  f.data = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(e + c.image_off) + v);
+  f.byte = e[c.flat_off + b];
+  f.word = reinterpret_cast<const uint64_t *>(e)[b / 64];
+  f.bit = b & 63;
+  return f;
 }
 
-// 16-byte piece v of the raw row, in two halves so that a lane can have several pieces on their way before
-// it looks at the first: codec_fetch issues the load (of the piece itself, or of its block's byte),
-// codec_piece turns what arrived into the 16 bytes.  The 64 lanes of the calling wave (all of them call)
-// pass 64 consecutive values of v that start at a multiple of 64: their 16 blocks lie within one word of the
-// mask.  Lanes whose v lies beyond the row fetch the wave's first piece instead (and drop it).
-struct CodecFetched {
-  u32x4 data;    // kept block: the piece
-  uint32_t byte; // flat block: its byte
-  bool kept;
-};
-
-__device__ __forceinline__ CodecFetched codec_fetch(const CodecRow &r, const CodecShape &c, uint32_t v)
+// The same for a whole wave whose 64 lanes hold 64 consecutive pieces starting at a multiple of 64 (16
+// blocks: one word of the mask, 16 consecutive block bytes): the word and the bytes come through the
+// scalar data cache (read only), which keeps them out of the queue of the vector memory pipeline, where
+// they would wait behind the row loads of the same compute unit.  e must be 16-byte aligned.
+__device__ __forceinline__ void codec_fetch_wave_scalars(const uint8_t *e, const CodecShape &c, uint32_t v_first,
+                                                         uint64_t *word, u32x4 *bytes)
 {
-  const uint32_t nvec = c.raw_bytes / 16;
-  const uint32_t v_first = __builtin_amdgcn_readfirstlane(v);
-  if (v >= nvec) v = v_first < nvec ? v_first : 0;
-  const uint32_t w = __builtin_amdgcn_readfirstlane(v >> 8);
-  uint64_t word = 0;
-  uint32_t base = 0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    if ((uint32_t)i == w) word = r.m[i], base = r.before[i];
-  const uint32_t b = v / 4, bit = b & 63;
-  const uint32_t rank = base + __popcll(word & ((1ull << bit) - 1));
-  CodecFetched f;
-  f.kept = word >> bit & 1;
-  f.byte = 0;
-  f.data = u32x4{0, 0, 0, 0};
-  if (f.kept)
-    f.data = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(r.e + c.raw_off + 64 * rank) + (v & 3));
-  else
-    f.byte = r.e[c.flat_off + (b - rank)];
-  return f;
+  const uint64_t pe = (uint64_t)(uintptr_t)e;
+  // (the builtin returns a signed int: without the casts the low half would be sign-extended)
+  const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(pe >> 32));
+  const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)pe);
+  const uint64_t base = ((uint64_t)hi << 32) | (uint64_t)lo;
+  const uint32_t vf = (uint32_t)__builtin_amdgcn_readfirstlane((int)v_first);
+  const uint64_t p_word = base + 8ull * (vf >> 8);
+  const uint64_t p_bytes = base + c.flat_off + vf / 4;
+  uint64_t w;
+  u32x4 b;
+  asm volatile("s_load_dwordx2 %0, %2, 0x0\n\ts_load_dwordx4 %1, %3, 0x0\n\ts_waitcnt lgkmcnt(0)"
+               : "=&s"(w), "=&s"(b)
+               : "s"(p_word), "s"(p_bytes)
+               : "memory");
+  *word = w;
+  *bytes = b;
+}
+
+// The byte of the block of lane `lane`'s piece out of the 16 bytes fetched above.
+__device__ __forceinline__ uint32_t codec_wave_byte(const u32x4 &bytes, uint32_t lane)
+{
+  const uint32_t i = lane / 4;  // block within the wave
+  const uint32_t dw = i < 4 ? bytes.x : i < 8 ? bytes.y : i < 12 ? bytes.z : bytes.w;
+  return (dw >> (8 * (i & 3))) & 0xffu;
 }
 
 __device__ __forceinline__ u32x4 codec_piece(const CodecFetched &f)
 {
   const uint32_t x = f.byte * 0x01010101u;
-  return f.kept ? f.data : u32x4{x, x, x, x};
-}
-
-// The same with a whole block per lane (a flat block then costs its lane one load instead of four): the 64
-// lanes of the calling wave (all of them call) pass 64 consecutive block numbers that start at a multiple of
-// 64.  Lanes whose block lies beyond the row fetch nothing.
-struct CodecBlock {
-  u32x4 q[4];
-  uint32_t byte;
-  bool kept, valid;
-};
-
-__device__ __forceinline__ CodecBlock codec_fetch_block(const CodecRow &r, const CodecShape &c, uint32_t b)
-{
-  const uint32_t w = __builtin_amdgcn_readfirstlane(b >> 6);
-  uint64_t word = 0;
-  uint32_t base = 0;
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-    if ((uint32_t)i == w) word = r.m[i], base = r.before[i];
-  const uint32_t bit = b & 63;
-  const uint32_t rank = base + __popcll(word & ((1ull << bit) - 1));
-  CodecBlock f;
-  f.valid = b < c.nb;
-  f.kept = word >> bit & 1;
-  f.byte = 0;
-#pragma unroll
-  for (int q = 0; q < 4; ++q) f.q[q] = u32x4{0, 0, 0, 0};
-  if (f.valid) {
-    if (f.kept) {
-      const u32x4 *p = reinterpret_cast<const u32x4 *>(r.e + c.raw_off + 64 * rank);
-#pragma unroll
-      for (int q = 0; q < 4; ++q) f.q[q] = __builtin_nontemporal_load(p + q);
-    } else {
-      f.byte = r.e[c.flat_off + (b - rank)];
-    }
-  }
-  return f;
-}
-
-// Writes the block to its place in the raw row `out`.
-__device__ __forceinline__ void codec_store_block(const CodecBlock &f, uint8_t *out, uint32_t b)
-{
-  if (!f.valid) return;
-  const uint32_t x = f.byte * 0x01010101u;
-  u32x4 *o = reinterpret_cast<u32x4 *>(out + 64ull * b);
-#pragma unroll
-  for (int q = 0; q < 4; ++q) __builtin_nontemporal_store(f.kept ? f.q[q] : u32x4{x, x, x, x}, o + q);
+  return (f.word >> f.bit & 1) ? f.data : u32x4{x, x, x, x};
 }
 
 // A learner batch (m <= blockDim) handled by one workgroup: duplicates are resolved in an LDS hash
@@ -1124,8 +1073,8 @@ struct StepArgs {
   AddRoundArgs add;
   AddLeavesArgs leaves;
   // Rows stored through the block codec (kCodec launches only): row_bytes is then the stride of the
-  // encoded rows in src, the rows written to dst are codec.raw_bytes long, vecs_per_row counts their
-  // 16-byte pieces, and rows have at most 512 blocks.
+  // encoded rows in src, the rows written to dst are codec.raw_bytes long, and vecs_per_row counts their
+  // 16-byte pieces.
   CodecShape codec;
 };
 
@@ -1298,16 +1247,28 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   const Vec *s = reinterpret_cast<const Vec *>(a.src + (uint64_t)my_slot * a.row_bytes);
   Vec *d = reinterpret_cast<Vec *>(a.dst + (uint64_t)row * (kCodec ? (uint64_t)a.codec.raw_bytes : a.row_bytes));
   Vec tmp[kUnroll];
-  CodecRow enc;
-  CodecBlock blk;
-  if constexpr (kCodec) {  // a block per lane; rows of at most 512 blocks take at most two passes
-    enc = codec_open_row(reinterpret_cast<const uint8_t *>(s), a.codec);
-    blk = codec_fetch_block(enc, a.codec, tid - first);
-  } else {
+  CodecFetched fetched[kCodec ? kUnroll : 1] = {};
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t v = tid - first + u * copiers;
+    if constexpr (kCodec) {  // the pieces as the image holds them; mask and block bytes follow below
+      if (v < a.vecs_per_row)
+        fetched[u].data = __builtin_nontemporal_load(
+            reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(s) + a.codec.image_off) + v);
+    } else {
+      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+    }
+  }
+  if constexpr (kCodec) {
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const uint32_t v = tid - first + u * copiers;
-      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+      const uint32_t v = tid - first + u * copiers, v_first = v - lane;  // the wave's 64 pieces start at v_first
+      if (v_first < a.vecs_per_row) {  // the same for all lanes of the wave
+        u32x4 bytes;
+        codec_fetch_wave_scalars(reinterpret_cast<const uint8_t *>(s), a.codec, v_first, &fetched[u].word, &bytes);
+        fetched[u].byte = codec_wave_byte(bytes, lane);
+        fetched[u].bit = (v / 4) & 63;
+      }
     }
   }
 
@@ -1328,24 +1289,30 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   }
 
   if constexpr (kCodec) {
-    codec_store_block(blk, reinterpret_cast<uint8_t *>(d), tid - first);
-    for (uint32_t b0 = copiers; b0 < a.codec.nb; b0 += copiers) {
-      blk = codec_fetch_block(enc, a.codec, b0 + tid - first);
-      codec_store_block(blk, reinterpret_cast<uint8_t *>(d), b0 + tid - first);
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const u32x4 piece = codec_piece(fetched[u]);
+      __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
     }
-  } else {
+  }
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = tid - first + u * copiers;
     if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
   }
-  }
   // rows longer than one pass of the workgroup (more than 32 KB, or narrow vectors)
-  for (uint32_t base = copiers * kUnroll; !kCodec && base < a.vecs_per_row; base += copiers * kUnroll) {
+  for (uint32_t base = copiers * kUnroll; base < a.vecs_per_row; base += copiers * kUnroll) {
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint32_t v = base + tid - first + u * copiers;
-      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+      if constexpr (kCodec) {
+        if (v < a.vecs_per_row) {
+          const u32x4 piece = codec_piece(codec_fetch_all(reinterpret_cast<const uint8_t *>(s), a.codec, v));
+          __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
+        }
+      } else {
+        if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+      }
     }
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {

@@ -200,7 +200,7 @@ int apex_pipeline_set_codec(apex_pipeline_t *p, uint32_t raw_bytes)
     return APEX_OK;
   }
   const size_t stride = apex_codec_row_bytes(raw_bytes);
-  if (!stride || raw_bytes / 64 > 512 || (p->r->cfg.obs_bytes & 15)) return APEX_ERR_INVALID_ARG;
+  if (!stride || (p->r->cfg.obs_bytes & 15)) return APEX_ERR_INVALID_ARG;
   if (stride > p->r->cfg.obs_bytes) return APEX_ERR_TOO_LARGE;
   if (!p->wide && !fused_steps_fit(p->r, p->nb, p->k, p->depth, p->sets.data())) return APEX_ERR_INVALID_ARG;
   for (const apex_batch_buffers_t &b : p->sets)

@@ -38,16 +38,16 @@ def test_hand_worked_row():
     assert enc.shape == (1, int(g["stride"][0])) and oracle.codec_row_bytes(int(g["raw_bytes"][0])) == int(g["stride"][0])
     assert int(used[0]) == int(g["used"][0])
     hexs = lambda b: [("%02x" % x) for x in b]
-    assert hexs(enc[0, 0:16]) == g["header"]
-    assert hexs(enc[0, 16:32]) == g["mask"]
-    assert hexs(enc[0, 32:48]) == g["flat"]
-    assert np.array_equal(enc[0, 48:112], row[64:128])
-    assert np.array_equal(enc[0, 112:176], row[192:256])
+    assert hexs(enc[0, 0:16]) == g["mask"]
+    assert hexs(enc[0, 16:32]) == g["flat"]
+    image = enc[0, 32:]
+    assert np.array_equal(image[64:128], row[64:128]) and np.array_equal(image[192:256], row[192:256])
+    assert not image[0:64].any() and not image[128:192].any()
     assert np.array_equal(oracle.codec_decode(enc, 256)[0], row)
 
 
-@pytest.mark.parametrize("raw_bytes,stride", [(64, 112), (4096, 16 + 16 + 64 + 4096), (4160, 16 + 16 + 80 + 4160),
-                                              (28224, 16 + 64 + 448 + 28224), (256, 304)])
+@pytest.mark.parametrize("raw_bytes,stride", [(64, 96), (4096, 16 + 64 + 4096), (4160, 16 + 80 + 4160),
+                                              (28224, 64 + 448 + 28224), (256, 288)])
 def test_stride_closed_form(raw_bytes, stride):
     assert oracle.codec_row_bytes(raw_bytes) == stride
 
@@ -73,32 +73,32 @@ def test_round_trip_and_second_derivation(raw_bytes, flat_share):
     rows = frame_like(rng, 6, raw_bytes, flat_share)
     enc, used = oracle.codec_encode(rows)
     assert np.array_equal(oracle.codec_decode(enc, raw_bytes), rows)        # lossless
-    # the same header, mask and counts from array operations
+    # the same mask, bytes and image from array operations
     nb = raw_bytes // 64
     blocks = rows.reshape(6, nb, 64)
     not_flat = (blocks != blocks[:, :, :1]).any(axis=2)
-    n_raw = not_flat.sum(axis=1)
-    assert np.array_equal(enc[:, :4].copy().view("<u4")[:, 0], n_raw)
-    assert not enc[:, 4:16].any()
+    n_kept = not_flat.sum(axis=1)
     M = (8 * ((nb + 63) // 64) + 15) // 16 * 16
     V = (nb + 15) // 16 * 16
-    bits = np.unpackbits(enc[:, 16:16 + M], axis=1, bitorder="little")[:, :nb]
-    assert np.array_equal(bits.astype(bool), not_flat)
-    assert not np.unpackbits(enc[:, 16:16 + M], axis=1, bitorder="little")[:, nb:].any()
-    assert np.array_equal(used, 16 + M + (nb - n_raw) + 64 * n_raw)
-    for i in range(6):
-        assert np.array_equal(enc[i, 16 + M:16 + M + nb - n_raw[i]], blocks[i, ~not_flat[i], 0])
-        assert np.array_equal(enc[i, 16 + M + V:16 + M + V + 64 * n_raw[i]].reshape(-1, 64), blocks[i, not_flat[i]])
+    bits = np.unpackbits(enc[:, :M], axis=1, bitorder="little")
+    assert np.array_equal(bits[:, :nb].astype(bool), not_flat) and not bits[:, nb:].any()
+    assert np.array_equal(used, M + (nb - n_kept) + 64 * n_kept)
+    flat_bytes = enc[:, M:M + nb]
+    assert np.array_equal(flat_bytes[~not_flat], blocks[~not_flat][:, 0])
+    image = enc[:, M + V:].reshape(6, nb, 64)
+    assert np.array_equal(image[not_flat], blocks[not_flat])
 
 
 def test_every_part_of_the_encoding_matters():
-    """A changed mask bit, flat value or stored block changes what is decoded."""
+    """A changed mask bit, byte of a flat block or stored block changes what is decoded."""
     rng = np.random.default_rng(5)
     rows = frame_like(rng, 1, 4160, 0.5)
     enc, _ = oracle.codec_encode(rows)
-    nb = 65
+    blocks = rows.reshape(65, 64)
+    not_flat = (blocks != blocks[:, :1]).any(axis=1)
+    first_flat, first_kept = int(np.argmin(not_flat)), int(np.argmax(not_flat))
     M, V = 16, 80
-    for off in (16, 16 + M, 16 + M + V + 70):
+    for off in (0, M + first_flat, M + V + 64 * first_kept + 5):
         bad = enc.copy()
         bad[0, off] ^= 1
         assert not np.array_equal(oracle.codec_decode(bad, 4160), rows)
