@@ -309,9 +309,10 @@ int apex_replay_stats(apex_replay_t *r, apex_replay_stats_t *out /*host*/, void 
  * apex_replay_add_publish.  apex_replay_gather_decoded is apex_replay_gather with obs_out
  * [count, raw_bytes] (16-byte aligned, may be NULL) decoded on its way out.  Both:
  * APEX_ERR_INVALID_ARG for a raw_bytes the codec refuses or misaligned rows, APEX_ERR_TOO_LARGE
- * if the memory's rows are too short for raw_bytes.  The fused learner step of the pipeline
- * copies rows as they are stored; a caller of the codec draws with apex_replay_sample_begin and
- * apex_replay_sample_finish (obs_out NULL) and fetches with apex_replay_gather_decoded.
+ * if the memory's rows are too short for raw_bytes.  With the plain calls a caller of the
+ * codec draws with apex_replay_sample_begin and apex_replay_sample_finish (obs_out NULL) and
+ * fetches with apex_replay_gather_decoded; the pipeline does both itself after
+ * apex_pipeline_set_codec.
  * ---------------------------------------------------------------------------------------- */
 size_t apex_codec_row_bytes(uint32_t raw_bytes);
 int apex_replay_add_payload_encoded(apex_replay_t *r, uint64_t count, const void *raw_obs, uint32_t raw_bytes,
