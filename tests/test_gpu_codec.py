@@ -133,6 +133,76 @@ def test_pipeline_with_the_codec(raw_bytes, flat_share, nb, k, depth):
 
 
 @pytest.mark.gpu
+@pytest.mark.parametrize("raw_bytes,nb,k,depth", [(4160, 1, 80, 3), (28224, 1, 64, 3), (4160, 4, 512, 2)])
+def test_pipeline_graph_replays_with_the_codec(raw_bytes, nb, k, depth):
+    """One cycle with the codec on (an add round encoded on the copy stream beside learner steps that decode
+    while they gather, then eviction) recorded as a HIP graph and replayed; every replay against the oracle,
+    with eager calls on the same memory in between."""
+    from paper_1803_00933_amd import apex, synth
+    rng = np.random.default_rng(raw_bytes + nb)
+    stride = oracle.codec_row_bytes(raw_bytes)
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=stride, capacity=2500, max_slots=4096, streams=6, chunk=30, k=k)
+    g = apex.Replay(w.capacity, w.max_slots, stride, w.act_bytes)
+    o = oracle.Replay(w.capacity, w.max_slots, raw_bytes, w.act_bytes)
+
+    def eager_add(cnt):
+        raw = frame_like(rng, cnt, raw_bytes, 0.7)
+        act = rng.integers(0, 256, (cnt, w.act_bytes), dtype=np.uint8)
+        ret, gacc = rng.standard_normal(cnt).astype(F32), rng.random(cnt).astype(F32)
+        prio = rng.lognormal(0, 1, cnt).astype(F32)
+        assert g.add_payload_encoded(dev(raw), dev(act), dev(ret), dev(gacc)) == 0
+        assert g.add_publish(dev(prio)) == o.add(prio, raw, act, ret, gacc)
+
+    eager_add(w.capacity)
+    pipe = apex.Pipeline(g, depth, nb, w.k)
+    assert pipe.set_codec(raw_bytes) == 0
+    n_steps = depth - 1 if nb > 1 else 5
+    rnd = rng.integers(0, U64, (n_steps, nb * w.k), dtype=np.uint64)
+    newp = rng.lognormal(0, 1, (n_steps, nb * w.k)).astype(F32)
+    d_rnd, d_newp = dev(rnd), dev(newp)
+    n_rows = w.streams * w.chunk
+    scratch = [torch.empty(n_rows, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    d = synth.actor_round(w, 0)
+    d["obs"] = frame_like(rng, n_rows, raw_bytes, 0.7)
+    dd = {k2: dev(v) for k2, v in d.items()}
+    torch.cuda.synchronize()
+
+    def oracle_cycle():
+        res = []
+        for s in range(n_steps):
+            res.append(o.sample(nb, w.k, 0.4, rnd[s])[1])
+            o.update_priorities(res[-1]["key"], newp[s])
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+        assert o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1), ref[2].reshape(-1))[0] == 0
+        assert o.evict() == (0, n_rows)
+        return res
+
+    assert pipe.capture_begin() == 0
+    assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                          dd["obs"], dd["act"], *scratch) == 0
+    assert pipe.steps(n_steps, 0.4, d_rnd, d_newp)[0] == 0
+    rc, _, ev = pipe.add_end(True)
+    assert (rc, ev) == (0, n_rows)
+    assert pipe.capture_end() == 0
+    first_kept = max(0, n_steps - depth)
+    for replay in range(3):
+        assert pipe.fork() == 0
+        assert pipe.replay(1) == 0
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        res = oracle_cycle()
+        for s in range(first_kept, n_steps):
+            assert_sample_equal(pipe.sets[s % depth], res[s])
+        assert g.resync() == 0
+        check_gpu_tree(g, o)
+        if replay == 0:                       # eager calls between replays, on the same memory
+            eager_add(30)
+            assert g.evict() == o.evict()
+    pipe.close()
+
+
+@pytest.mark.gpu
 def test_codec_status_codes():
     from paper_1803_00933_amd import apex
     g = apex.Replay(100, 128, 288, 4)                      # rows for 256 raw bytes
