@@ -633,9 +633,11 @@ bool fused_steps_fit(const apex_replay *r, uint32_t num_batches, uint32_t k, uin
   return true;
 }
 
-void launch_step(const StepArgs &a, uint32_t vector_bytes, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds,
-                 hipStream_t stream, int rider = kNoRider)
+void launch_step(const StepArgs &args, uint32_t vector_bytes, uint32_t n_top, uint32_t wgs, uint32_t threads,
+                 size_t lds, hipStream_t stream, int rider = kNoRider)
 {
+  StepArgs a = args;
+  a.next_top = a.next.tv.level[a.next.tv.nlev - 1];
   if (a.codec.raw_bytes && a.slot) return launch_step_codec(a, n_top, wgs, threads, lds, rider, stream);
   if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, wgs, threads, lds, rider, stream);
   else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, wgs, threads, lds, rider, stream);

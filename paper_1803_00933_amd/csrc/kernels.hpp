@@ -902,13 +902,18 @@ struct Drawn {
 // One wavefront walks from the top level (exclusive prefix sums `pre` in LDS) down to the slots whose
 // cumulative-mass intervals hold x[0 .. kSamples): the loads of all samples go out together on every
 // level, so that several draws take the time of one.  Called by all 64 lanes.
-template <int kSamples>
+// between(): called once, when the loads of the first level below the top are on their way (right away if
+// the tree has no such level): arithmetic that does not depend on the walk costs nothing there.
+template <int kSamples, typename Between>
 __device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t *pre, uint64_t total,
-                                             const uint64_t (&x_in)[kSamples], Drawn (&out)[kSamples])
+                                             const uint64_t (&x_in)[kSamples], Drawn (&out)[kSamples],
+                                             Between between)
 {
   const int lane = lane_id();
   const uint32_t n_top = tv.n_top;
   const uint32_t stride = (n_top + kWave - 1) / kWave;
+  // the two lowest levels' addresses are at fixed places of the arguments: fetched with them, not on the way down
+  const uint64_t *const low0 = tv.level[0], *const low1 = tv.level[1];
   uint64_t x[kSamples], idx[kSamples], mass[kSamples];
 #pragma unroll
   for (int s = 0; s < kSamples; ++s) {
@@ -928,10 +933,16 @@ __device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t 
   }
   // lower levels: 64 children per step, prefix sum across the wave, first child whose
   // running sum exceeds the remainder
+  bool called = false;
   for (int l = (int)tv.nlev - 2; l >= 0; --l) {
+    const uint64_t *const lv = l == 0 ? low0 : l == 1 ? low1 : tv.level[l];
     uint64_t c[kSamples];
 #pragma unroll
-    for (int s = 0; s < kSamples; ++s) c[s] = tv.level[l][idx[s] * kFanout + lane];
+    for (int s = 0; s < kSamples; ++s) c[s] = lv[idx[s] * kFanout + lane];
+    if (!called) {
+      between();
+      called = true;
+    }
 #pragma unroll
     for (int s = 0; s < kSamples; ++s) {
       const uint64_t sc = wave_inclusive_scan(c[s]);
@@ -944,12 +955,28 @@ __device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t 
       mass[s] = c_sel;
     }
   }
+  if (!called) between();
 #pragma unroll
   for (int s = 0; s < kSamples; ++s) out[s] = Drawn{idx[s], mass[s]};
 }
 
+template <int kSamples>
+__device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t *pre, uint64_t total,
+                                             const uint64_t (&x_in)[kSamples], Drawn (&out)[kSamples])
+{
+  wave_descend<kSamples>(tv, pre, total, x_in, out, [] {});
+}
+
+// The ring key of a drawn slot: head + its distance from the head's slot around the ring.
+// head_slot = head % P.
+__device__ __forceinline__ uint64_t ring_key(uint64_t slot, uint64_t head, uint64_t head_slot, uint64_t P)
+{
+  return head + (slot >= head_slot ? slot - head_slot : slot + P - head_slot);
+}
+
 // What a draw writes for sample o (called by all 64 lanes of the wave that drew it).
-__device__ __forceinline__ void write_drawn(const SampleArgs &a, uint64_t o, Drawn d, uint64_t head)
+__device__ __forceinline__ void write_drawn(const SampleArgs &a, uint64_t o, Drawn d, uint64_t head,
+                                            uint64_t head_slot)
 {
   const TreeView &tv = a.tv;
   const int lane = lane_id();
@@ -957,7 +984,7 @@ __device__ __forceinline__ void write_drawn(const SampleArgs &a, uint64_t o, Dra
   if (lane == 0) {
     a.slot_out[o] = (uint32_t)slot;
     if (a.key_out)
-      a.key_out[o] = a.gen ? ((uint64_t)a.gen[slot] << 32) | slot : head + ((slot + tv.P - head % tv.P) % tv.P);
+      a.key_out[o] = a.gen ? ((uint64_t)a.gen[slot] << 32) | slot : ring_key(slot, head, head_slot, tv.P);
     a.mass[o] = d.mass;
     if (a.ret_out) a.ret_out[o] = a.ret[slot];
     if (a.gacc_out) a.gacc_out[o] = a.gacc[slot];
@@ -997,9 +1024,10 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
     const uint64_t x = (uint64_t)j * w + __umul64hi(u, w);  // point inside stratum j
     const uint64_t xs[1] = {x};
     Drawn drs[1];
-    wave_descend<1>(tv, pre, total, xs, drs);
+    uint64_t head_slot = 0;
+    wave_descend<1>(tv, pre, total, xs, drs, [&] { head_slot = head % tv.P; });
     const Drawn dr = drs[0];
-    write_drawn(a, o, dr, head);
+    write_drawn(a, o, dr, head, head_slot);
   }
 }
 
@@ -1062,6 +1090,7 @@ struct StepArgs {
   TreeView wr;            // the copy that is written
   WeightArgs wa;          // weights of batch i
   SampleArgs next;        // draw of batch i+1 from next.tv, the copy that is read; next.rnd == null: none
+  const uint64_t *next_top;  // the top level of next.tv (its address at a fixed place of the arguments)
   const float *next_prio; // [k] new priorities of batch i+1 (null: none) ...
   uint64_t *next_dq;      // ... the changes they bring, kept for the next launch
   QuantParams qp;
@@ -1085,6 +1114,11 @@ typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 // The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier: the
 // top level (eight consecutive nodes per lane and pass of 512, 16-byte loads) into registers, its prefix
 // sums into LDS, two walks down, outputs, and the change that the sample's new priority brings.
+// The wave's path through memory is the launch's critical path, so it holds exactly one round trip per
+// tree level: the top-level loads are the first instructions to go out, the sample's random number, new
+// priority and the ring's head follow them and are used after them (a wave's loads return in the order of
+// issue), and the arithmetic that does not depend on the walk (priority -> mass, head % P) runs while the
+// first row of children is on its way.
 // LDS: round_up(n_top, 64) words of 8 bytes.
 template <int kTopChunk>
 __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *pre)
@@ -1094,16 +1128,13 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
   const uint32_t n_top_pad = (n_top + kFanout - 1) & ~(kFanout - 1);  // the level is zero-padded to this in memory
   const bool second = a.next_prio && row + 1 < a.next.k;              // a next sample to compare slots with
   __builtin_amdgcn_s_setprio(2);
-
-  const uint64_t un0 = a.next.rnd[row], un1 = second ? a.next.rnd[row + 1] : 0;
-  const float prio_next = a.next_prio ? a.next_prio[row] : 0.0f;
-  const uint64_t head = a.next.st->head;
-  const uint64_t *top = rd.level[rd.nlev - 1];
+  const uint64_t *top = a.next_top;
+  constexpr uint32_t kChunkNodes = kTopChunk * 8 * kWave;
 
   // ---- top level: exclusive prefix sums -> LDS; the loads of kTopChunk passes go out together
+  uint64_t v[kTopChunk][8];
   uint64_t carry = 0;
-  for (uint32_t c0 = 0; c0 < n_top_pad; c0 += kTopChunk * 8 * kWave) {
-    uint64_t v[kTopChunk][8];
+  auto issue = [&](uint32_t c0) {
 #pragma unroll
     for (int p = 0; p < kTopChunk; ++p) {
       const uint32_t i0 = c0 + p * 8 * kWave + 8 * lane;
@@ -1117,6 +1148,8 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
         }
       }
     }
+  };
+  auto consume = [&](uint32_t c0) {
 #pragma unroll
     for (int p = 0; p < kTopChunk; ++p) {
       const uint32_t i0 = c0 + p * 8 * kWave + 8 * lane;
@@ -1134,25 +1167,40 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
       }
       carry += __shfl(incl, kWave - 1, kWave);
     }
+  };
+  issue(0);
+  // no load below is conditional: a branch around a load would make the wave wait for it there
+  const uint64_t un0 = a.next.rnd[row], un1 = a.next.rnd[second ? row + 1 : row];
+  const float prio_next = *(a.next_prio ? a.next_prio + row : reinterpret_cast<const float *>(a.next.rnd + row));
+  const uint64_t head = a.next.st->head;
+  consume(0);
+  for (uint32_t c0 = kChunkNodes; c0 < n_top_pad; c0 += kChunkNodes) {
+    issue(c0);
+    consume(c0);
   }
   const uint64_t total = carry;
-  bool clamped = false;
-  const uint64_t q_next = a.next_prio ? quantise_priority(prio_next, a.qp, &clamped) : 0;
   wave_lds_sync();
 
   const uint64_t w = total / a.next.k;
   const uint64_t xs[2] = {(uint64_t)row * w + __umul64hi(un0, w), (uint64_t)(row + 1) * w + __umul64hi(un1, w)};
+  bool clamped = false;
+  uint64_t q_next = 0, head_slot = 0;
+  auto between = [&] {
+    if (a.next_prio) q_next = quantise_priority(prio_next, a.qp, &clamped);
+    head_slot = head % rd.P;
+  };
   Drawn dr[2];
   if (second) {
-    wave_descend<2>(rd, pre, total, xs, dr);
+    wave_descend<2>(rd, pre, total, xs, dr, between);
   } else {
     const uint64_t x1[1] = {xs[0]};
     Drawn d1[1];
-    wave_descend<1>(rd, pre, total, x1, d1);
+    wave_descend<1>(rd, pre, total, x1, d1, between);
     dr[0] = d1[0];
     dr[1] = Drawn{~0ull, 0};
   }
-  write_drawn(a.next, row, dr[0], head);
+  // Outputs first, atomics last: nothing that the compiler makes wait for an atomic's completion follows them.
+  write_drawn(a.next, row, dr[0], head, head_slot);
   if (a.next_prio && lane == 0) {
     // the change this pair brings: none if the next pair has the same slot (the later one counts)
     const uint64_t delta = dr[1].slot != dr[0].slot ? q_next - dr[0].mass : 0;
@@ -1206,10 +1254,6 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
     if (first) return;
   }
   const uint32_t my_slot = a.slot[row];
-  // The drawing wave's first loads are to reach the memory pipeline ahead of the row loads: the
-  // other waves wait a few hundred cycles.
-  if (draw) __builtin_amdgcn_s_sleep(6);
-
   // ---- small loads first, so that nothing that uses them waits for the row
   const bool carrier = write_back && tid == kWave;
   uint64_t pc_dq = 0;
