@@ -14,8 +14,9 @@ struct apex_pipeline {
   std::vector<apex_batch_buffers_t> sets;
   hipStream_t tree, add;  // learner steps and every tree operation; add payloads
 
-  // A "mark" is the latest record of one role (payload copied, tail advanced).  Outside a capture each role re-records its own long-lived event; inside a capture
-  // every record gets a fresh event, so that no event is recorded twice in one capture.
+  // A "mark" is the latest record of one role (payload copied, tail advanced).  Outside a capture each
+  // role re-records its own long-lived event; inside a capture every record gets a fresh event, so that
+  // no event is recorded twice in one capture.
   struct Mark {
     hipEvent_t own = nullptr;  // long-lived
     hipEvent_t cur = nullptr;  // what a wait has to wait for; null: nothing to wait for
