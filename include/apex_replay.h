@@ -329,8 +329,11 @@ int apex_replay_gather_decoded(apex_replay_t *r, uint64_t count, const uint32_t 
  * them on the other (the copy stream).  A sequence of steps of one batch each is issued as one
  * launch per step (gather, weights and priority write-back of a batch together with the draw of
  * the next one; it uses the second copy of the sum tree held in the tree region); steps of
- * several batches put their gathers on the copy stream.  Results are in every case those of
- * the plain calls issued in the order: draw batch, update, [publish add], [evict].
+ * several batches put their gathers on the copy stream and on a third stream in turn, so that
+ * one large gather follows the other without a gap; the payload of an add round is written
+ * after the gathers of all batches drawn before it (it may land in slots that an eviction has
+ * freed since).  Results are in every case those of the plain calls issued in the order: draw
+ * batch, update, [publish add], [evict].
  * ---------------------------------------------------------------------------------------- */
 typedef struct apex_pipeline apex_pipeline_t;
 
@@ -349,7 +352,8 @@ typedef struct apex_batch_buffers {
 /*
  * sets: host array of `depth` (1..64) buffer sets, all pointers non-NULL device memory owned by
  * the caller; step i fills set i mod depth.  The caller must have consumed a set before depth
- * further steps are issued.  Creates two streams and a few events.
+ * further steps are issued.  Creates two streams (three for steps of several batches) and a few
+ * events.
  */
 int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buffers_t *sets, uint32_t num_batches,
                          uint32_t k, apex_pipeline_t **out);
@@ -412,7 +416,7 @@ int apex_pipeline_set_codec(apex_pipeline_t *p, uint32_t raw_bytes);
 /*
  * The same sequence as a HIP graph.  Between apex_pipeline_capture_begin and
  * apex_pipeline_capture_end the steps / add_begin / add_end calls are recorded instead of run
- * (stream capture across the pipeline's two streams; fork and join are not allowed inside);
+ * (stream capture across the pipeline's streams; fork and join are not allowed inside);
  * apex_pipeline_replay then launches the recorded sequence `times` times on the tree stream.
  * Because head and tail are read on the device, each replay continues where the last stopped;
  * the buffers, uniforms and priorities are those named at capture time.  The host mirror is

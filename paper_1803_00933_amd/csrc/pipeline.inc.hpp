@@ -13,6 +13,9 @@ struct apex_pipeline {
   uint32_t depth, nb, k;
   std::vector<apex_batch_buffers_t> sets;
   hipStream_t tree, add;  // learner steps and every tree operation; add payloads
+  // wide steps only: their gathers alternate between `add` and this stream, so that the next gather starts when
+  // its draw is done, not when the one before it has been retired (no idle gap between two large copies)
+  hipStream_t add2 = nullptr;
 
   // A "mark" is the latest record of one role (payload copied, tail advanced).  Outside a capture each
   // role re-records its own long-lived event; inside a capture every record gets a fresh event, so that
@@ -27,6 +30,9 @@ struct apex_pipeline {
   bool wide = false;
   Mark drawn;
   std::vector<Mark> gathered;
+  // the latest gather on each of the two copy streams: an add round's payload may overwrite slots that an
+  // eviction has just freed, so it waits for the gathers of batches drawn before that eviction
+  hipEvent_t last_gather[2] = {nullptr, nullptr};
   hipEvent_t fork_ev = nullptr, join_ev = nullptr;
   std::vector<hipEvent_t> capture_events;
 
@@ -47,7 +53,8 @@ struct apex_pipeline {
   hipGraph_t graph = nullptr;
   hipGraphExec_t graph_exec = nullptr;
 
-  hipStream_t streams(int i) const { return i == 0 ? tree : add; }
+  static constexpr int kStreams = 3;
+  hipStream_t streams(int i) const { return i == 0 ? tree : i == 1 ? add : add2; }  // add2 may be null
 };
 
 namespace {
@@ -91,7 +98,18 @@ void forget_marks(apex_pipeline *p)
 {
   p->payload_done.cur = p->tail_ready.cur = p->drawn.cur = nullptr;
   for (apex_pipeline::Mark &m : p->gathered) m.cur = nullptr;
+  p->last_gather[0] = p->last_gather[1] = nullptr;
   p->first_step = p->step;
+}
+
+// Stream s waits for the gathers of wide steps that are in flight on the other streams: what s is about to
+// write into the ring (an add round's payload) may land in slots that an eviction has freed since those
+// batches were drawn.
+int wait_for_gathers(apex_pipeline *p, hipStream_t s)
+{
+  for (int i = 0; i < 2; ++i)
+    if (p->last_gather[i] && p->streams(1 + i) != s) APEX_HIP(hipStreamWaitEvent(s, p->last_gather[i], 0));
+  return APEX_OK;
 }
 
 void drop_graph(apex_pipeline *p)
@@ -111,7 +129,7 @@ void pipeline_free(apex_pipeline *p)
     if (e) (void)hipEventDestroy(e);
   for (apex_pipeline::Mark &m : p->gathered)
     if (m.own) (void)hipEventDestroy(m.own);
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < apex_pipeline::kStreams; ++i)
     if (p->streams(i)) (void)hipStreamDestroy(p->streams(i));
   delete p;
 }
@@ -152,6 +170,7 @@ int apex_pipeline_create(apex_replay_t *r, uint32_t depth, const apex_batch_buff
   p->wide = (uint64_t)num_batches * k >= kWideStepSamples && depth >= 2 &&
             (uint64_t)num_batches * k * r->cfg.obs_bytes >= kWideStepBytes;
   if (p->wide) {
+    ok = ok && !hip_failed(hipStreamCreateWithFlags(&p->add2, hipStreamNonBlocking));
     p->gathered.resize(depth);
     for (apex_pipeline::Mark &m : p->gathered) ok = ok && new_mark_event(&m.own);
   }
@@ -167,7 +186,8 @@ int apex_pipeline_destroy(apex_pipeline_t *p)
 {
   if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
   (void)issue_held_step(&p->held, p->tree);
-  for (int i = 0; i < 2; ++i) (void)hipStreamSynchronize(p->streams(i));
+  for (int i = 0; i < apex_pipeline::kStreams; ++i)
+    if (p->streams(i)) (void)hipStreamSynchronize(p->streams(i));
   pipeline_free(p);
   return APEX_OK;
 }
@@ -177,7 +197,8 @@ int apex_pipeline_fork(apex_pipeline_t *p, void *after)
   if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
   APEX_TRY(issue_held_step(&p->held, p->tree));
   APEX_HIP(hipEventRecord(p->fork_ev, static_cast<hipStream_t>(after)));
-  for (int i = 0; i < 2; ++i) APEX_HIP(hipStreamWaitEvent(p->streams(i), p->fork_ev, 0));
+  for (int i = 0; i < apex_pipeline::kStreams; ++i)
+    if (p->streams(i)) APEX_HIP(hipStreamWaitEvent(p->streams(i), p->fork_ev, 0));
   return APEX_OK;
 }
 
@@ -185,7 +206,8 @@ int apex_pipeline_join(apex_pipeline_t *p, void *stream)
 {
   if (!p || p->capturing) return APEX_ERR_INVALID_ARG;
   APEX_TRY(issue_held_step(&p->held, p->tree));
-  for (int i = 0; i < 2; ++i) {
+  for (int i = 0; i < apex_pipeline::kStreams; ++i) {
+    if (!p->streams(i)) continue;
     APEX_HIP(hipEventRecord(p->join_ev, p->streams(i)));
     APEX_HIP(hipStreamWaitEvent(static_cast<hipStream_t>(stream), p->join_ev, 0));
   }
@@ -235,15 +257,17 @@ int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64
       APEX_TRY(apex_replay_sample_begin(p->r, p->nb, p->k, rnd + i * per, b.key, b.slot, b.mass, b.act, b.ret, b.gacc,
                                         p->tree));
       APEX_TRY(mark_record(p, p->drawn, p->tree));
-      APEX_TRY(mark_wait(p->drawn, p->add));
+      hipStream_t gs = (p->step & 1) ? p->add2 : p->add;
+      APEX_TRY(mark_wait(p->drawn, gs));
       if (p->codec_raw_bytes) {  // weights, then the rows through the decoder
-        APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, nullptr, p->add));
+        APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, nullptr, gs));
         APEX_TRY(apex_replay_gather_decoded(p->r, per, b.slot, p->codec_raw_bytes, b.obs, nullptr, nullptr, nullptr,
-                                            p->add));
+                                            gs));
       } else {
-        APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs, p->add));
+        APEX_TRY(apex_replay_sample_finish(p->r, p->nb, p->k, beta, b.slot, b.mass, b.weight, b.obs, gs));
       }
-      APEX_TRY(mark_record(p, p->gathered[set], p->add));
+      APEX_TRY(mark_record(p, p->gathered[set], gs));
+      p->last_gather[p->step & 1] = p->gathered[set].cur;
       if (new_prio) APEX_TRY(apex_replay_update_priorities(p->r, per, b.key, new_prio + i * per, p->tree));
       ++p->step;
       continue;
@@ -289,6 +313,7 @@ int apex_pipeline_add_begin(apex_pipeline_t *p, uint32_t S, uint32_t T, uint32_t
       }
       APEX_TRY(mark_wait(p->tail_ready, p->add));  // the add stream reads tail on the device
     }
+    APEX_TRY(wait_for_gathers(p, s));
     APEX_TRY(apex_nstep_priorities(S, T, n, A, q_online, q_target, action, reward, discount, r->cfg.alpha, r->cfg.eps,
                                    r->cfg.frac_bits, r->cfg.max_slots, prio, ret, gacc, nullptr, s));
     if (p->codec_raw_bytes && obs)
@@ -312,6 +337,7 @@ int apex_pipeline_add_end(apex_pipeline_t *p, int evict, uint64_t *first_key_out
     int rc = issue_held_step_with_round(p->r, &p->held, p->add_ns, p->add_obs, p->add_act, first_key_out, p->tree);
     if (rc == APEX_ERR_NOT_READY) {
       APEX_TRY(issue_held_step(&p->held, p->tree));
+      APEX_TRY(wait_for_gathers(p, p->tree));
       rc = add_round_small(p->r, p->add_ns, p->add_obs, p->add_act, first_key_out, p->tree);
     }
     APEX_TRY(rc);
@@ -332,16 +358,18 @@ int apex_pipeline_capture_begin(apex_pipeline_t *p)
 {
   if (!p || p->capturing || p->add_open) return APEX_ERR_INVALID_ARG;
   APEX_TRY(issue_held_step(&p->held, p->tree));
-  for (int i = 0; i < 2; ++i) APEX_HIP(hipStreamSynchronize(p->streams(i)));  // drained: nothing older to wait for
+  for (int i = 0; i < apex_pipeline::kStreams; ++i)  // drained: nothing older to wait for
+    if (p->streams(i)) APEX_HIP(hipStreamSynchronize(p->streams(i)));
   drop_graph(p);
   forget_marks(p);
   APEX_HIP(hipStreamBeginCapture(p->tree, hipStreamCaptureModeRelaxed));
   p->capturing = true;
   p->r->second_version = 0;  // a replay cannot know the state it starts from: the record refreshes the second copy first
-  // fork the add stream into the capture
+  // fork the other streams into the capture
   apex_pipeline::Mark origin;
   int rc = mark_record(p, origin, p->tree);
-  if (rc == APEX_OK) rc = mark_wait(origin, p->add);
+  for (int i = 1; i < apex_pipeline::kStreams && rc == APEX_OK; ++i)
+    if (p->streams(i)) rc = mark_wait(origin, p->streams(i));
   return rc;
 }
 
@@ -349,10 +377,14 @@ int apex_pipeline_capture_end(apex_pipeline_t *p)
 {
   if (!p || !p->capturing || p->add_open) return APEX_ERR_INVALID_ARG;
   (void)issue_held_step(&p->held, p->tree);
-  // join the add stream back into the origin of the capture
-  apex_pipeline::Mark done;
-  int rc = mark_record(p, done, p->add);
-  if (rc == APEX_OK) rc = mark_wait(done, p->tree);
+  // join the other streams back into the origin of the capture
+  int rc = APEX_OK;
+  for (int i = 1; i < apex_pipeline::kStreams && rc == APEX_OK; ++i) {
+    if (!p->streams(i)) continue;
+    apex_pipeline::Mark done;
+    rc = mark_record(p, done, p->streams(i));
+    if (rc == APEX_OK) rc = mark_wait(done, p->tree);
+  }
   hipGraph_t g = nullptr;
   const bool failed = hip_failed(hipStreamEndCapture(p->tree, &g));
   p->capturing = false;

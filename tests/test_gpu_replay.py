@@ -408,6 +408,56 @@ def test_pipeline_matches_the_plain_call_order(nb, k, ob, depth):
     pipe.close()
 
 
+@pytest.mark.parametrize("streams", [48, 30])      # a round on the copy stream (5 MB), one on the learner's stream
+def test_wide_steps_are_gathered_before_their_slots_are_reused(streams):
+    """A ring with no slack: every add round lands in the slots that the eviction before it has just freed, and
+    the batches drawn before that eviction hold many of the evicted keys.  Their gathers, which run on the copy
+    streams, have to be through before the round's payload is written; nothing here synchronises in between."""
+    from paper_1803_00933_amd import apex, synth
+    nb, k, ob, depth, T = 4, 512, 4224, 4, 25
+    count = streams * T
+    C = 2100
+    w = synth.WORKLOADS["tiny"].scaled(obs_bytes=ob, capacity=C, max_slots=C + count, streams=streams, chunk=T, k=k)
+    rng = np.random.default_rng(streams)
+    g, o = make_pair(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    add_both(g, o, rng, w.capacity)
+    pipe = apex.Pipeline(g, depth, nb, w.k)
+    cycles = 3 * depth
+    rnd = rng.integers(0, U64, (cycles, nb * w.k), dtype=np.uint64)
+    newp = rng.lognormal(0, 1, (cycles, nb * w.k)).astype(F32)
+    d_rnd, d_newp = dev(rnd), dev(newp)
+    scratch = [torch.empty(count, dtype=torch.float32, device="cuda:0") for _ in range(3)]
+    rounds = []
+    for i in range(cycles):
+        d = synth.actor_round(w, i)
+        d["obs"] = rng.integers(0, 256, (count, w.obs_bytes), dtype=np.uint8)
+        rounds.append((d, {k2: dev(v) for k2, v in d.items()}))
+    torch.cuda.synchronize()
+    for c0 in range(0, cycles, depth):
+        assert pipe.fork() == 0
+        refs = []
+        for s in range(c0, c0 + depth):
+            d, dd = rounds[s]
+            assert pipe.add_begin(dd["q_online"], dd["q_target"], dd["action"], dd["reward"], dd["discount"], w.n,
+                                  dd["obs"], dd["act"], *scratch) == 0
+            rc, first = pipe.steps(1, 0.4, d_rnd[s], d_newp[s])
+            assert rc == 0 and first == s % depth
+            rc, first_key, ev = pipe.add_end(True)
+            refs.append(o.sample(nb, w.k, 0.4, rnd[s])[1])
+            o.update_priorities(refs[-1]["key"], newp[s])
+            ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                          w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+            assert (rc, first_key) == o.add(ref[0].reshape(-1), d["obs"], d["act"], ref[1].reshape(-1),
+                                            ref[2].reshape(-1))
+            assert o.evict() == (0, ev) and ev == count
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        for s in range(c0, c0 + depth):
+            assert_sample_equal(pipe.sets[s % depth], refs[s - c0])
+        check_gpu_tree(g, o)
+    pipe.close()
+
+
 def test_pipeline_small_and_large_add_rounds():
     """Small add rounds travel on the learner's stream, large ones on the copy stream: rounds of both kinds
     in one pipeline, with learner steps in between, against the oracle."""
