@@ -216,6 +216,16 @@ int launch_copy(const void *src, const RowMap &smap, void *dst, const RowMap &dm
 }
 
 
+// The constants of fast_div for the divisor d >= 1.
+FastDiv make_fast_div(uint32_t d)
+{
+  if (d == 0) d = 1;
+  uint32_t L = 0;
+  while (L < 32 && (1ull << L) < d) ++L;
+  const unsigned __int128 num = ((unsigned __int128)((1ull << L) - d)) << 64;
+  return FastDiv{(uint64_t)(num / d) + 1, L < 1 ? L : 1, L > 0 ? L - 1 : 0};
+}
+
 // One launch of the fused learner step (see learner_step_kernel) for vectors of sizeof(Vec) bytes.
 // Steps whose rows are decoded on their way out (16-byte vectors; riders: none, or the masses of an add round).
 void launch_step_codec(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t threads, size_t lds, int rider,
@@ -638,6 +648,7 @@ void launch_step(const StepArgs &args, uint32_t vector_bytes, uint32_t n_top, ui
 {
   StepArgs a = args;
   a.next_top = a.next.tv.level[a.next.tv.nlev - 1];
+  a.next_k_div = make_fast_div(a.next.k);
   if (a.codec.raw_bytes && a.slot) return launch_step_codec(a, n_top, wgs, threads, lds, rider, stream);
   if (vector_bytes == 16) launch_step_t<u32x4>(a, n_top, wgs, threads, lds, rider, stream);
   else if (vector_bytes == 4) launch_step_t<uint32_t>(a, n_top, wgs, threads, lds, rider, stream);

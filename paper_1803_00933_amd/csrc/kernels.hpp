@@ -899,40 +899,91 @@ struct Drawn {
   uint64_t slot, mass;
 };
 
-// One wavefront walks from the top level (exclusive prefix sums `pre` in LDS) down to the slots whose
-// cumulative-mass intervals hold x[0 .. kSamples): the loads of all samples go out together on every
-// level, so that several draws take the time of one.  Called by all 64 lanes.
+// Exact floor(n / d) for any n by a multiplication, for a divisor that the host knows at launch time
+// (the 64-bit quotient of a sum of masses by the batch size is otherwise a long software division on the
+// drawing wave's critical path).  Granlund and Montgomery's unsigned division by an invariant integer:
+// L = ceil(log2 d), mul = floor(2^64 (2^L - d) / d) + 1, sh1 = min(L, 1), sh2 = max(L - 1, 0).
+struct FastDiv {
+  uint64_t mul;
+  uint32_t sh1, sh2;
+};
+
+__device__ __forceinline__ uint64_t fast_div(uint64_t n, const FastDiv &d)
+{
+  const uint64_t t = __umul64hi(d.mul, n);
+  return (t + ((n - t) >> d.sh1)) >> d.sh2;
+}
+
+// Where a walk stands after the top level: node idx of that level, whose interval of cumulative mass
+// holds the point; x is the point's offset inside the interval, mass the node's mass.
+struct TopHit {
+  uint64_t idx, x, mass;
+};
+
+// Top level from LDS: `pre` holds its exclusive prefix sums; largest i with pre[i] <= x, by two rounds of
+// 64-way comparison.  Called by all 64 lanes.
+__device__ __forceinline__ TopHit top_search_lds(const uint64_t *pre, uint32_t n_top, uint64_t total, uint64_t x)
+{
+  const int lane = lane_id();
+  const uint32_t stride = (n_top + kWave - 1) / kWave;
+  const uint32_t p0 = lane * stride;
+  uint32_t cnt = __popcll(__ballot(p0 < n_top && pre[p0] <= x));
+  const uint32_t base = (cnt - 1) * stride;  // pre[0] = 0 <= x, so cnt >= 1
+  cnt = 0;
+  for (uint32_t off = 0; off < stride; off += kWave) {
+    const uint32_t p1 = base + off + lane;
+    cnt += __popcll(__ballot(off + lane < stride && p1 < n_top && pre[p1] <= x));
+  }
+  const uint64_t idx = base + cnt - 1;
+  const uint64_t mass = ((idx + 1 < n_top) ? pre[idx + 1] : total) - pre[idx];
+  return TopHit{idx, x - pre[idx], mass};
+}
+
+// Top level of at most 512 nodes from registers: lane l holds the masses v[0..8) of nodes 8l .. 8l+7 (zero
+// beyond the level) and lane_before, the sum of all nodes before them.  The same node as top_search_lds
+// finds (the last one whose prefix sum is <= x), without a round trip through LDS: the lane by one
+// ballot, the node inside the lane by eight comparisons that every lane makes for itself, the winner's
+// values by lane reads.  Called by all 64 lanes.
+__device__ __forceinline__ uint32_t read_lane_u32(uint32_t v, uint32_t l)
+{
+  return (uint32_t)__builtin_amdgcn_readlane((int)v, (int)l);
+}
+__device__ __forceinline__ uint64_t read_lane_u64(uint64_t v, uint32_t l)
+{
+  return ((uint64_t)read_lane_u32((uint32_t)(v >> 32), l) << 32) | read_lane_u32((uint32_t)v, l);
+}
+__device__ __forceinline__ TopHit top_search_regs(const uint64_t (&v)[8], uint64_t lane_before, uint64_t x)
+{
+  const uint32_t l = __popcll(__ballot(lane_before <= x)) - 1;  // lane 0 has lane_before = 0 <= x
+  uint64_t p = lane_before, p_hit = lane_before, v_hit = v[0];
+  uint32_t t_hit = 0;
+#pragma unroll
+  for (int t = 1; t < 8; ++t) {
+    p += v[t - 1];
+    const bool le = p <= x;  // true for the first few t only: the prefix sums do not decrease
+    t_hit = le ? t : t_hit;
+    p_hit = le ? p : p_hit;
+    v_hit = le ? v[t] : v_hit;
+  }
+  return TopHit{8ull * l + read_lane_u32(t_hit, l), x - read_lane_u64(p_hit, l), read_lane_u64(v_hit, l)};
+}
+
+// One wavefront walks from its places in the top level down to the slots whose cumulative-mass intervals
+// hold the points: the loads of all samples go out together on every level, so that several draws take
+// the time of one.  Called by all 64 lanes.
 // between(): called once, when the loads of the first level below the top are on their way (right away if
 // the tree has no such level): arithmetic that does not depend on the walk costs nothing there.
 template <int kSamples, typename Between>
-__device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t *pre, uint64_t total,
-                                             const uint64_t (&x_in)[kSamples], Drawn (&out)[kSamples],
-                                             Between between)
+__device__ __forceinline__ void walk_down(const TreeView &tv, const TopHit (&top)[kSamples], Drawn (&out)[kSamples],
+                                          Between between)
 {
   const int lane = lane_id();
-  const uint32_t n_top = tv.n_top;
-  const uint32_t stride = (n_top + kWave - 1) / kWave;
   // the two lowest levels' addresses are at fixed places of the arguments: fetched with them, not on the way down
   const uint64_t *const low0 = tv.level[0], *const low1 = tv.level[1];
   uint64_t x[kSamples], idx[kSamples], mass[kSamples];
 #pragma unroll
-  for (int s = 0; s < kSamples; ++s) {
-    // top level: largest i with pre[i] <= x, by two rounds of 64-way comparison
-    x[s] = x_in[s];
-    const uint32_t p0 = lane * stride;
-    uint32_t cnt = __popcll(__ballot(p0 < n_top && pre[p0] <= x[s]));
-    const uint32_t base = (cnt - 1) * stride;  // pre[0] = 0 <= x, so cnt >= 1
-    cnt = 0;
-    for (uint32_t off = 0; off < stride; off += kWave) {
-      const uint32_t p1 = base + off + lane;
-      cnt += __popcll(__ballot(off + lane < stride && p1 < n_top && pre[p1] <= x[s]));
-    }
-    idx[s] = base + cnt - 1;
-    mass[s] = ((idx[s] + 1 < n_top) ? pre[idx[s] + 1] : total) - pre[idx[s]];
-    x[s] -= pre[idx[s]];
-  }
-  // lower levels: 64 children per step, prefix sum across the wave, first child whose
-  // running sum exceeds the remainder
+  for (int s = 0; s < kSamples; ++s) x[s] = top[s].x, idx[s] = top[s].idx, mass[s] = top[s].mass;
+  // 64 children per step, prefix sum across the wave, first child whose running sum exceeds the remainder
   bool called = false;
   for (int l = (int)tv.nlev - 2; l >= 0; --l) {
     const uint64_t *const lv = l == 0 ? low0 : l == 1 ? low1 : tv.level[l];
@@ -958,6 +1009,18 @@ __device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t 
   if (!called) between();
 #pragma unroll
   for (int s = 0; s < kSamples; ++s) out[s] = Drawn{idx[s], mass[s]};
+}
+
+// The whole descent with the top level in LDS (exclusive prefix sums `pre`).
+template <int kSamples, typename Between>
+__device__ __forceinline__ void wave_descend(const TreeView &tv, const uint64_t *pre, uint64_t total,
+                                             const uint64_t (&x_in)[kSamples], Drawn (&out)[kSamples],
+                                             Between between)
+{
+  TopHit top[kSamples];
+#pragma unroll
+  for (int s = 0; s < kSamples; ++s) top[s] = top_search_lds(pre, tv.n_top, total, x_in[s]);
+  walk_down<kSamples>(tv, top, out, between);
 }
 
 template <int kSamples>
@@ -1091,6 +1154,7 @@ struct StepArgs {
   WeightArgs wa;          // weights of batch i
   SampleArgs next;        // draw of batch i+1 from next.tv, the copy that is read; next.rnd == null: none
   const uint64_t *next_top;  // the top level of next.tv (its address at a fixed place of the arguments)
+  FastDiv next_k_div;        // division by next.k
   const float *next_prio; // [k] new priorities of batch i+1 (null: none) ...
   uint64_t *next_dq;      // ... the changes they bring, kept for the next launch
   QuantParams qp;
@@ -1111,15 +1175,26 @@ enum StepRider { kNoRider = 0, kRoundRides = 1, kLeavesRide = 2 };
 
 typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
+// Keeps a wave-uniform value in scalar registers from here on: the compiler would otherwise fetch a
+// kernel argument only where it is first used, behind a wait of its own.
+template <typename T>
+__device__ __forceinline__ void fetch_now(T *p)
+{
+  asm volatile("" ::"s"(p));
+}
+
 // The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier: the
-// top level (eight consecutive nodes per lane and pass of 512, 16-byte loads) into registers, its prefix
-// sums into LDS, two walks down, outputs, and the change that the sample's new priority brings.
+// top level (eight consecutive nodes per lane and pass of 512, 16-byte loads) into registers, two walks
+// down, outputs, and the change that the sample's new priority brings.
 // The wave's path through memory is the launch's critical path, so it holds exactly one round trip per
-// tree level: the top-level loads are the first instructions to go out, the sample's random number, new
-// priority and the ring's head follow them and are used after them (a wave's loads return in the order of
-// issue), and the arithmetic that does not depend on the walk (priority -> mass, head % P) runs while the
-// first row of children is on its way.
-// LDS: round_up(n_top, 64) words of 8 bytes.
+// tree level and as little else as can be:
+//  - the top-level loads are the first instructions to go out, the sample's random number, new priority
+//    and the ring's head follow them and are used after them (a wave's loads return in the order of issue);
+//  - a top level of one pass (kTopChunk == 1: at most 512 nodes) is searched in the registers it was
+//    loaded into; larger ones go through LDS as exclusive prefix sums (round_up(n_top, 64) words of 8 bytes);
+//  - the stratum width is an exact division by multiplication (StepArgs::next_k_div);
+//  - what does not depend on the walk (priority -> mass, head % P, the addresses of everything written at
+//    the end) is computed or fetched while the first row of children is on its way.
 template <int kTopChunk>
 __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *pre)
 {
@@ -1131,9 +1206,7 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
   const uint64_t *top = a.next_top;
   constexpr uint32_t kChunkNodes = kTopChunk * 8 * kWave;
 
-  // ---- top level: exclusive prefix sums -> LDS; the loads of kTopChunk passes go out together
   uint64_t v[kTopChunk][8];
-  uint64_t carry = 0;
   auto issue = [&](uint32_t c0) {
 #pragma unroll
     for (int p = 0; p < kTopChunk; ++p) {
@@ -1149,64 +1222,102 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
       }
     }
   };
-  auto consume = [&](uint32_t c0) {
-#pragma unroll
-    for (int p = 0; p < kTopChunk; ++p) {
-      const uint32_t i0 = c0 + p * 8 * kWave + 8 * lane;
-      uint64_t mine = 0;
-#pragma unroll
-      for (int t = 0; t < 8; ++t) mine += v[p][t];
-      const uint64_t incl = wave_inclusive_scan(mine);
-      uint64_t run = carry + incl - mine;
-      if (i0 < n_top_pad) {
-#pragma unroll
-        for (int t = 0; t < 8; ++t) {
-          pre[i0 + t] = run;
-          run += v[p][t];
-        }
-      }
-      carry += __shfl(incl, kWave - 1, kWave);
-    }
-  };
   issue(0);
   // no load below is conditional: a branch around a load would make the wave wait for it there
   const uint64_t un0 = a.next.rnd[row], un1 = a.next.rnd[second ? row + 1 : row];
   const float prio_next = *(a.next_prio ? a.next_prio + row : reinterpret_cast<const float *>(a.next.rnd + row));
   const uint64_t head = a.next.st->head;
-  consume(0);
-  for (uint32_t c0 = kChunkNodes; c0 < n_top_pad; c0 += kChunkNodes) {
-    issue(c0);
-    consume(c0);
-  }
-  const uint64_t total = carry;
-  wave_lds_sync();
 
-  const uint64_t w = total / a.next.k;
-  const uint64_t xs[2] = {(uint64_t)row * w + __umul64hi(un0, w), (uint64_t)(row + 1) * w + __umul64hi(un1, w)};
+  TopHit hit[2];
+  if constexpr (kTopChunk == 1) {
+    // ---- one pass: the level stays in the registers it was loaded into
+    uint64_t mine = 0;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) mine += v[0][t];
+    const uint64_t incl = wave_inclusive_scan(mine);
+    const uint64_t total = read_lane_u64(incl, kWave - 1);
+    const uint64_t w = fast_div(total, a.next_k_div);
+    hit[0] = top_search_regs(v[0], incl - mine, (uint64_t)row * w + __umul64hi(un0, w));
+    if (second) hit[1] = top_search_regs(v[0], incl - mine, (uint64_t)(row + 1) * w + __umul64hi(un1, w));
+  } else {
+    // ---- exclusive prefix sums -> LDS; the loads of kTopChunk passes go out together
+    uint64_t carry = 0;
+    auto consume = [&](uint32_t c0) {
+#pragma unroll
+      for (int p = 0; p < kTopChunk; ++p) {
+        const uint32_t i0 = c0 + p * 8 * kWave + 8 * lane;
+        uint64_t mine = 0;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) mine += v[p][t];
+        const uint64_t incl = wave_inclusive_scan(mine);
+        uint64_t run = carry + incl - mine;
+        if (i0 < n_top_pad) {
+#pragma unroll
+          for (int t = 0; t < 8; ++t) {
+            pre[i0 + t] = run;
+            run += v[p][t];
+          }
+        }
+        carry += __shfl(incl, kWave - 1, kWave);
+      }
+    };
+    consume(0);
+    for (uint32_t c0 = kChunkNodes; c0 < n_top_pad; c0 += kChunkNodes) {
+      issue(c0);
+      consume(c0);
+    }
+    const uint64_t total = carry;
+    wave_lds_sync();
+    const uint64_t w = fast_div(total, a.next_k_div);
+    hit[0] = top_search_lds(pre, n_top, total, (uint64_t)row * w + __umul64hi(un0, w));
+    if (second) hit[1] = top_search_lds(pre, n_top, total, (uint64_t)(row + 1) * w + __umul64hi(un1, w));
+  }
+
   bool clamped = false;
   uint64_t q_next = 0, head_slot = 0;
+  uint32_t *const slot_out = a.next.slot_out;
+  uint64_t *const key_out = a.next.key_out, *const mass_out = a.next.mass, *const dq_out = a.next_dq;
+  uint64_t *const wr0 = a.wr.level[0], *const wr1 = a.wr.level[1], *const wr2 = a.wr.level[2];
+  const uint32_t wr_nlev = a.wr.nlev;
   auto between = [&] {
+    fetch_now(slot_out), fetch_now(key_out), fetch_now(mass_out), fetch_now(dq_out);
+    fetch_now(wr0), fetch_now(wr1), fetch_now(wr2);
     if (a.next_prio) q_next = quantise_priority(prio_next, a.qp, &clamped);
     head_slot = head % rd.P;
   };
   Drawn dr[2];
   if (second) {
-    wave_descend<2>(rd, pre, total, xs, dr, between);
+    walk_down<2>(rd, hit, dr, between);
   } else {
-    const uint64_t x1[1] = {xs[0]};
+    const TopHit h1[1] = {hit[0]};
     Drawn d1[1];
-    wave_descend<1>(rd, pre, total, x1, d1, between);
+    walk_down<1>(rd, h1, d1, between);
     dr[0] = d1[0];
     dr[1] = Drawn{~0ull, 0};
   }
   // Outputs first, atomics last: nothing that the compiler makes wait for an atomic's completion follows them.
-  write_drawn(a.next, row, dr[0], head, head_slot);
-  if (a.next_prio && lane == 0) {
-    // the change this pair brings: none if the next pair has the same slot (the later one counts)
-    const uint64_t delta = dr[1].slot != dr[0].slot ? q_next - dr[0].mass : 0;
-    a.next_dq[row] = delta;
-    add_delta(a.wr, (uint32_t)dr[0].slot, delta);
-    if (clamped) atomic_add_u64(&a.st->n_clamped, 1);
+  // (The small payload columns of the drawn batch are gathered by the launch that copies its rows.)
+  if (lane == 0) {
+    const uint64_t slot = dr[0].slot;
+    slot_out[row] = (uint32_t)slot;
+    if (key_out) key_out[row] = ring_key(slot, head, head_slot, rd.P);
+    mass_out[row] = dr[0].mass;
+    if (a.next_prio) {
+      // the change this pair brings: none if the next pair has the same slot (the later one counts)
+      const uint64_t delta = dr[1].slot != slot ? q_next - dr[0].mass : 0;
+      dq_out[row] = delta;
+      if (delta) {
+        atomic_add_u64(wr0 + slot, delta);
+        if (wr_nlev > 1) atomic_add_u64(wr1 + (slot >> kFanoutLog2), delta);
+        if (wr_nlev > 2) atomic_add_u64(wr2 + (slot >> (2 * kFanoutLog2)), delta);
+        uint64_t idx = slot >> (2 * kFanoutLog2);
+        for (uint32_t l = 3; l < wr_nlev; ++l) {
+          idx >>= kFanoutLog2;
+          atomic_add_u64(a.wr.level[l] + idx, delta);
+        }
+      }
+      if (clamped) atomic_add_u64(&a.st->n_clamped, 1);
+    }
   }
   __builtin_amdgcn_s_setprio(0);
 }
