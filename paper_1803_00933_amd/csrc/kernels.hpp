@@ -1175,6 +1175,12 @@ enum StepRider { kNoRider = 0, kRoundRides = 1, kLeavesRide = 2 };
 
 typedef uint64_t u64x2 __attribute__((ext_vector_type(2)));
 
+// Waits until every load (and store) that this wave has issued is through.
+__device__ __forceinline__ void wait_for_all_loads()
+{
+  __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0); the other counters at their maxima (not waited for)
+}
+
 // Keeps a wave-uniform value in scalar registers from here on: the compiler would otherwise fetch a
 // kernel argument only where it is first used, behind a wait of its own.
 template <typename T>
@@ -1279,6 +1285,17 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
   uint64_t *const key_out = a.next.key_out, *const mass_out = a.next.mass, *const dq_out = a.next_dq;
   uint64_t *const wr0 = a.wr.level[0], *const wr1 = a.wr.level[1], *const wr2 = a.wr.level[2];
   const uint32_t wr_nlev = a.wr.nlev;
+  auto add_to_written_copy = [&](uint64_t slot, uint64_t delta) {  // one lane
+    if (!delta) return;
+    atomic_add_u64(wr0 + slot, delta);
+    if (wr_nlev > 1) atomic_add_u64(wr1 + (slot >> kFanoutLog2), delta);
+    if (wr_nlev > 2) atomic_add_u64(wr2 + (slot >> (2 * kFanoutLog2)), delta);
+    uint64_t idx = slot >> (2 * kFanoutLog2);
+    for (uint32_t l = 3; l < wr_nlev; ++l) {
+      idx >>= kFanoutLog2;
+      atomic_add_u64(a.wr.level[l] + idx, delta);
+    }
+  };
   auto between = [&] {
     fetch_now(slot_out), fetch_now(key_out), fetch_now(mass_out), fetch_now(dq_out);
     fetch_now(wr0), fetch_now(wr1), fetch_now(wr2);
@@ -1306,16 +1323,7 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
       // the change this pair brings: none if the next pair has the same slot (the later one counts)
       const uint64_t delta = dr[1].slot != slot ? q_next - dr[0].mass : 0;
       dq_out[row] = delta;
-      if (delta) {
-        atomic_add_u64(wr0 + slot, delta);
-        if (wr_nlev > 1) atomic_add_u64(wr1 + (slot >> kFanoutLog2), delta);
-        if (wr_nlev > 2) atomic_add_u64(wr2 + (slot >> (2 * kFanoutLog2)), delta);
-        uint64_t idx = slot >> (2 * kFanoutLog2);
-        for (uint32_t l = 3; l < wr_nlev; ++l) {
-          idx >>= kFanoutLog2;
-          atomic_add_u64(a.wr.level[l] + idx, delta);
-        }
-      }
+      add_to_written_copy(slot, delta);
       if (clamped) atomic_add_u64(&a.st->n_clamped, 1);
     }
   }
@@ -1364,54 +1372,56 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
     draw_in_first_wave<kTopChunk>(a, row, lds);
     if (first) return;
   }
+  // The compiler places its waits for memory by counting loads in flight; it can count them only along
+  // straight-line code, and where a load sits in a branch, or loads and stores are in flight together, it
+  // waits for everything.  As first written this part had the row loads wait for every small load, the
+  // weights' eight loads wait for one another, and each of the row's stores wait for the one before it to
+  // be acknowledged (read in the kernel's own ISA; the waves with a side job ended 1 - 2 us after the
+  // others, and the launch with them).  So: the slot is waited for at once (everything depends on it),
+  // no load below sits in a divergent branch (indices are clamped, unused lanes read an address of their
+  // own workgroup that is always valid), the row is waited for once, and the side jobs' stores and
+  // atomics follow the row's.
   const uint32_t my_slot = a.slot[row];
-  // ---- small loads first, so that nothing that uses them waits for the row
+  wait_for_all_loads();
+
+  // ---- small loads, ahead of the row so that they return ahead of it
+  // the change that pair `row` brings (0 if a later pair of the batch has the same slot), carried into the
+  // written copy by one lane: behind the row's stores in a launch that draws (its end is set by the drawing
+  // wave's own atomics, and ahead of the stores this wave's part of the row would wait for them); as soon as
+  // it has arrived in a launch that draws nothing (these atomics are then the last thing to finish)
   const bool carrier = write_back && tid == kWave;
   uint64_t pc_dq = 0;
-  if (carrier) pc_dq = a.dq[row];  // 0 if a later pair of the batch has the same slot
-  float small = 0.0f;
-  if (tid == kWave + 1 && a.ret_out) small = a.ret[my_slot];
-  if (tid == kWave + 2 && a.gacc_out) small = a.gacc[my_slot];
+  if (write_back) pc_dq = a.dq[row];  // by every lane: the same for all, and no address that the whole grid shares
+  const bool ret_lane = tid == kWave + 1 && a.ret_out, gacc_lane = tid == kWave + 2 && a.gacc_out;
+  const float small = *(ret_lane    ? a.ret + my_slot
+                        : gacc_lane ? a.gacc + my_slot
+                                    : reinterpret_cast<const float *>(a.slot + row));
   const bool weigher = wave == 3 && a.wa.weight_out && row * kWave < a.k;
-  uint64_t mass_min = ~0ull, mass_mine = 1;
-  if (weigher) {  // smallest mass of the batch, eight loads per lane in flight
-    for (uint32_t j0 = 0; j0 < a.k; j0 += 8 * kWave) {
-      uint64_t wm[8];
-#pragma unroll
-      for (int t = 0; t < 8; ++t) {
-        const uint32_t j = j0 + t * kWave + lane;
-        wm[t] = j < a.k ? a.wa.mass[j] : ~0ull;
-      }
-#pragma unroll
-      for (int t = 0; t < 8; ++t) mass_min = wm[t] < mass_min ? wm[t] : mass_min;
-    }
-    if (row * kWave + lane < a.k) mass_mine = a.wa.mass[row * kWave + lane];
-  }
   uint8_t act_byte[4] = {0, 0, 0, 0};
   const bool act_early = wave == 2 && a.act_out && a.act_bytes <= 4 * kWave;
   if (act_early) {
 #pragma unroll
-    for (int t = 0; t < 4; ++t) {
-      const uint32_t by = t * kWave + lane;
-      if (by < a.act_bytes) act_byte[t] = a.act[(uint64_t)my_slot * a.act_bytes + by];
-    }
+    for (int t = 0; t < 4; ++t)
+      act_byte[t] = a.act[(uint64_t)my_slot * a.act_bytes + min(t * kWave + lane, a.act_bytes - 1)];
   }
+
+  if (carrier && !draw) add_delta(a.wr, my_slot, pc_dq);
 
   // ---- the row
   const uint32_t copiers = nthr - first;
   const Vec *s = reinterpret_cast<const Vec *>(a.src + (uint64_t)my_slot * a.row_bytes);
   Vec *d = reinterpret_cast<Vec *>(a.dst + (uint64_t)row * (kCodec ? (uint64_t)a.codec.raw_bytes : a.row_bytes));
+  const uint32_t v_last = a.vecs_per_row - 1;
   Vec tmp[kUnroll];
   CodecFetched fetched[kCodec ? kUnroll : 1] = {};
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
-    const uint32_t v = tid - first + u * copiers;
+    const uint32_t v = min(tid - first + u * copiers, v_last);
     if constexpr (kCodec) {  // the pieces as the image holds them; mask and block bytes follow below
-      if (v < a.vecs_per_row)
-        fetched[u].data = __builtin_nontemporal_load(
-            reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(s) + a.codec.image_off) + v);
+      fetched[u].data = __builtin_nontemporal_load(
+          reinterpret_cast<const u32x4 *>(reinterpret_cast<const uint8_t *>(s) + a.codec.image_off) + v);
     } else {
-      if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+      tmp[u] = __builtin_nontemporal_load(s + v);
     }
   }
   if constexpr (kCodec) {
@@ -1426,10 +1436,42 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
       }
     }
   }
+  // the weights' loads go out behind the row's (ahead of them, the wave's part of the row would leave a
+  // round trip or two late): smallest mass of the batch, eight loads per lane in flight
+  uint64_t mass_min = ~0ull, mass_mine = 1;
+  if (weigher) {
+    mass_mine = a.wa.mass[min(row * kWave + lane, a.k - 1)];
+    for (uint32_t j0 = 0; j0 < a.k; j0 += 8 * kWave) {
+      uint64_t wm[8];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) wm[t] = a.wa.mass[min(j0 + t * kWave + lane, a.k - 1)];
+#pragma unroll
+      for (int t = 0; t < 8; ++t) mass_min = wm[t] < mass_min ? wm[t] : mass_min;
+    }
+  }
 
-  if (carrier) add_delta(a.wr, my_slot, pc_dq);
-  if (tid == kWave + 1 && a.ret_out) a.ret_out[row] = small;
-  if (tid == kWave + 2 && a.gacc_out) a.gacc_out[row] = small;
+  wait_for_all_loads();
+  if constexpr (kCodec) {
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+      const u32x4 piece = codec_piece(fetched[u]);
+      __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
+    }
+  }
+  // One store at a time per wave (a wave waits for its last store before it issues the next): with a wave's
+  // four stores in flight together the launch took 0.3 - 0.8 us longer (measured both ways), the write
+  // queues of the whole chip filling at once.
+#pragma unroll
+  for (int u = 0; u < kUnroll; ++u) {
+    const uint32_t v = tid - first + u * copiers;
+    if (u > 0 && v - lane < a.vecs_per_row) wait_for_all_loads();  // the same for all lanes of the wave
+    if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+  }
+
+  // ---- what the side jobs write
+  if (carrier && draw) add_delta(a.wr, my_slot, pc_dq);
+  if (ret_lane) a.ret_out[row] = small;
+  if (gacc_lane) a.gacc_out[row] = small;
   if (act_early) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
@@ -1438,37 +1480,23 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
     }
   }
   if (weigher) {
-    const float fmn = (float)wave_min(mass_min);
-    const uint32_t j = row * kWave + lane;
-    if (j < a.k) a.wa.weight_out[j] = pow_fixed_sequence(fmn / (float)mass_mine, a.wa.beta);
+    const float weight = pow_fixed_sequence((float)wave_min(mass_min) / (float)mass_mine, a.wa.beta);
+    if (row * kWave + lane < a.k) a.wa.weight_out[row * kWave + lane] = weight;
   }
 
-  if constexpr (kCodec) {
-#pragma unroll
-    for (int u = 0; u < kUnroll; ++u) {
-      const u32x4 piece = codec_piece(fetched[u]);
-      __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
-    }
-  }
-#pragma unroll
-  for (int u = 0; u < kUnroll; ++u) {
-    const uint32_t v = tid - first + u * copiers;
-    if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
-  }
   // rows longer than one pass of the workgroup (more than 32 KB, or narrow vectors)
   for (uint32_t base = copiers * kUnroll; base < a.vecs_per_row; base += copiers * kUnroll) {
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
-      const uint32_t v = base + tid - first + u * copiers;
+      const uint32_t v = min(base + tid - first + u * copiers, v_last);
       if constexpr (kCodec) {
-        if (v < a.vecs_per_row) {
-          const u32x4 piece = codec_piece(codec_fetch_all(reinterpret_cast<const uint8_t *>(s), a.codec, v));
-          __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
-        }
+        const u32x4 piece = codec_piece(codec_fetch_all(reinterpret_cast<const uint8_t *>(s), a.codec, v));
+        __builtin_memcpy(&tmp[u], &piece, sizeof(Vec));
       } else {
-        if (v < a.vecs_per_row) tmp[u] = __builtin_nontemporal_load(s + v);
+        tmp[u] = __builtin_nontemporal_load(s + v);
       }
     }
+    wait_for_all_loads();
 #pragma unroll
     for (int u = 0; u < kUnroll; ++u) {
       const uint32_t v = base + tid - first + u * copiers;
