@@ -897,6 +897,7 @@ __device__ __forceinline__ uint64_t top_prefix_sums(uint64_t *pre, uint64_t *wav
 
 struct Drawn {
   uint64_t slot, mass;
+  uint64_t x;  // where in the slot's interval of cumulative mass the point fell: 0 <= x < mass
 };
 
 // Exact floor(n / d) for any n by a multiplication, for a divisor that the host knows at launch time
@@ -1008,7 +1009,7 @@ __device__ __forceinline__ void walk_down(const TreeView &tv, const TopHit (&top
   }
   if (!called) between();
 #pragma unroll
-  for (int s = 0; s < kSamples; ++s) out[s] = Drawn{idx[s], mass[s]};
+  for (int s = 0; s < kSamples; ++s) out[s] = Drawn{idx[s], mass[s], x[s]};
 }
 
 // The whole descent with the top level in LDS (exclusive prefix sums `pre`).
@@ -1111,8 +1112,8 @@ __global__ __launch_bounds__(1024) void sample_descent_kernel(SampleArgs a)
 //
 // Within a batch the drawn slots do not decrease (the strata are ordered), so the pairs that
 // share a slot are neighbours and the last of them is the one that counts: the wave that draws
-// sample j draws sample j+1 as well (both walks load together), only to see whether it lands
-// in the same slot.
+// sample j also computes the point of sample j+1 and sees whether it still lies inside the slot's
+// interval of cumulative mass.
 // --------------------------------------------------------------------------------------------
 __device__ __forceinline__ void add_delta(const TreeView &tv, uint32_t slot, uint64_t delta)
 {
@@ -1190,7 +1191,7 @@ __device__ __forceinline__ void fetch_now(T *p)
 }
 
 // The draw of sample `row` of the next batch by the first wave of a workgroup, with no barrier: the
-// top level (eight consecutive nodes per lane and pass of 512, 16-byte loads) into registers, two walks
+// top level (eight consecutive nodes per lane and pass of 512, 16-byte loads) into registers, the walk
 // down, outputs, and the change that the sample's new priority brings.
 // The wave's path through memory is the launch's critical path, so it holds exactly one round trip per
 // tree level and as little else as can be:
@@ -1234,7 +1235,12 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
   const float prio_next = *(a.next_prio ? a.next_prio + row : reinterpret_cast<const float *>(a.next.rnd + row));
   const uint64_t head = a.next.st->head;
 
-  TopHit hit[2];
+  // Within a batch the points do not decrease, so the pairs that share a slot are neighbours and the last of
+  // them is the one that counts: pair `row` loses to pair row + 1 exactly if the next point still lies in the
+  // interval of cumulative mass of the slot drawn here, which needs no second walk: both points are known
+  // from the start, and the walk ends with the place of its point inside the slot's interval.
+  uint64_t point = 0, next_point = 0;
+  TopHit hit[1];
   if constexpr (kTopChunk == 1) {
     // ---- one pass: the level stays in the registers it was loaded into
     uint64_t mine = 0;
@@ -1243,8 +1249,8 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
     const uint64_t incl = wave_inclusive_scan(mine);
     const uint64_t total = read_lane_u64(incl, kWave - 1);
     const uint64_t w = fast_div(total, a.next_k_div);
-    hit[0] = top_search_regs(v[0], incl - mine, (uint64_t)row * w + __umul64hi(un0, w));
-    if (second) hit[1] = top_search_regs(v[0], incl - mine, (uint64_t)(row + 1) * w + __umul64hi(un1, w));
+    point = (uint64_t)row * w + __umul64hi(un0, w), next_point = (uint64_t)(row + 1) * w + __umul64hi(un1, w);
+    hit[0] = top_search_regs(v[0], incl - mine, point);
   } else {
     // ---- exclusive prefix sums -> LDS; the loads of kTopChunk passes go out together
     uint64_t carry = 0;
@@ -1275,8 +1281,8 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
     const uint64_t total = carry;
     wave_lds_sync();
     const uint64_t w = fast_div(total, a.next_k_div);
-    hit[0] = top_search_lds(pre, n_top, total, (uint64_t)row * w + __umul64hi(un0, w));
-    if (second) hit[1] = top_search_lds(pre, n_top, total, (uint64_t)(row + 1) * w + __umul64hi(un1, w));
+    point = (uint64_t)row * w + __umul64hi(un0, w), next_point = (uint64_t)(row + 1) * w + __umul64hi(un1, w);
+    hit[0] = top_search_lds(pre, n_top, total, point);
   }
 
   bool clamped = false;
@@ -1302,16 +1308,9 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
     if (a.next_prio) q_next = quantise_priority(prio_next, a.qp, &clamped);
     head_slot = head % rd.P;
   };
-  Drawn dr[2];
-  if (second) {
-    walk_down<2>(rd, hit, dr, between);
-  } else {
-    const TopHit h1[1] = {hit[0]};
-    Drawn d1[1];
-    walk_down<1>(rd, h1, d1, between);
-    dr[0] = d1[0];
-    dr[1] = Drawn{~0ull, 0};
-  }
+  Drawn dr[1];
+  walk_down<1>(rd, hit, dr, between);
+  const bool next_has_same_slot = second && next_point - point < dr[0].mass - dr[0].x;
   // Outputs first, atomics last: nothing that the compiler makes wait for an atomic's completion follows them.
   // (The small payload columns of the drawn batch are gathered by the launch that copies its rows.)
   if (lane == 0) {
@@ -1321,7 +1320,7 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
     mass_out[row] = dr[0].mass;
     if (a.next_prio) {
       // the change this pair brings: none if the next pair has the same slot (the later one counts)
-      const uint64_t delta = dr[1].slot != slot ? q_next - dr[0].mass : 0;
+      const uint64_t delta = next_has_same_slot ? 0 : q_next - dr[0].mass;
       dq_out[row] = delta;
       add_to_written_copy(slot, delta);
       if (clamped) atomic_add_u64(&a.st->n_clamped, 1);
