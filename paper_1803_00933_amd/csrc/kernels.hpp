@@ -1462,12 +1462,13 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
   // One store at a time per wave (a wave waits for its last store before it issues the next): with a wave's
   // four stores in flight together the launch took 0.3 - 0.8 us longer, and with every piece stored as soon
   // as it had arrived (the row's writes beside the rest of its reads) 0.2 - 0.5 us longer (each measured
-  // against this on one box).
+  // against this on one box).  Ordinary stores, streaming loads: streaming stores, which such a wave waits
+  // for longer, cost 0.4 us per launch; ordinary loads of the rows cost 1.5.
 #pragma unroll
   for (int u = 0; u < kUnroll; ++u) {
     const uint32_t v = tid - first + u * copiers;
     if (u > 0 && v - lane < a.vecs_per_row) wait_for_all_loads();  // the same for all lanes of the wave
-    if (v < a.vecs_per_row) __builtin_nontemporal_store(tmp[u], d + v);
+    if (v < a.vecs_per_row) d[v] = tmp[u];
   }
 
   // ---- what the side jobs write
