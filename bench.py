@@ -31,7 +31,7 @@ ADD_EVERY, EVICT_EVERY = 25, 100
 # (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads for a
 # plain 508,032,000-byte copy in the same run (FETCH_SIZE reads half the bytes, WRITE_SIZE all):
 #   (7842.96 * 1.99991 + 14434.31 * 1.0) KiB.   See profiles/learner_step_atari_hbm_traffic.txt.
-MEASURED_STEP_TRAFFIC_BYTES = int((7625.406 * 496125.0 / 248074.09 + 14446.575) * 1024)
+MEASURED_STEP_TRAFFIC_BYTES = int((7647.976 * 496125.0 / 248074.09 + 14321.975) * 1024)
 STEP_ALGORITHMIC_BYTES = 512 * 57030   # per learner step of batch 512: gather read + write, sample outputs,
                                        # descent reads, update read-modify-writes (57,030 B per transition)
 
