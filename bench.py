@@ -27,13 +27,52 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 ADD_EVERY, EVICT_EVERY = 25, 100
 
-# HBM bytes per launch of the learner-step kernel, from two rocprofv3 --pmc runs of this script
-# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch), each scaled by what the same counter reads for a
-# plain 508,032,000-byte copy in the same run (FETCH_SIZE reads half the bytes, WRITE_SIZE all):
-#   (7842.96 * 1.99991 + 14434.31 * 1.0) KiB.   See profiles/learner_step_atari_hbm_traffic.txt.
-MEASURED_STEP_TRAFFIC_BYTES = int((7647.976 * 496125.0 / 248074.09 + 14321.975) * 1024)
-STEP_ALGORITHMIC_BYTES = 512 * 57030   # per learner step of batch 512: gather read + write, sample outputs,
-                                       # descent reads, update read-modify-writes (57,030 B per transition)
+# One byte model for every HBM fraction in the output line: what the method itself has to move per sampled
+# transition of this workload -- gather read + write 2 * (28,224 + 4 + 8), sample outputs and uniform 24,
+# descent reads 8 * 21, update read-modify-writes 16 * 22 + 12 = 57,030 B -- times the batch of 512.
+STEP_ALGORITHMIC_BYTES = 512 * 57030
+
+# HBM traffic of one launch of the learner-step kernel as the hardware counters saw it.  A RECORDED figure, not
+# measured by this run: two `rocprofv3 --pmc` runs of this script (FETCH_SIZE, then WRITE_SIZE; KiB per
+# dispatch, averaged over the kernel's dispatches), each scaled by what the same counter reads for the plain
+# 508,032,000-byte payload copy of an add round in the same run (FETCH_SIZE: 248,074.09 KiB for 496,125 KiB
+# read, factor 1.9999; WRITE_SIZE: factor 1.0).  Source: profiles/learner_step_atari_hbm_traffic.txt.
+RECORDED_STEP_TRAFFIC = {
+    "fetch_kib_per_dispatch": 7647.976, "fetch_scale": 496125.0 / 248074.09,
+    "write_kib_per_dispatch": 14321.975, "write_scale": 1.0,
+    "source": "profiles/learner_step_atari_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, recorded; "
+              "not re-measured by this run)",
+}
+RECORDED_STEP_TRAFFIC_BYTES = int((RECORDED_STEP_TRAFFIC["fetch_kib_per_dispatch"] * RECORDED_STEP_TRAFFIC["fetch_scale"]
+                                   + RECORDED_STEP_TRAFFIC["write_kib_per_dispatch"]
+                                   * RECORDED_STEP_TRAFFIC["write_scale"]) * 1024)
+
+
+def normalise_steps(steps, warmup):
+    """(K, W) that are actually run for the requested --steps / --warmup.
+
+    The timed schedule is periodic in EVICT_EVERY learner steps (four add rounds and one eviction, after which
+    the memory is back at its capacity), and the graph-replay variant records exactly one such cycle, so both
+    counts are rounded UP to whole cycles: 20 -> 100, 5 -> 100, 2000 -> 2000, 0 warm-up steps stay 0."""
+    if steps < 1 or warmup < 0:
+        raise ValueError("--steps must be >= 1 and --warmup >= 0")
+    up = lambda v: -(-v // EVICT_EVERY) * EVICT_EVERY
+    return up(steps), up(warmup)
+
+
+def host_cpu():
+    """(model name, logical cores) of the machine this runs on."""
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.lower().startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return model, os.cpu_count()
+
 
 def dev(a):
     import torch
@@ -680,8 +719,9 @@ def codec_numbers(log):
     return res
 
 
-def cpu_baseline(w, budget_steps, log):
-    """The oracle, untouched, on one host core: same schedule, bounded number of steps."""
+def cpu_baseline(w, budget_steps, budget_seconds, log):
+    """The oracle, untouched, on one host core: same schedule, bounded sample -- whole cycles of EVICT_EVERY
+    steps until budget_seconds have passed, at most budget_steps."""
     import oracle
     from paper_1803_00933_amd import synth
     payload_slots = 1 << 15                      # frame rows aliased modulo 32768 slots (0.9 GB): timing only
@@ -696,10 +736,9 @@ def cpu_baseline(w, budget_steps, log):
     rounds = [synth.actor_round(w, i) for i in range(2)]
     rnd = [synth.uniforms(w.seed, s, 1, w.k).reshape(-1) for s in range(budget_steps)]
     td = [synth.priorities(w.td_dist, w.seed, s, w.k) for s in range(budget_steps)]
-    t0 = time.perf_counter()
-    for s in range(budget_steps):
-        rc, out = o.sample(1, w.k, w.beta, rnd[s])
-        o.update_priorities(out["key"], td[s])
+    def step(s):
+        rc, out = o.sample(1, w.k, w.beta, rnd[s % len(rnd)])
+        o.update_priorities(out["key"], td[s % len(td)])
         if (s + 1) % ADD_EVERY == 0:
             d = rounds[(s // ADD_EVERY) % 2]
             prio, ret, gacc, _ = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"],
@@ -707,42 +746,72 @@ def cpu_baseline(w, budget_steps, log):
             o.add(prio.reshape(-1), obs, d["act"], ret.reshape(-1), gacc.reshape(-1))
         if (s + 1) % EVICT_EVERY == 0:
             o.evict()
+
+    for s in range(EVICT_EVERY):                 # one untimed cycle: first touch of the payload pages
+        step(s)
+    t0 = time.perf_counter()
+    done = 0
+    for s in range(budget_steps):
+        if s % EVICT_EVERY == 0 and s and time.perf_counter() - t0 >= budget_seconds:
+            break
+        done = s + 1
+        step(EVICT_EVERY + s)
     dt = time.perf_counter() - t0
-    log("cpu oracle: %d steps in %.2f s" % (budget_steps, dt))
+    budget_steps = done
+    model, nproc = host_cpu()
+    log("cpu oracle: %d steps in %.2f s on one core of %d (%s)" % (budget_steps, dt, nproc, model))
     return {"value": w.k * budget_steps / dt, "unit": "transitions/s", "cores": 1, "kind": "oracle",
-            "sample": "%d learner steps of the same schedule (batch %d, add round every %d steps, evict every %d); "
-                      "tree and keys at full size, frame rows aliased modulo %d slots to fit host memory"
-                      % (budget_steps, w.k, ADD_EVERY, EVICT_EVERY, payload_slots),
+            "cpu_model": model, "host_logical_cores": nproc,
+            "sample": "%d learner steps of the same schedule (batch %d, add round every %d steps, evict every %d) "
+                      "after one untimed cycle, single thread; tree and keys at full size, frame rows aliased modulo %d slots to fit host "
+                      "memory" % (budget_steps, w.k, ADD_EVERY, EVICT_EVERY, payload_slots),
             "seconds": dt}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=2000)
-    ap.add_argument("--warmup", type=int, default=200)
-    ap.add_argument("--cpu-steps", type=int, default=2000, help="learner steps timed on the CPU oracle (0 = skip)")
-    ap.add_argument("--no-control", action="store_true", help="skip the measurements of the other workload shapes")
+    ap.add_argument("--steps", type=int, default=2000,
+                    help="learner steps to time; rounded up to whole cycles of %d (the schedule's period)" % EVICT_EVERY)
+    ap.add_argument("--warmup", type=int, default=200, help="untimed steps before them; rounded up the same way")
+    ap.add_argument("--cpu-steps", type=int, default=8000,
+                    help="most learner steps timed on the CPU oracle (0 = skip) ...")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0,
+                    help="... which stops at the first whole cycle after this many seconds")
+    ap.add_argument("--extras", choices=("auto", "on", "off"), default="auto",
+                    help="the other workload shapes and library features beside the headline (control, skew, scale, "
+                         "learner-side priorities, prioritized eviction, observation codec: two to three minutes more). "
+                         "auto: only when at least 1000 steps are asked for")
+    ap.add_argument("--no-control", action="store_true", help="same as --extras off")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU (the replay memory lives in one MI355X's HBM); "
               "--gpus %d is not supported" % args.gpus, file=sys.stderr)
         sys.exit(2)
+    try:
+        K, W = normalise_steps(args.steps, args.warmup)       # before anything is allocated
+    except ValueError as e:
+        print("bench.py: %s" % e, file=sys.stderr)
+        sys.exit(2)
+    extras = not args.no_control and (args.extras == "on" or (args.extras == "auto" and args.steps >= 1000))
 
     def log(msg):
         if not args.quiet:
             print("[bench] " + msg, file=sys.stderr, flush=True)
 
+    t_start = time.time()
     import torch
     from paper_1803_00933_amd import synth
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     w = synth.WORKLOADS["atari"]
-    K, W = args.steps, args.warmup
+    if (K, W) != (args.steps, args.warmup):
+        log("--steps %d --warmup %d run as %d timed steps after %d of warm-up (whole cycles of %d)"
+            % (args.steps, args.warmup, K, W, EVICT_EVERY))
     torch.cuda.set_stream(torch.cuda.Stream())      # plain calls go to an ordinary stream, not the null stream
-    job = GpuJob(w, W + 2 * K, log)
+    K_roof = max(K, 1000)                           # launches behind the roofline figure (learner-only loop)
+    job = GpuJob(w, max(W + 2 * K, W + K_roof), log)
 
-    assert K % EVICT_EVERY == 0 and W % EVICT_EVERY == 0, "steps and warmup must be multiples of %d" % EVICT_EVERY
     job.setup_pipeline()
     job.run(0, W)
     # (1) every call on one stream, in order
@@ -751,17 +820,19 @@ def main():
     dt_learner, _ = job.timed(lambda: job.run(W + K, K, with_actors=False))
     log("one stream, learner steps only: %.2f us/step" % (dt_learner / K * 1e6))
     # (2) the library's pipeline (one launch per learner step; add payloads on a second stream)
+    job.run_pipelined(0, EVICT_EVERY)               # one untimed cycle in this launch mode
     dt_pipe, host_pipe, reps_pipe = job.timed_median(lambda: job.run_pipelined(W, K))
     log("pipeline, two streams: %.2f us/step, median of %d runs (%s; host enqueue %.2f us/step)"
         % (dt_pipe / K * 1e6, len(reps_pipe), " ".join("%.2f" % (t / K * 1e6) for t in reps_pipe), host_pipe / K * 1e6))
-    dt_pipe_learner, _, _ = job.timed_median(lambda: job.run_pipelined_learner_only(W + K, K))
+    dt_pipe_learner, _, _ = job.timed_median(lambda: job.run_pipelined_learner_only(W, K))
     log("pipeline, learner steps only: %.2f us/step (median of 5)" % (dt_pipe_learner / K * 1e6))
     dt_in_place, _, _ = job.timed_median(lambda: job.run_pipelined(W, K, in_place=True))
     log("pipeline, observations of the add rounds written in place by their producer (no copy): %.2f us/step"
         % (dt_in_place / K * 1e6))
-    us_codec = codec_schedule_us(job, K, log) if not args.no_control else None
-    us16 = job.prefetch16_us_per_batch(K, with_actors=False)
-    us16_full = job.prefetch16_us_per_batch(K, with_actors=True)
+    us_codec = codec_schedule_us(job, K, log) if extras else None
+    K16 = max(K, 400) // 16 * 16
+    us16 = job.prefetch16_us_per_batch(K16, with_actors=False)
+    us16_full = job.prefetch16_us_per_batch(K16, with_actors=True)
     log("pipeline, 16 batches of 512 per call: %.2f us per batch learner only, %.2f with adds and eviction"
         % (us16, us16_full))
     mode, dt = "apex_pipeline: two streams, eager launches", dt_pipe
@@ -779,25 +850,29 @@ def main():
     assert st["size"] == w.capacity, st
     log("state after run: %s" % st)
 
-    step_us = job.step_kernel_us(W, K)
-    gather_bytes = 2 * w.k * w.obs_bytes                       # read + write of one batch of frame stacks
-    achieved = gather_bytes / (step_us * 1e-6) / 1e9
-    log("learner-step kernel: %.2f us/launch, %.0f GB/s" % (step_us, achieved))
+    step_us = job.step_kernel_us(W, K_roof)
+    achieved = STEP_ALGORITHMIC_BYTES / (step_us * 1e-6) / 1e9
+    log("learner-step kernel: %.2f us/launch over %d launches, %.0f GB/s of algorithmic bytes"
+        % (step_us, K_roof, achieved))
 
     ops = op_timings(job)
     log("other steps alone, us: %s" % {k: round(v, 2) for k, v in ops.items()})
     del job
     torch.cuda.empty_cache()
-    control = control_numbers(log) if not args.no_control else None
-    tree_bound = tree_bound_workloads(log) if not args.no_control else None
-    next_rows = next_row_numbers(log) if not args.no_control else None
-    cpu = cpu_baseline(w, args.cpu_steps, log) if args.cpu_steps > 0 else None
+    control = control_numbers(log) if extras else None
+    tree_bound = tree_bound_workloads(log) if extras else None
+    next_rows = next_row_numbers(log) if extras else None
+    cpu = cpu_baseline(w, args.cpu_steps, args.cpu_seconds, log) if args.cpu_steps > 0 else None
+
+    def frac(us):
+        return STEP_ALGORITHMIC_BYTES / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
 
     line = {
         "metric": "sampled transitions/s (sample+IS+gather+update) at 2M slots, batch 512",
         "value": w.k * K / dt,
         "unit": "transitions/s",
         "n_gpus": 1, "steps": K, "warmup": W,
+        "steps_requested": args.steps, "warmup_requested": args.warmup,
         "ms_per_step": dt / K * 1e3,
         "higher_is_better": True,
         "scaling": "weak",
@@ -808,7 +883,9 @@ def main():
                                "beta 0.4, batch 512; add round of 360x50 every 25 steps, FIFO evict every 100",
                    "capacity": w.capacity, "max_slots": w.max_slots, "obs_bytes": w.obs_bytes, "batch": w.k,
                    "add_round": w.add_count, "add_every": ADD_EVERY, "evict_every": EVICT_EVERY,
-                   "launch_mode": mode},
+                   "launch_mode": mode,
+                   "steps_note": "steps and warmup are what was run: the requested counts rounded up to whole "
+                                 "cycles of %d steps, the period of the schedule" % EVICT_EVERY},
         "priority_updates_per_s": w.k * K / dt,
         "adds_per_s": w.add_count * (K // ADD_EVERY) / dt,
         "nstep_priorities_per_s": w.add_count / (ops["nstep_priorities_18000"] * 1e-6),
@@ -818,19 +895,23 @@ def main():
                         "pipeline_us_per_step": [t / K * 1e6 for t in reps_pipe],
                         "pipeline_graph_us_per_step": [t / K * 1e6 for t in reps_graph]},
         "variants_us_per_step": {"one_stream": dt_serial / K * 1e6, "one_stream_learner_only": dt_learner / K * 1e6,
-                                 "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6, "pipeline_graph": dt_graph / K * 1e6,
+                                 "pipeline": dt_pipe / K * 1e6, "pipeline_learner_only": dt_pipe_learner / K * 1e6,
+                                 "pipeline_graph": dt_graph / K * 1e6,
                                  "pipeline_add_payload_in_place": dt_in_place / K * 1e6,
                                  "pipeline_16_batches_per_call_learner_only": us16,
                                  "pipeline_16_batches_per_call": us16_full},
-        "hbm_frac_of_step": {name: STEP_ALGORITHMIC_BYTES / (us * 1e-6) / 1e9 / HBM_PEAK_GBS
-                             for name, us in (("pipeline_learner_only", dt_pipe_learner / K * 1e6),
-                                              ("pipeline_16_batches_per_call_learner_only", us16))},
+        "hbm_frac_of_step": {"bytes_per_step": STEP_ALGORITHMIC_BYTES,
+                             "pipeline_learner_only": frac(dt_pipe_learner / K * 1e6),
+                             "pipeline_16_batches_per_call_learner_only": frac(us16)},
         "roofline": {"bound": "hbm", "kernel": "learner_step_kernel<u32x4,512,4,1,0> (gather of one batch of frame "
                                                "stacks + IS weights + priority write-back + draw of the next "
                                                "batch; distinct rows every launch)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_STEP_TRAFFIC_BYTES, "bytes_per_launch": gather_bytes,
-                     "us_per_launch": step_us},
+                     "traffic": RECORDED_STEP_TRAFFIC_BYTES, "traffic_source": RECORDED_STEP_TRAFFIC["source"],
+                     "bytes_per_launch": STEP_ALGORITHMIC_BYTES, "bytes_model": "512 x 57,030 B per sampled transition",
+                     "us_per_launch": step_us, "launches_timed": K_roof,
+                     "timing": "HIP events around back-to-back launches of the learner-only loop: launch to "
+                               "launch, gaps included"},
         "roofline_add_payload": {"bound": "hbm", "kernel": "copy_rows_dense_kernel<u32x4,2> (18,000 frame stacks "
                                                            "of an add round into the ring)",
                                  "achieved": ops["add_payload_GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -840,7 +921,9 @@ def main():
         "control_workload": control,
         "tree_bound_workloads": tree_bound,
         "next_rows": next_rows,
+        "extras_run": extras,
         "cpu_baseline": cpu,
+        "wall_seconds": time.time() - t_start,
     }
     print(json.dumps(line), flush=True)
 

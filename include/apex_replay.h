@@ -372,6 +372,10 @@ int apex_pipeline_join(apex_pipeline_t *p, void *stream);
  * step draws.  *first_set_out (host, may be NULL) receives the index of the set
  * the first of these steps fills.  With the one-launch-per-step form the payload columns of a
  * set are complete when the launch after its draw has run, i.e. once the call's work is done.
+ * Returns what apex_replay_sample returns for the same memory: APEX_ERR_NOT_READY below
+ * min_size_to_sample, APEX_ERR_EMPTY if nothing is stored (decided from the host's mirror of head and
+ * tail; none of the n steps has been enqueued then), APEX_ERR_INVALID_ARG for a NULL rnd or a beta
+ * outside [0, 1].
  */
 int apex_pipeline_steps(apex_pipeline_t *p, uint32_t n, float beta, const uint64_t *rnd, const float *new_prio,
                         uint32_t *first_set_out);

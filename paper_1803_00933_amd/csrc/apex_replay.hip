@@ -714,6 +714,11 @@ int fused_steps(apex_replay *r, uint32_t n, uint32_t k, float beta, const uint64
                 const apex_batch_buffers_t *sets, uint32_t depth, uint32_t first_set, HeldStep *hold,
                 uint32_t codec_raw_bytes, hipStream_t stream)
 {
+  // The same gate as apex_replay_sample, from the host mirror and before anything is enqueued: a draw from an
+  // empty tree has no defined result (every stratum has width 0), and the learner waits for a minimum fill.
+  const uint64_t size = r->tail - r->head;
+  if (size < r->cfg.min_size_to_sample) return APEX_ERR_NOT_READY;
+  if (size == 0) return APEX_ERR_EMPTY;
   const auto idx = [&](uint32_t i) { return (first_set + i) % depth; };
   const auto set = [&](uint32_t i) -> const apex_batch_buffers_t & { return sets[idx(i)]; };
   const apex_batch_buffers_t &b0 = set(0);

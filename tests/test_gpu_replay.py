@@ -183,6 +183,47 @@ def test_status_codes():
     check_gpu_tree(g, o)
 
 
+@pytest.mark.parametrize("P,C", [(128, 100), (1 << 20, 1_000_000)])   # the larger shape has a top level of 256 nodes
+def test_fused_steps_refuse_an_empty_or_unready_memory(P, C):
+    """Learner steps as one launch each obey the same gate as apex_replay_sample: nothing stored -> EMPTY, fewer
+    than min_size_to_sample -> NOT_READY, with or without priorities to write back, and nothing is enqueued
+    (tree, counters and buffers stay as they were)."""
+    from paper_1803_00933_amd import apex
+    rng = np.random.default_rng(17)
+    k = 8
+    rnd, newp = dev(rng.integers(0, U64, (3, k), dtype=np.uint64)), dev(rng.random((3, k)).astype(F32))
+    for min_size, fill, want in ((0, 0, apex.ERR_EMPTY), (50, 0, apex.ERR_NOT_READY), (50, 49, apex.ERR_NOT_READY)):
+        g, o = make_pair(C, P, 16, 4, min_size_to_sample=min_size)
+        if fill:
+            assert add_both(g, o, rng, fill) == 0
+        pipe = apex.Pipeline(g, 4, 1, k)
+        for s_ in pipe.sets:
+            s_["slot"].fill_(-7)
+        torch.cuda.synchronize()
+        before = g.stats()
+        assert o.sample(1, k, 0.4, np.zeros(k, np.uint64))[0] == want
+        assert pipe.fork() == 0
+        assert pipe.steps(3, 0.4, rnd, newp)[0] == want
+        assert pipe.steps(3, 0.4, rnd, None)[0] == want
+        assert pipe.join() == 0
+        torch.cuda.synchronize()
+        assert g.stats() == before
+        assert all(int((s_["slot"] != -7).sum()) == 0 for s_ in pipe.sets)
+        check_gpu_tree(g, o)
+        if fill:                                   # one more transition and the same call goes through
+            assert add_both(g, o, rng, 1) == 0
+            assert pipe.fork() == 0
+            rc, first = pipe.steps(3, 0.4, rnd, newp)
+            assert rc == apex.OK and pipe.join() == 0
+            torch.cuda.synchronize()
+            for i in range(3):
+                rco, oo = o.sample(1, k, 0.4, host(rnd[i], np.uint64))
+                assert rco == 0 and o.update_priorities(oo["key"], host(newp[i])) == 0
+                assert_sample_equal(pipe.sets[(first + i) % 4], oo)
+            check_gpu_tree(g, o)
+        pipe.close()
+
+
 def test_tiny_workload_full_trace():
     """The small configuration end to end: 200 rounds of {n-step priorities, add 400, sample 32,
     update with fresh |N(0,1)| errors, evict}; every output of every round is compared."""
