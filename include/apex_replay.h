@@ -60,6 +60,7 @@ typedef enum apex_status {
 #define APEX_MAX_SAMPLES_PER_CALL 65536u
 #define APEX_MAX_BATCHES_PER_CALL 1024u
 #define APEX_TREE_MAX_LEVELS 8u
+#define APEX_NOALLOC_MAX_SAMPLES 16384u /* num_batches * k of apex_replay_sample_noalloc */
 
 typedef struct apex_replay apex_replay_t; /* opaque host object; created and destroyed by the library */
 
@@ -194,6 +195,26 @@ int apex_replay_add_publish(apex_replay_t *r, uint64_t count, const float *prio,
 int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
                        uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
                        float *ret_out, float *gacc_out, void *hip_stream);
+
+/*
+ * apex_replay_sample for callers that cannot allocate device memory and do not want the call to touch
+ * the memory's scratch region: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same arguments, same results, same status codes as apex_replay_sample, with two
+ * differences:
+ *   - the per-call temporary (the mass of every drawn transition, which the draw writes and the
+ *     importance weights read) lives in an array that is part of the library's code object:
+ *     APEX_NOALLOC_MAX_SAMPLES * 8 bytes = 128 KB on every GPU the library runs on, held until the
+ *     process ends.  Its device address is looked up once per GPU (by apex_replay_create on the GPU
+ *     that is current then; else by the first call).  The call allocates nothing and frees nothing;
+ *   - num_batches * k > APEX_NOALLOC_MAX_SAMPLES is refused with APEX_ERR_TOO_LARGE, nothing enqueued.
+ * The GPU that holds the memory must be current in the calling thread (as for every call).  All calls
+ * on one GPU share that GPU's array, whatever memory object or stream they name: two calls whose work
+ * overlaps in time on one GPU race on it (order them on one stream or by an event); a later call simply
+ * overwrites what an earlier one left, nothing has to start at zero.
+ */
+int apex_replay_sample_noalloc(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                               uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out,
+                               void *act_out, float *ret_out, float *gacc_out, void *hip_stream);
 
 /*
  * The two halves of apex_replay_sample, for callers that run the large copy on another stream

@@ -17,11 +17,12 @@ STATUS_NAMES = {0: "APEX_OK", -1: "APEX_ERR_INVALID_ARG", -2: "APEX_ERR_FULL", -
                 -4: "APEX_ERR_EMPTY", -5: "APEX_ERR_HIP", -6: "APEX_ERR_TOO_LARGE"}
 MAX_SAMPLES_PER_CALL = 65536
 MAX_BATCHES_PER_CALL = 1024
+NOALLOC_MAX_SAMPLES = 16384
 TREE_MAX_LEVELS = 8
 
 EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_destroy", "apex_replay_layout",
            "apex_nstep_priorities", "apex_replay_add", "apex_replay_add_payload", "apex_replay_add_publish",
-           "apex_replay_sample", "apex_replay_sample_begin", "apex_replay_sample_finish",
+           "apex_replay_sample", "apex_replay_sample_noalloc", "apex_replay_sample_begin", "apex_replay_sample_finish",
            "apex_replay_sample_finish_update", "apex_replay_sample_finish_writeback", "apex_replay_gather",
            "apex_replay_update_priorities", "apex_replay_update_from_q", "apex_replay_evict", "apex_replay_resync", "apex_replay_stats",
            "apex_last_hip_error", "apex_pipeline_create", "apex_pipeline_destroy", "apex_pipeline_fork",
@@ -87,6 +88,7 @@ lib.apex_nstep_priorities.argtypes = [_u32, _u32, _u32, _u32, _vp, _vp, _vp, _vp
                                       _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_add.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp, C.POINTER(_u64), _vp]
 lib.apex_replay_sample.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+lib.apex_replay_sample_noalloc.argtypes = lib.apex_replay_sample.argtypes
 lib.apex_replay_add_payload.argtypes = [_vp, _u64, _vp, _vp, _vp, _vp, _vp]
 lib.apex_replay_add_publish.argtypes = [_vp, _u64, _vp, C.POINTER(_u64), _vp]
 lib.apex_replay_sample_begin.argtypes = [_vp, _u32, _u32, _vp, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
@@ -245,6 +247,13 @@ class Replay:
                                     _ptr(out.get("weight")), _ptr(out.get("obs")), _ptr(out.get("act")),
                                     _ptr(out.get("ret")), _ptr(out.get("gacc")), _stream(stream))
         return rc, out
+
+    def sample_noalloc(self, num_batches, k, beta, rnd, out, stream=None):
+        """apex_replay_sample_noalloc into caller-made outputs (see alloc_sample_outputs)."""
+        return lib.apex_replay_sample_noalloc(self.h, num_batches, k, beta, _ptr(rnd), _ptr(out.get("key")),
+                                              _ptr(out["slot"]), _ptr(out.get("weight")), _ptr(out.get("obs")),
+                                              _ptr(out.get("act")), _ptr(out.get("ret")), _ptr(out.get("gacc")),
+                                              _stream(stream))
 
     def add_payload(self, count, obs=None, act=None, ret=None, gacc=None, stream=None):
         return lib.apex_replay_add_payload(self.h, count, _ptr(obs), _ptr(act), _ptr(ret), _ptr(gacc), _stream(stream))

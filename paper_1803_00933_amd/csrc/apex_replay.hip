@@ -5,12 +5,19 @@
 
 #include <hip/hip_runtime.h>
 
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "kernels.hpp"
 
 using namespace apex;
+
+// Scratch of apex_replay_sample_noalloc: the masses of the drawn transitions between the descent
+// and the weights.  One copy per GPU, held until the process ends.  In host code this name is only
+// a handle for hipGetSymbolAddress: the device address it yields (static_scratch_ptr) is what goes
+// into kernel arguments.
+static __device__ __align__(256) uint64_t scratch[APEX_NOALLOC_MAX_SAMPLES];
 
 namespace {
 
@@ -27,6 +34,26 @@ inline bool hip_failed(hipError_t e)
   do {                                         \
     if (hip_failed((call))) return APEX_ERR_HIP; \
   } while (0)
+
+// The device address of `scratch` on the GPU that is current in the calling thread: looked up once per
+// device (each GPU holds its own copy of the array at its own address) and kept.  Null, with the
+// error recorded, if the lookup fails.
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+uint64_t *g_scratch_ptr[kMaxDevices] = {};
+
+uint64_t *static_scratch_ptr()
+{
+  int dev = -1;
+  if (hip_failed(hipGetDevice(&dev)) || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hip_failed(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch))) || !ptr) return nullptr;
+    g_scratch_ptr[dev] = static_cast<uint64_t *>(ptr);
+  }
+  return g_scratch_ptr[dev];
+}
 
 inline uint64_t round_up(uint64_t v, uint64_t a) { return (v + a - 1) / a * a; }
 inline uint32_t blocks_for(uint64_t n, uint32_t per) { return (uint32_t)((n + per - 1) / per); }
@@ -430,6 +457,11 @@ int apex_replay_create(const apex_replay_config_t *cfg, void *d_storage, void *d
   r->tv2 = r->tv;
   for (uint32_t l = 0; l < r->geo.nlev; ++l) r->tv2.level[l] = r->tv.level[l] + r->geo.tree_words;
 
+  // set-up for apex_replay_sample_noalloc on this GPU, so that the call itself has nothing left to look up
+  if (!static_scratch_ptr()) {
+    delete r;
+    return APEX_ERR_HIP;
+  }
   fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(r->tree, 2 * r->geo.tree_words);
   fill_zero_kernel<<<dim3(1024), dim3(256), 0, nullptr>>>(reinterpret_cast<uint64_t *>(r->scratch),
                                                           r->geo.scratch_bytes / 8);
@@ -863,6 +895,21 @@ int apex_replay_sample(apex_replay_t *r, uint32_t num_batches, uint32_t k, float
   if (rc != APEX_OK) return rc;
   if (!weight_out && !obs_out) return APEX_OK;
   return apex_replay_sample_finish(r, num_batches, k, beta, slot_out, r->mass(), weight_out, obs_out, hip_stream);
+}
+
+int apex_replay_sample_noalloc(apex_replay_t *r, uint32_t num_batches, uint32_t k, float beta, const uint64_t *rnd,
+                               uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
+                               float *ret_out, float *gacc_out, void *hip_stream)
+{
+  if (!r || !(beta >= 0.0f) || !(beta <= 1.0f)) return APEX_ERR_INVALID_ARG;
+  if (num_batches && k && (uint64_t)num_batches * k > APEX_NOALLOC_MAX_SAMPLES) return APEX_ERR_TOO_LARGE;
+  uint64_t *const mass = static_scratch_ptr();  // this GPU's copy; every entry the weights read is written by the draw
+  if (!mass) return APEX_ERR_HIP;
+  const int rc = apex_replay_sample_begin(r, num_batches, k, rnd, key_out, slot_out, mass, act_out, ret_out, gacc_out,
+                                          hip_stream);
+  if (rc != APEX_OK) return rc;
+  if (!weight_out && !obs_out) return APEX_OK;
+  return apex_replay_sample_finish(r, num_batches, k, beta, slot_out, mass, weight_out, obs_out, hip_stream);
 }
 
 int apex_replay_gather(apex_replay_t *r, uint64_t count, const uint32_t *slot, void *obs_out, void *act_out,
