@@ -719,6 +719,42 @@ def codec_numbers(log):
     return res
 
 
+def profile_loop(job, n, log):
+    """--profile-loop: only the launches that the rocprofv3 passes under profiles/ look at, each kind n times
+    with other rows or uniforms every time, so that per-kernel averages of counters mean something:
+    (a) learner steps as one launch each (learner_step_kernel: gather + weights + write-back + next draw),
+    (b) plain gathers of 512 frame stacks (copy_rows_long_kernel, no side jobs),
+    (c) draws of 512 samples (sample_descent_kernel),
+    (d) gathers of 16 batches = 8192 frame stacks with their weights (copy_rows_long_kernel with weights)."""
+    torch, w, rep = job.torch, job.w, job.rep
+    job.setup_pipeline()
+    job.run_pipelined_learner_only(0, n)
+    torch.cuda.synchronize()
+    st = rep.stats()
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(1)
+    head_slot = st["head"] % w.max_slots
+    slots = ((torch.randint(0, st["size"], (n, w.k), device="cuda:0", generator=gen) + head_slot) % w.max_slots).to(torch.int32)
+    outs = [torch.empty((w.k, w.obs_bytes), dtype=torch.uint8, device="cuda:0") for _ in range(4)]
+    for i in range(n):
+        assert rep.gather(slots[i], obs=outs[i % 4]) == 0
+    torch.cuda.synchronize()
+    o = job.outs[0]
+    o["mass"] = torch.empty(w.k, dtype=torch.int64, device="cuda:0")
+    for i in range(n):
+        assert rep.sample_begin(1, w.k, job.rnd[i], o) == 0
+    torch.cuda.synchronize()
+    nb = 16
+    o16 = rep.alloc_sample_outputs(nb, w.k)
+    o16["mass"] = torch.empty(nb * w.k, dtype=torch.int64, device="cuda:0")
+    for c in range(max(1, n // nb)):
+        assert rep.sample_begin(nb, w.k, job.rnd[c * nb:(c + 1) * nb], o16) == 0
+        assert rep.sample_finish(nb, w.k, w.beta, o16) == 0
+    torch.cuda.synchronize()
+    log("profile loop: %d fused steps, %d gathers of %d rows, %d draws, %d gathers of %d rows"
+        % (n, n, w.k, n, max(1, n // nb), nb * w.k))
+
+
 def cpu_baseline(w, budget_steps, budget_seconds, log):
     """The oracle, untouched, on one host core: same schedule, bounded sample -- whole cycles of EVICT_EVERY
     steps until budget_seconds have passed, at most budget_steps."""
@@ -783,6 +819,9 @@ def main():
                          "learner-side priorities, prioritized eviction, observation codec: two to three minutes more). "
                          "auto: only when at least 1000 steps are asked for")
     ap.add_argument("--no-control", action="store_true", help="same as --extras off")
+    ap.add_argument("--profile-loop", type=int, default=0, metavar="N",
+                    help="after the prefill run only N launches of each kernel that the counter passes under "
+                         "profiles/ look at, print no result line (for use under rocprofv3)")
     ap.add_argument("--quiet", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -810,6 +849,9 @@ def main():
             % (args.steps, args.warmup, K, W, EVICT_EVERY))
     torch.cuda.set_stream(torch.cuda.Stream())      # plain calls go to an ordinary stream, not the null stream
     K_roof = max(K, 1000)                           # launches behind the roofline figure (learner-only loop)
+    if args.profile_loop > 0:
+        profile_loop(GpuJob(w, args.profile_loop, log), args.profile_loop, log)
+        return
     job = GpuJob(w, max(W + 2 * K, W + K_roof), log)
 
     job.setup_pipeline()

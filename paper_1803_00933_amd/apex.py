@@ -194,7 +194,7 @@ class Replay:
         self.layout = lay
 
     def close(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:     # (lib is None while the interpreter shuts down)
             lib.apex_replay_destroy(self.h)
             self.h = None
 
@@ -342,7 +342,7 @@ class Pipeline:
         self.h = h
 
     def close(self):
-        if getattr(self, "h", None):
+        if getattr(self, "h", None) and lib is not None:
             lib.apex_pipeline_destroy(self.h)
             self.h = None
 
