@@ -177,9 +177,20 @@ def obs_rows_torch(seed: int, first_key: int, count: int, obs_bytes: int, device
     """Same bytes as :func:`obs_rows`, produced on ``device`` with integer tensor ops
     (obs_bytes must be a multiple of 8)."""
     import torch
+    key = torch.arange(first_key, first_key + count, dtype=torch.int64, device=device)
+    return obs_rows_for_keys_torch(seed, key, obs_bytes, device)
+
+
+def obs_rows_for_keys_torch(seed: int, keys, obs_bytes: int, device):
+    """uint8 [len(keys), obs_bytes] on ``device``: row i holds the bytes of key keys[i] (any order, repeats allowed;
+    a numpy uint64 / int64 array or an int64 tensor).  The bytes of :func:`obs_rows` for the same keys."""
+    import torch
     assert obs_bytes % 8 == 0
     words = obs_bytes // 8
-    key = torch.arange(first_key, first_key + count, dtype=torch.int64, device=device)[:, None]
+    if not torch.is_tensor(keys):
+        keys = torch.from_numpy(np.ascontiguousarray(np.asarray(keys).astype(np.uint64)).view(np.int64))
+    key = keys.to(device=device, dtype=torch.int64).reshape(-1)[:, None]
+    count = key.shape[0]
     j = torch.arange(words, dtype=torch.int64, device=device)[None, :]
     z = key * _s64(_K1) + j * _s64(_K2) + _s64(seed)
 
@@ -192,3 +203,15 @@ def obs_rows_torch(seed: int, first_key: int, count: int, obs_bytes: int, device
     z = z * _s64(_M2)
     z = z ^ lsr(z, 31)
     return z.view(torch.uint8).reshape(count, obs_bytes)
+
+
+def frame_rows_for_keys_torch(seed: int, keys, obs_bytes: int, device, flat_per_256: int = 205):
+    """The bytes of :func:`frame_rows` for the keys given, produced on ``device``."""
+    import torch
+    assert obs_bytes % 64 == 0
+    rows = obs_rows_for_keys_torch(seed, keys, obs_bytes, device)
+    count = rows.shape[0]
+    rows = rows.reshape(count, obs_bytes // 64, 64)
+    flat = rows[:, :, 0] < flat_per_256
+    value = (rows[:, :, 1] & 7) * 31
+    return torch.where(flat[:, :, None], value[:, :, None], rows).reshape(count, obs_bytes).contiguous()

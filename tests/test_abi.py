@@ -66,3 +66,16 @@ def test_synthetic_observation_bytes_agree_between_numpy_and_torch():
     assert np.array_equal(a, b)
     assert len(np.unique(a)) > 200                                  # looks like uniform bytes
     assert np.array_equal(synth.obs_rows(7, (1 << 40) + 5, 2, 64), a[2:4])   # a pure function of the key
+
+
+def test_rows_for_scattered_keys_are_the_rows_of_those_keys():
+    import numpy as np
+    from paper_1803_00933_amd import synth
+    keys = np.array([5, (1 << 40) + 3, 5, 0, (1 << 63) + 17, 123456789], dtype=np.uint64)
+    got = synth.obs_rows_for_keys_torch(7, keys, 128, "cpu").numpy()
+    for i, k in enumerate(keys):
+        assert np.array_equal(got[i], synth.obs_rows(7, int(k), 1, 128)[0])
+    got = synth.frame_rows_for_keys_torch(7, keys, 128, "cpu").numpy()
+    for i, k in enumerate(keys):
+        assert np.array_equal(got[i], synth.frame_rows(7, int(k), 1, 128)[0])
+    assert np.array_equal(synth.frame_rows_torch(7, 40, 9, 256, "cpu").numpy(), synth.frame_rows(7, 40, 9, 256))

@@ -1,8 +1,13 @@
-"""GPU parity at the full sizes of the five workloads: the HIP library driven through its C ABI
-against the oracle on the same seeded inputs.  Indices, keys, tree sums and eviction are compared
-bit for bit at every step; weights to 1e-5 relative / 1e-6 absolute; observation bytes against
-their definition as a function of the key (the oracle keeps no 59 GB copy).
+"""GPU parity at the full sizes of the five workloads and over their full schedules: the HIP library
+driven through its C ABI against the oracle on the same seeded inputs.  Indices, keys, tree sums and
+eviction are compared bit for bit at every step; weights to 1e-5 relative / 1e-6 absolute; gathered
+observation rows, every row of a batch, against their definition as a function of the oracle's key (the
+oracle keeps no 59 GB copy; the rows are regenerated on the device from the keys it drew).
+APEX_TEST_SCHEDULE=short in the environment cuts the two long schedules (skew: 10,000 steps, scale: 5,000
+steps) to a tenth; the default runs them whole.
 """
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -12,6 +17,7 @@ from gpu_util import assert_close, check_gpu_tree, dev, host
 
 pytestmark = pytest.mark.gpu
 F32 = np.float32
+SHORT = os.environ.get("APEX_TEST_SCHEDULE", "") == "short"
 
 
 class Pair:
@@ -25,6 +31,7 @@ class Pair:
                                payload_slots=0)
         self.key0 = 0
         self.round = 0
+        self.rounds_from = None
 
     def add_round_nstep(self):
         """One round of S x T transitions: n-step priorities on both sides, then add."""
@@ -62,58 +69,79 @@ class Pair:
         assert a == b
         return a[1]
 
+    def content_keys(self, key):
+        """The key whose bytes a stored row holds.  Rows added through this class hold the bytes of their own key;
+        rounds_from names the first key of a run of add rounds that all carried the rows of keys 0 .. add_count-1
+        (the staging buffer that the pipeline tests re-use)."""
+        key = np.asarray(key).astype(np.uint64)
+        if self.rounds_from is None:
+            return key
+        late = key >= np.uint64(self.rounds_from)
+        return np.where(late, (key - np.uint64(self.rounds_from)) % np.uint64(self.w.add_count), key)
+
     def check_obs(self, key, obs_out):
-        """Gathered rows are the bytes their keys define."""
+        """Every gathered row is the bytes that its key - the oracle's - defines; compared on the device."""
         from paper_1803_00933_amd import synth
         w = self.w
-        key = np.asarray(key)
-        for i in np.linspace(0, len(key) - 1, min(len(key), 24)).astype(int):
-            exp = synth.obs_rows(w.seed, int(key[i]), 1, w.obs_bytes)[0]
-            assert np.array_equal(host(obs_out[i]), exp), (i, int(key[i]))
+        key = self.content_keys(key)
+        assert obs_out.shape[0] == len(key)
+        for lo in range(0, len(key), 2048):                  # 2048 frame stacks = 58 MB of expected bytes at a time
+            exp = synth.obs_rows_for_keys_torch(w.seed, key[lo:lo + 2048], w.obs_bytes, "cuda:0")
+            if not torch.equal(obs_out[lo:lo + 2048], exp):
+                bad = (obs_out[lo:lo + 2048] != exp).any(dim=1).nonzero().reshape(-1)
+                raise AssertionError("gathered rows differ from their keys' bytes: rows %s of %d"
+                                     % ((bad[:8] + lo).tolist(), len(key)))
 
 
-def learner_steps(p, steps, nb, beta_of, add_every=0, evict_every=0, add_fn=None, check_obs_every=50):
-    """steps x {sample nb x k, update the drawn keys with fresh priorities} with no synchronisation in
-    between; every output is kept on the device and compared afterwards."""
+def learner_steps(p, steps, nb, beta_of, add_every=0, evict_every=0, add_fn=None, check_obs_every=50, chunk=500):
+    """steps x {sample nb x k, update the drawn keys with fresh priorities} with no synchronisation inside a
+    chunk of steps; every output is kept on the device and compared when the chunk is done (slots, keys, weights
+    of every step; every gathered row of every check_obs_every-th step).  Returns the number of samples that drew
+    a transition already drawn in the same call."""
     from paper_1803_00933_amd import synth
     w, g, o = p.w, p.g, p.o
     n = nb * w.k
-    keys = torch.empty((steps, n), dtype=torch.int64, device="cuda:0")
-    slots = torch.empty((steps, n), dtype=torch.int32, device="cuda:0")
-    wts = torch.empty((steps, n), dtype=torch.float32, device="cuda:0")
-    obs_keep = {}
-    ref = []
+    chunk = min(chunk, steps)
+    keys = torch.empty((chunk, n), dtype=torch.int64, device="cuda:0")
+    slots = torch.empty((chunk, n), dtype=torch.int32, device="cuda:0")
+    wts = torch.empty((chunk, n), dtype=torch.float32, device="cuda:0")
     scratch_obs = torch.empty((n, w.obs_bytes), dtype=torch.uint8, device="cuda:0")
     scratch_small = g.alloc_sample_outputs(nb, w.k)
-    for s in range(steps):
-        rnd = synth.uniforms(w.seed, s, nb, w.k).reshape(-1)
-        newp = synth.priorities(w.td_dist, w.seed, s, n)
-        beta = beta_of(s)
-        rco, oo = o.sample(nb, w.k, beta, rnd, payload=False)
-        assert rco == 0
-        assert o.update_priorities(oo["key"], newp) == 0
-        keep = s % check_obs_every == 0
-        obs_out = torch.empty_like(scratch_obs) if keep else scratch_obs
-        if keep:
-            obs_keep[s] = obs_out
-        out = dict(key=keys[s], slot=slots[s], weight=wts[s], obs=obs_out, act=scratch_small["act"],
-                   ret=scratch_small["ret"], gacc=scratch_small["gacc"])
-        assert g.sample(nb, w.k, beta, dev(rnd), out=out)[0] == 0
-        assert g.update_priorities(keys[s], dev(newp)) == 0
-        ref.append(oo)
-        if add_every and (s + 1) % add_every == 0:
-            add_fn()
-        if evict_every and (s + 1) % evict_every == 0:
-            p.evict()
-    torch.cuda.synchronize()
-    hk, hs, hw = host(keys, np.uint64), host(slots, np.uint32), host(wts)
-    for s, oo in enumerate(ref):
-        assert np.array_equal(hs[s], oo["slot"]), "slot, step %d" % s
-        assert np.array_equal(hk[s], oo["key"]), "key, step %d" % s
-        assert_close(hw[s], oo["weight"], "weight, step %d" % s)
-    for s, obs_out in obs_keep.items():
-        p.check_obs(ref[s]["key"], obs_out)
-    return ref
+    dup = 0
+    for c0 in range(0, steps, chunk):
+        obs_keep, ref = {}, []
+        for s in range(c0, min(c0 + chunk, steps)):
+            i = s - c0
+            rnd = synth.uniforms(w.seed, s, nb, w.k).reshape(-1)
+            newp = synth.priorities(w.td_dist, w.seed, s, n)
+            beta = beta_of(s)
+            rco, oo = o.sample(nb, w.k, beta, rnd, payload=False)
+            assert rco == 0
+            assert o.update_priorities(oo["key"], newp) == 0
+            keep = s % check_obs_every == 0
+            obs_out = torch.empty_like(scratch_obs) if keep else scratch_obs
+            if keep:
+                obs_keep[i] = obs_out
+            out = dict(key=keys[i], slot=slots[i], weight=wts[i], obs=obs_out, act=scratch_small["act"],
+                       ret=scratch_small["ret"], gacc=scratch_small["gacc"])
+            assert g.sample(nb, w.k, beta, dev(rnd), out=out)[0] == 0
+            assert g.update_priorities(keys[i], dev(newp)) == 0
+            ref.append(oo)
+            if add_every and (s + 1) % add_every == 0:
+                add_fn()
+            if evict_every and (s + 1) % evict_every == 0:
+                p.evict()
+        torch.cuda.synchronize()
+        hk, hs, hw = host(keys, np.uint64), host(slots, np.uint32), host(wts)
+        for i, oo in enumerate(ref):
+            assert np.array_equal(hs[i], oo["slot"]), "slot, step %d" % (c0 + i)
+            assert np.array_equal(hk[i], oo["key"]), "key, step %d" % (c0 + i)
+            assert_close(hw[i], oo["weight"], "weight, step %d" % (c0 + i))
+            dup += len(oo["key"]) - len(np.unique(oo["key"]))
+        for i, obs_out in obs_keep.items():
+            p.check_obs(ref[i]["key"], obs_out)
+        print("  steps %d..%d of %d checked" % (c0, c0 + len(ref) - 1, steps), flush=True)
+    return dup
 
 
 def final_checks(p):
@@ -172,8 +200,8 @@ def test_atari_shape_full_size():
             assert np.array_equal(host(g_["slot"], np.uint32), o_["slot"])
             assert np.array_equal(host(g_["key"], np.uint64), o_["key"])
             assert_close(host(g_["weight"]), o_["weight"], "weight")
-            idx = torch.from_numpy(o_["slot"][:32].astype(np.int64)).to("cuda:0")
-            assert torch.equal(g_["obs"][:32], p.g.obs_view()[idx])
+            if s % 6 == 0:                # all 512 rows of every sixth batch of the window
+                p.check_obs(o_["key"], g_["obs"])
         # the add round's payload (copied on the second stream) sits in the slots of its keys
         first = p.o.tail - w.add_count
         rows = np.linspace(0, w.add_count - 1, 97).astype(np.int64)
@@ -183,6 +211,7 @@ def test_atari_shape_full_size():
         assert torch.equal(p.g.act_view()[slots_new], dd["act"][rows_t])
         assert np.array_equal(host(p.g.ret_view()[slots_new]).view(np.uint32), ref_n[1].reshape(-1)[rows].view(np.uint32))
 
+    p.rounds_from = p.key0                # every round from here on carries the rows of keys 0 .. add_count-1
     torch.cuda.synchronize()
     for _ in range(6):                    # 150 learner steps and six add rounds, checked window by window
         assert pipe.fork() == 0
@@ -225,8 +254,7 @@ def test_atari_shape_full_size():
         assert np.array_equal(host(g_["slot"], np.uint32), o_["slot"])
         assert np.array_equal(host(g_["key"], np.uint64), o_["key"])
         assert_close(host(g_["weight"]), o_["weight"], "weight")
-        idx = torch.from_numpy(o_["slot"][::257].astype(np.int64)).to("cuda:0")
-        assert torch.equal(g_["obs"][::257], p.g.obs_view()[idx])
+        p.check_obs(o_["key"], g_["obs"])   # all 8192 rows of the call
         assert pipe.fork() == 0
     assert pipe.add_end(True)[0] == 0
     assert pipe.join() == 0
@@ -244,9 +272,8 @@ def test_priority_skew_full_size():
     p = Pair(w)
     p.add_bulk(w.max_slots, "pareto", 0)
     final_checks(p)
-    steps = 1200
-    ref = learner_steps(p, steps, w.num_batches, lambda s: 0.4 + 0.6 * s / (steps - 1), check_obs_every=400)
-    dup = sum(len(r["key"]) - len(np.unique(r["key"])) for r in ref)
+    steps = 1000 if SHORT else 10_000
+    dup = learner_steps(p, steps, w.num_batches, lambda s: 0.4 + 0.6 * s / (steps - 1), check_obs_every=400)
     assert dup > steps          # the skew does make samples collide
     final_checks(p)
 
@@ -351,10 +378,14 @@ def test_scale_stress_full_size():
         step += 1
     st = final_checks(p)
     assert st["size"] == w.capacity
-    learner_steps(p, 600, 1, lambda s: w.beta, add_every=8, evict_every=100, add_fn=p.add_round_nstep,
-                  check_obs_every=150)
+    steps = 500 if SHORT else 5000        # an add round of 51,200 every 8 steps: 625 rounds = 32,000,000 more
+    learner_steps(p, steps, 1, lambda s: w.beta, add_every=8, evict_every=100, add_fn=p.add_round_nstep,
+                  check_obs_every=150)    # transitions, 1.9 x the capacity on top of the prefill
     st = final_checks(p)
     assert st["n_clamped"] == p.o.n_clamped
+    if not SHORT:
+        assert st["tail"] == w.capacity + 625 * w.add_count and st["tail"] > 2 * w.max_slots   # the ring wrapped twice
+        assert st["head"] == st["tail"] - w.capacity - (steps % 100) // 8 * w.add_count
 
 
 def test_atari_shape_full_size_through_the_observation_codec():
@@ -377,11 +408,12 @@ def test_atari_shape_full_size_through_the_observation_codec():
     assert g.evict() == o.evict()
     check_gpu_tree(g, o)
 
-    def check_rows(keys, obs_out, n_check=24):
+    def check_rows(keys, obs_out):
+        """Every decoded row is the frame-like row that its key - the oracle's - defines."""
         keys = np.asarray(keys)
-        for i in np.linspace(0, len(keys) - 1, min(len(keys), n_check)).astype(int):
-            exp = synth.frame_rows(w.seed, int(keys[i]), 1, w.obs_bytes)[0]
-            assert np.array_equal(host(obs_out[i]), exp), (i, int(keys[i]))
+        for lo in range(0, len(keys), 2048):
+            exp = synth.frame_rows_for_keys_torch(w.seed, keys[lo:lo + 2048], w.obs_bytes, "cuda:0")
+            assert torch.equal(obs_out[lo:lo + 2048], exp), "decoded rows %d.. differ from their keys' bytes" % lo
 
     d = synth.actor_round(w, 4242)
     dd = {k2: dev(v) for k2, v in d.items()}
@@ -418,7 +450,8 @@ def test_atari_shape_full_size_through_the_observation_codec():
             assert np.array_equal(host(g_["slot"], np.uint32), o_["slot"])
             assert np.array_equal(host(g_["key"], np.uint64), o_["key"])
             assert_close(host(g_["weight"]), o_["weight"], "weight")
-            check_rows(o_["key"], g_["obs"], 6)
+            if s % 6 == 0:
+                check_rows(o_["key"], g_["obs"])
         check_gpu_tree(g, o)
     # the round added by the last window is sampled from as well: its rows went through the encoder on the copy stream
     pipe.close()
@@ -441,6 +474,6 @@ def test_atari_shape_full_size_through_the_observation_codec():
         assert np.array_equal(host(g_["slot"], np.uint32), oo["slot"])
         assert np.array_equal(host(g_["key"], np.uint64), oo["key"])
         assert_close(host(g_["weight"]), oo["weight"], "weight")
-        check_rows(oo["key"], g_["obs"], 48)
+        check_rows(oo["key"], g_["obs"])
     check_gpu_tree(g, o)
     pipe.close()
