@@ -79,13 +79,21 @@ def test_quantiser_dense_near_typical_priorities():
     assert np.array_equal(got[3], ref[3])
 
 
-def test_quantiser_exhaustive_over_all_non_negative_floats():
+@pytest.mark.parametrize("alpha,eps,P", [
+    (0.6, 1e-6, 1 << 21),               # the paper's exponent (Section 4.1), the Atari-shaped ring
+    (0.0, 1e-6, 1 << 21),               # uniform replay
+    (1.0, 1e-6, 1 << 21),
+    (0.3, 1e-6, 1 << 21),               # the ends of the range the Appendix reports as stable
+    (0.7, 1e-6, (1 << 24) + (1 << 20)),
+    (-0.4, 1e-6, 1 << 20),              # the eviction exponent of the continuous-control variant
+])
+def test_quantiser_exhaustive_over_all_non_negative_floats(alpha, eps, P):
     """Every one of the 2^31 non-negative fp32 bit patterns (all finite values, inf, all NaNs) through the
-    device quantiser and through the oracle, at the paper's exponent; the oracle side runs on a thread pool
-    (its C loop releases the interpreter lock)."""
+    device quantiser and through the oracle, for every exponent the workloads use; the oracle side runs on a
+    thread pool (its C loop releases the interpreter lock)."""
     from concurrent.futures import ThreadPoolExecutor
     from paper_1803_00933_amd import apex
-    alpha, eps, F, P = 0.6, 1e-6, 24, 1 << 21
+    F = 24
     chunk = 1 << 24
     z1 = np.zeros((1, chunk + 1, 1), F32)
     zi = np.zeros((1, chunk + 1), np.int32)
