@@ -17,14 +17,23 @@ _SO = os.path.join(_HERE, "libapex_oracle.so")
 OK, ERR_INVALID_ARG, ERR_FULL, ERR_NOT_READY, ERR_EMPTY = 0, -1, -2, -3, -4
 
 
-def build(force=False):
-    """Compile the oracle with the host C compiler (no HIP, no GPU)."""
-    if force or not os.path.exists(_SO) or os.path.getmtime(_SO) < os.path.getmtime(_SRC):
-        tmp = _SO + ".tmp.%d" % os.getpid()
-        subprocess.check_call(["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-mfma", "-Wall", "-Wextra",
-                               "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
-        os.replace(tmp, _SO)
-    return _SO
+_SO_SAN = os.path.join(_HERE, "libapex_oracle_san.so")
+SANITIZE_ENV = "APEX_ORACLE_SANITIZE"      # "1": load the build with AddressSanitizer + UndefinedBehaviorSanitizer
+
+
+def build(force=False, sanitize=False):
+    """Compile the oracle with the host C compiler (no HIP, no GPU).  sanitize: the same source with
+    -fsanitize=address,undefined (the process that loads it needs the AddressSanitizer runtime preloaded;
+    tests/test_host_sanitizers.py does that in a child process)."""
+    so = _SO_SAN if sanitize else _SO
+    if force or not os.path.exists(so) or os.path.getmtime(so) < os.path.getmtime(_SRC):
+        tmp = so + ".tmp.%d" % os.getpid()
+        opt = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+               "-fno-sanitize-recover=undefined"] if sanitize else ["-O2"]
+        subprocess.check_call(["gcc"] + opt + ["-std=c11", "-ffp-contract=off", "-mfma", "-Wall", "-Wextra",
+                                               "-shared", "-fPIC", "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, so)
+    return so
 
 
 _lib = None
@@ -34,7 +43,7 @@ _u64, _u32, _f32, _i32, _vp = C.c_uint64, C.c_uint32, C.c_float, C.c_int32, C.c_
 def lib():
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
+        L = C.CDLL(build(sanitize=os.environ.get(SANITIZE_ENV, "") == "1"))
         L.oracle_pow_spec.restype = _f32
         L.oracle_pow_spec.argtypes = [_f32, _f32]
         L.oracle_quantise.restype = _u64
