@@ -550,7 +550,41 @@ def next_row_numbers(log):
         schedule()
         torch.cuda.synchronize()
         dt = (time.perf_counter() - t0) / steps * 1e6
-    out["prioritized_evict_memory_control_schedule_us_per_step"] = dt
+    out["prioritized_evict_memory_control_schedule_plain_calls_us_per_step"] = dt
+
+    # the same schedule through the calls that keep the host out of the loop: an actor round as one launch, a
+    # learner step as two, the eviction enqueued (its count confirmed later from a snapshot)
+    # (argument lists made beforehand: the timed loop only marshals integers into the C ABI)
+    stream = torch.cuda.current_stream().cuda_stream
+    round_args = [(g.h, w.streams, w.chunk, w.n, w.num_actions, t["q_online"].data_ptr(), t["q_target"].data_ptr(),
+                   t["action"].data_ptr(), t["reward"].data_ptr(), t["discount"].data_ptr(), obs.data_ptr(),
+                   t["act"].data_ptr(), stream) for t in rounds_in]
+    step_args = [(g.h, w.k, 0.4, rnds[i].data_ptr(), td[i].data_ptr(), so["key"].data_ptr(), so["slot"].data_ptr(),
+                  so["weight"].data_ptr(), so["obs"].data_ptr(), so["act"].data_ptr(), so["ret"].data_ptr(),
+                  so["gacc"].data_ptr(), stream) for i in range(n)]
+    lib = apex.lib
+
+    def schedule_fused(n_steps):
+        for s in range(n_steps):
+            assert lib.apex_pe_add_round(*round_args[s % 4]) == 0
+            assert lib.apex_pe_sample_update(*step_args[s % n]) == 0
+            if (s + 1) % 10 == 0:
+                rc, asked = g.evict_enqueue(3, rnd_ev)
+                assert rc == 0 and asked == 10 * w.add_count, (rc, asked)
+
+    steps_f = 1000
+    best = 1e30
+    for rep_i in range(3):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        schedule_fused(steps_f)
+        t_host = time.perf_counter() - t0
+        torch.cuda.synchronize()
+        best = min(best, (time.perf_counter() - t0) / steps_f * 1e6)
+    st = g.stats()
+    assert st["size"] == w.capacity and st["evicted"] == st["inserted"] - w.capacity, st
+    out["prioritized_evict_memory_control_schedule_us_per_step"] = best
+    out["prioritized_evict_memory_control_schedule_host_us_per_step"] = t_host / steps_f * 1e6
     g.close()
     out["observation_codec"] = codec_numbers(log)
     log("next rows: %s" % {k: (round(v, 2) if not isinstance(v, dict) else v) for k, v in out.items()})

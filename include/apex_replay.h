@@ -517,6 +517,37 @@ int apex_pe_update_priorities(apex_pe_replay_t *r, uint64_t m, const uint64_t *k
                               void *hip_stream);
 int apex_pe_evict(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uint64_t *evicted_out /*host*/,
                   void *hip_stream);
+/*
+ * apex_pe_evict without the host in the loop: enqueues the same rounds for e = size - capacity transitions and
+ * returns; *requested_out (host, may be NULL) receives e.  rnd is [rounds, e] as above.  The host's own count of
+ * stored transitions (which decides APEX_ERR_FULL, APEX_ERR_EMPTY and the next e) takes all e to be gone; behind
+ * the rounds the call copies the device's counters into host memory of the library's, and the next calls look at
+ * that copy once it has arrived: if the rounds ran out before e distinct transitions were found, the host's
+ * count is corrected then (and the next eviction asks for the rest).  An add that would only fit if the
+ * unconfirmed eviction was complete waits for the copy first, so a slot is never handed out twice.  No device
+ * memory is allocated.  Not for HIP graph capture (the copy and its event would be recorded once).
+ */
+int apex_pe_evict_enqueue(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uint64_t *requested_out /*host*/,
+                          void *hip_stream);
+/*
+ * An actor round in one launch (Algorithm 1: ComputePriorities, then replay.Add): the n-step priorities of S x T
+ * transitions (arguments and arithmetic as apex_nstep_priorities) and their insertion with obs [S*T, obs_bytes]
+ * and act [S*T, act_bytes] (device; act may be NULL), partial return and accumulated discount as computed.
+ * Result: that of apex_nstep_priorities followed by apex_pe_add.  Only for observation rows of at most 256
+ * vectors (4 KB when rows and pointers are 16-byte aligned): APEX_ERR_TOO_LARGE otherwise.
+ */
+int apex_pe_add_round(apex_pe_replay_t *r, uint32_t S, uint32_t T, uint32_t n, uint32_t A, const float *q_online,
+                      const float *q_target, const int32_t *action, const float *reward, const float *discount,
+                      const void *obs, const void *act, void *hip_stream);
+/*
+ * A learner step in two launches (Algorithm 2: replay.Sample, replay.SetPriority): apex_pe_sample of one batch
+ * of k <= 1024 with the uniforms rnd [k], then apex_pe_update_priorities(k, key_out, new_prio) with new_prio [k]
+ * (device) - the gather, the weights and the write-back share the second launch.  key_out and slot_out are
+ * required, the other outputs may be NULL.  Same row limit as apex_pe_add_round when obs_out is given.
+ */
+int apex_pe_sample_update(apex_pe_replay_t *r, uint32_t k, float beta, const uint64_t *rnd, const float *new_prio,
+                          uint64_t *key_out, uint32_t *slot_out, float *weight_out, void *obs_out, void *act_out,
+                          float *ret_out, float *gacc_out, void *hip_stream);
 int apex_pe_stats(apex_pe_replay_t *r, apex_pe_stats_t *out /*host*/, void *hip_stream);
 
 /* hipError_t of the last failed HIP call of the calling thread (0 if none). */

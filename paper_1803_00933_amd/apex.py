@@ -30,6 +30,7 @@ EXPORTS = ["apex_replay_workspace_bytes", "apex_replay_create", "apex_replay_des
            "apex_pipeline_capture_begin", "apex_pipeline_capture_end", "apex_pipeline_replay",
            "apex_pe_workspace_bytes", "apex_pe_create", "apex_pe_destroy", "apex_pe_layout", "apex_pe_add",
            "apex_pe_sample", "apex_pe_update_priorities", "apex_pe_evict", "apex_pe_stats",
+           "apex_pe_evict_enqueue", "apex_pe_add_round", "apex_pe_sample_update",
            "apex_codec_row_bytes", "apex_replay_add_payload_encoded", "apex_replay_gather_decoded",
            "apex_pipeline_set_codec"]
 
@@ -126,6 +127,9 @@ lib.apex_pe_sample.argtypes = [_vp, _u32, _u32, _f32, _vp, _vp, _vp, _vp, _vp, _
 lib.apex_pe_update_priorities.argtypes = [_vp, _u64, _vp, _vp, _vp]
 lib.apex_pe_evict.argtypes = [_vp, _u32, _vp, C.POINTER(_u64), _vp]
 lib.apex_pe_stats.argtypes = [_vp, C.POINTER(PeStats), _vp]
+lib.apex_pe_evict_enqueue.argtypes = [_vp, _u32, _vp, C.POINTER(_u64), _vp]
+lib.apex_pe_add_round.argtypes = [_vp, _u32, _u32, _u32, _u32] + [_vp] * 8
+lib.apex_pe_sample_update.argtypes = [_vp, _u32, _f32] + [_vp] * 10
 for _name in EXPORTS:
     getattr(lib, _name).restype = C.c_int
 
@@ -466,6 +470,22 @@ class PeReplay:
         e = _u64(0)
         rc = lib.apex_pe_evict(self.h, rounds, _ptr(rnd), C.byref(e), _stream(stream))
         return rc, int(e.value)
+
+    def evict_enqueue(self, rounds, rnd, stream=None):
+        """apex_pe_evict_enqueue: returns (rc, number of evictions asked for); nothing is waited for."""
+        e = _u64(0)
+        rc = lib.apex_pe_evict_enqueue(self.h, rounds, _ptr(rnd), C.byref(e), _stream(stream))
+        return rc, int(e.value)
+
+    def add_round(self, q_online, q_target, action, reward, discount, n, obs, act=None, stream=None):
+        S, L, A = q_online.shape
+        return lib.apex_pe_add_round(self.h, S, L - n, n, A, _ptr(q_online), _ptr(q_target), _ptr(action), _ptr(reward),
+                                     _ptr(discount), _ptr(obs), _ptr(act), _stream(stream))
+
+    def sample_update(self, k, beta, rnd, new_prio, out, stream=None):
+        return lib.apex_pe_sample_update(self.h, k, beta, _ptr(rnd), _ptr(new_prio), _ptr(out["key"]), _ptr(out["slot"]),
+                                         _ptr(out.get("weight")), _ptr(out.get("obs")), _ptr(out.get("act")),
+                                         _ptr(out.get("ret")), _ptr(out.get("gacc")), _stream(stream))
 
     def stats(self, stream=None):
         st = PeStats()

@@ -91,6 +91,28 @@ __device__ __forceinline__ void add_to_ancestors_grouped(const TreeView &tv, boo
   }
 }
 
+// Same, for a wave whose lanes hold slots in any order (the free slots that a memory with prioritized
+// eviction hands out, the candidates of an eviction round - both mostly ascending, so that neighbouring lanes
+// mostly share their ancestors): on every level each run of neighbouring lanes under one node is summed with
+// one prefix sum over the wave and sends one atomic.  A node that appears in several runs receives several
+// atomics.  Sums are modulo 2^64, so a removal passes 0 - mass.  Must be called by all 64 lanes.
+__device__ __forceinline__ void add_runs_to_ancestors(const TreeView &tv, bool active, uint64_t slot, uint64_t delta)
+{
+  const int lane = lane_id();
+  const uint64_t incl = wave_inclusive_scan(active ? delta : 0);
+  uint64_t idx = slot;
+  for (uint32_t l = 1; l < tv.nlev; ++l) {
+    idx >>= kFanoutLog2;
+    const uint64_t node = active ? idx : ~0ull;  // lanes without a delta form runs of their own, which send nothing
+    const uint64_t prev = __shfl_up(node, 1, kWave);
+    const uint64_t starts = __ballot(lane == 0 || prev != node);
+    const bool ends = lane == kWave - 1 || ((starts >> (lane + 1)) & 1);
+    const int first = 63 - __builtin_clzll(starts & (~0ull >> (63 - lane)));  // where this lane's run starts (bit 0 is set)
+    const uint64_t before = __shfl(incl, first > 0 ? first - 1 : 0, kWave);
+    if (active && ends) atomic_add_u64(tv.level[l] + idx, incl - (first > 0 ? before : 0));
+  }
+}
+
 // --------------------------------------------------------------------------------------------
 // n-step priorities: one thread per transition (Algorithm 1, ComputePriorities; Sections 3.1, 3.2)
 // --------------------------------------------------------------------------------------------

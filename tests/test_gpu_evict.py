@@ -131,3 +131,86 @@ def test_control_shape_with_prioritized_eviction():
             assert g.evict(rounds, dev(rnd_e)) == o.evict(rounds, rnd_e) == (0, e)
             check(g, o)
     check(g, o)
+
+
+def test_control_schedule_without_the_host_in_the_loop():
+    """The control-shaped schedule on the memory with prioritized eviction through the calls that wait for nothing:
+    an actor round in one launch (n-step priorities + add), a learner step in two (draw; gather + weights +
+    write-back), the eviction enqueued - against the oracle doing n-step priorities, add, sample, update, evict."""
+    from paper_1803_00933_amd import apex, synth
+    w = synth.WORKLOADS["control"]
+    g = apex.PeReplay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    o = oracle.PrioritizedEvictionReplay(w.capacity, w.max_slots, w.obs_bytes, w.act_bytes)
+    prio = synth.priorities("lognormal1", w.seed, 0, w.capacity, tag="bulk")
+    obs0 = np.zeros((w.capacity, w.obs_bytes), np.uint8)
+    assert o.add(prio, obs0)[0] == 0 and g.add(dev(prio), dev(obs0)) == 0
+    del obs0
+    rounds, steps = 5, 40
+    outs = [g.alloc_sample_outputs(1, w.k) for _ in range(steps)]
+    refs = []
+    key0 = w.capacity
+    for step in range(steps):                      # nothing in this loop waits for the GPU (the oracle runs beside it)
+        d = synth.actor_round(w, step)
+        obs = synth.obs_rows(w.seed, key0, w.add_count, w.obs_bytes)
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      w.n, w.alpha, w.eps, w.frac_bits, w.max_slots)
+        assert o.add(ref[0].reshape(-1), obs, d["act"], ref[1].reshape(-1), ref[2].reshape(-1))[0] == 0
+        assert g.add_round(dev(d["q_online"]), dev(d["q_target"]), dev(d["action"]), dev(d["reward"]),
+                           dev(d["discount"]), w.n, dev(obs), dev(d["act"])) == 0
+        key0 += w.add_count
+        rnd = synth.uniforms(w.seed, step, 1, w.k).reshape(-1)
+        newp = synth.priorities(w.td_dist, w.seed, step, w.k)
+        rco, oo = o.sample(1, w.k, w.beta, rnd)
+        assert rco == 0 and o.update_priorities(oo["key"], newp) == 0
+        refs.append(oo)
+        assert g.sample_update(w.k, w.beta, dev(rnd), dev(newp), outs[step]) == 0
+        if (step + 1) % 10 == 0:
+            e = o.size - w.capacity
+            rnd_e = np.random.default_rng(step).integers(0, U64, (rounds, e), dtype=np.uint64)
+            assert o.evict(rounds, rnd_e) == (0, e)
+            assert g.evict_enqueue(rounds, dev(rnd_e)) == (0, e)
+    torch.cuda.synchronize()
+    for step in range(steps):
+        assert_sample_equal(outs[step], refs[step])
+    check(g, o)
+    # the eviction that reports back still agrees, and so does the plain path after the enqueued ones
+    p_new = synth.priorities("lognormal1", w.seed, 99, w.add_count, tag="bulk")
+    assert o.add(p_new)[0] == 0 and g.add(dev(p_new)) == 0
+    e = o.size - w.capacity
+    rnd_e = np.random.default_rng(7).integers(0, U64, (rounds, e), dtype=np.uint64)
+    assert g.evict(rounds, dev(rnd_e)) == o.evict(rounds, rnd_e) == (0, e)
+    check(g, o)
+
+
+def test_enqueued_eviction_that_falls_short_is_noticed():
+    """One round with all points inside one transition removes 1 of the 2 asked for: the host's count is corrected
+    from the snapshot the call left behind - an add that only fits if both were gone is refused, the next eviction
+    asks for the one that is left - and the device state equals the oracle's throughout."""
+    from paper_1803_00933_amd import apex
+    g = apex.PeReplay(2, 4, 16, 4, alpha=1.0, alpha_evict=-1.0, eps=0.0)
+    o = oracle.PrioritizedEvictionReplay(2, 4, 16, 4, alpha=1.0, alpha_evict=-1.0, eps=0.0)
+    prio = np.array([1, 2, 4, 8], F32)
+    o.add(prio), g.add(dev(prio))
+    assert o.evict(1, np.zeros(2, np.uint64)) == (0, 1)
+    assert g.evict_enqueue(1, dev(np.zeros(2, np.uint64))) == (0, 2)     # asked for two
+    three = np.array([1, 1, 1], F32)
+    assert g.add(dev(three)) == apex.ERR_FULL == o.add(three)[0]         # 3 stored, 4 slots: no room for three
+    one = np.array([3], F32)
+    assert g.add(dev(one)) == 0 == o.add(one)[0]
+    check(g, o)
+    assert o.evict(3, np.zeros((3, 2), np.uint64)) == (0, 2)
+    assert g.evict_enqueue(3, dev(np.zeros((3, 2), np.uint64))) == (0, 2)
+    torch.cuda.synchronize()
+    check(g, o)
+    assert g.evict_enqueue(3, dev(np.zeros((3, 2), np.uint64))) == (0, 0)
+    # limits of the fused calls
+    big = apex.PeReplay(10, 16, 8192, 4)
+    z = torch.zeros((1, 3, 1), device="cuda:0")
+    zi = torch.zeros((1, 3), dtype=torch.int32, device="cuda:0")
+    obs = torch.zeros((2, 8192), dtype=torch.uint8, device="cuda:0")
+    assert big.add_round(z, z, zi, z[:, :, 0].contiguous(), z[:, :, 0].contiguous(), 1, obs) == apex.ERR_TOO_LARGE
+    out = g.alloc_sample_outputs(1, 2000)
+    assert g.sample_update(2000, 0.4, dev(np.zeros(2000, np.uint64)), dev(np.zeros(2000, F32)), out) == apex.ERR_TOO_LARGE
+    empty = apex.PeReplay(2, 4, 16, 4)
+    out = empty.alloc_sample_outputs(1, 4)
+    assert empty.sample_update(4, 0.4, dev(np.zeros(4, np.uint64)), dev(np.zeros(4, F32)), out) == apex.ERR_EMPTY
