@@ -205,17 +205,46 @@ __global__ __launch_bounds__(1024) void pe_update_small_kernel(PeView v, PeState
   pe_update_small_block(v, st, m, key, prio, h_slot, h_pos);
 }
 
+// The write-back of the batch that the launch before has drawn, nothing having touched the trees since: pair i
+// is valid, lives in slot[i] and weighs mass[i] in the sampling tree, so the loads key -> generation -> mass and
+// the hash table are not needed; the drawn slots do not decrease (the strata ascend), so pairs naming one slot
+// are neighbours and the last of them is the one that stands.  One workgroup of at least m lanes.
+__device__ __forceinline__ void pe_writeback_block(const PeView &v, PeState *__restrict__ st, uint32_t m,
+                                                   const uint32_t *__restrict__ slot, const uint64_t *__restrict__ mass,
+                                                   const float *__restrict__ prio)
+{
+  const uint32_t i = threadIdx.x;
+  const bool in = i < m;
+  const uint32_t s = in ? slot[i] : 0, s_next = i + 1 < m ? slot[i + 1] : 0xffffffffu;
+  const bool wins = in && s != s_next;
+  uint64_t d1 = 0, d2 = 0;
+  uint32_t nclamp = 0;
+  if (in) {
+    bool c1, c2;
+    const float p = prio[i];
+    const uint64_t q1 = quantise_priority(p, v.qs, &c1), q2 = quantise_priority(p, v.qe, &c2);
+    nclamp = (uint32_t)c1 + (uint32_t)c2;  // counted for pairs that lose too, as when they are applied one by one
+    if (wins) {
+      d1 = q1 - mass[i], d2 = q2 - v.te.level[0][s];
+      v.ts.level[0][s] = q1;
+      v.te.level[0][s] = q2;
+    }
+  }
+  add_runs_to_ancestors(v.ts, wins, s, d1);
+  add_runs_to_ancestors(v.te, wins, s, d2);
+  const uint64_t nc = wave_sum(nclamp);
+  if (nc && lane_id() == 0) atomic_add_u64(&st->base.n_clamped, nc);
+}
+
 // Everything that follows the draw of one batch of short rows whose new priorities are known, in one launch of
 // workgroups of 1024 lanes: workgroups [0, copy_blocks) gather the rows, the next one writes the importance
 // weights, the last one writes the batch's new priorities back (m = k <= 1024 pairs).
 template <typename Vec>
 __global__ __launch_bounds__(1024) void pe_finish_update_kernel(ShortCopyArgs c, uint32_t copy_blocks, WeightArgs wa,
                                                                 PeView v, PeState *__restrict__ st, uint32_t m,
-                                                                const uint64_t *__restrict__ key,
+                                                                const uint32_t *__restrict__ slot,
                                                                 const float *__restrict__ prio)
 {
-  __shared__ uint32_t h_slot[kDedupeSlots];
-  __shared__ uint32_t h_pos[kDedupeSlots];
   __shared__ uint64_t red[1024 / kWave];
   const uint32_t blk = blockIdx.x;
   if (blk < copy_blocks) {
@@ -223,7 +252,7 @@ __global__ __launch_bounds__(1024) void pe_finish_update_kernel(ShortCopyArgs c,
   } else if (blk == copy_blocks && wa.weight_out) {
     batch_weights(wa, 0, red);
   } else if (blk == copy_blocks + 1) {
-    pe_update_small_block(v, st, m, key, prio, h_slot, h_pos);
+    pe_writeback_block(v, st, m, slot, wa.mass, prio);
   }
 }
 
@@ -504,7 +533,7 @@ int pe_enqueue_eviction(apex_pe_replay *r, uint64_t e, uint32_t rounds, const ui
   a.ret = a.gacc = nullptr;
   a.act_out = nullptr;
   a.ret_out = a.gacc_out = nullptr;
-  const uint32_t waves = 4;
+  const uint32_t waves = 4;  // (16 waves per workgroup, which stage the top level fewer times, measured 20 % slower)
   const size_t lds = ((size_t)a.tv.n_top + waves) * sizeof(uint64_t);
   const uint32_t scan_blocks = blocks_for(e, kPeScanThreads);  // <= 1024 since e <= 2^20
   for (uint32_t rd = 0; rd < rounds; ++rd) {
@@ -838,7 +867,7 @@ int apex_pe_sample_update(apex_pe_replay_t *r, uint32_t k, float beta, const uin
   const WeightArgs wa{r->mass(), weight_out, k, beta};
   const dim3 grid(copy_blocks + 2), block(1024);
 #define APEX_PE_FINISH(Vec) \
-  pe_finish_update_kernel<Vec><<<grid, block, 0, stream>>>(c, copy_blocks, wa, r->v, r->state(), k, key_out, new_prio)
+  pe_finish_update_kernel<Vec><<<grid, block, 0, stream>>>(c, copy_blocks, wa, r->v, r->state(), k, slot_out, new_prio)
   if (vb == 16) APEX_PE_FINISH(u32x4);
   else if (vb == 4) APEX_PE_FINISH(uint32_t);
   else APEX_PE_FINISH(uint8_t);
