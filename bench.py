@@ -848,10 +848,9 @@ def main():
                     help="most learner steps timed on the CPU oracle (0 = skip) ...")
     ap.add_argument("--cpu-seconds", type=float, default=12.0,
                     help="... which stops at the first whole cycle after this many seconds")
-    ap.add_argument("--extras", choices=("auto", "on", "off"), default="auto",
+    ap.add_argument("--extras", choices=("on", "off"), default="on",
                     help="the other workload shapes and library features beside the headline (control, skew, scale, "
-                         "learner-side priorities, prioritized eviction, observation codec: two to three minutes more). "
-                         "auto: only when at least 1000 steps are asked for")
+                         "learner-side priorities, prioritized eviction, observation codec): about ten seconds more")
     ap.add_argument("--no-control", action="store_true", help="same as --extras off")
     ap.add_argument("--profile-loop", type=int, default=0, metavar="N",
                     help="after the prefill run only N launches of each kernel that the counter passes under "
@@ -867,7 +866,7 @@ def main():
     except ValueError as e:
         print("bench.py: %s" % e, file=sys.stderr)
         sys.exit(2)
-    extras = not args.no_control and (args.extras == "on" or (args.extras == "auto" and args.steps >= 1000))
+    extras = not args.no_control and args.extras == "on"
 
     def log(msg):
         if not args.quiet:

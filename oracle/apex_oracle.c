@@ -5,8 +5,12 @@
  * "Distributed Prioritized Experience Replay" computes.  It exists so that the HIP
  * library can be checked against something written independently from the paper.
  * Only tests, the smoke check and the benchmark's cpu_baseline leg may call it; the
- * product path never does.  It shares no source, header, table or constant generator
- * with the HIP code.
+ * product path never does.  It shares no source, header or generator with the HIP code.
+ * One thing is alike by specification: the mass of a priority has to be the same integer
+ * on both sides, so the power p^alpha is ONE specified sequence of fp32 operations with 19
+ * specified polynomial coefficients (oracle_pow_spec), typed in here and, again, in the
+ * library; what makes that sequence trustworthy is not the library but the pins against
+ * the double-precision pow of libm and the exact special cases.
  *
  * Data structures are the textbook ones: a binary array sum-tree of uint64 masses
  * (node[i] = node[2i] + node[2i+1], leaves at node[P2 + slot]) and a ring of slots
