@@ -145,7 +145,7 @@ def test_control_schedule_without_the_host_in_the_loop():
     obs0 = np.zeros((w.capacity, w.obs_bytes), np.uint8)
     assert o.add(prio, obs0)[0] == 0 and g.add(dev(prio), dev(obs0)) == 0
     del obs0
-    rounds, steps = 5, 40
+    rounds, steps = 5, 100
     outs = [g.alloc_sample_outputs(1, w.k) for _ in range(steps)]
     refs = []
     key0 = w.capacity
@@ -214,3 +214,52 @@ def test_enqueued_eviction_that_falls_short_is_noticed():
     empty = apex.PeReplay(2, 4, 16, 4)
     out = empty.alloc_sample_outputs(1, 4)
     assert empty.sample_update(4, 0.4, dev(np.zeros(4, np.uint64)), dev(np.zeros(4, F32)), out) == apex.ERR_EMPTY
+
+
+@pytest.mark.parametrize("P,C,ob,ab,S,T,n,A,k", [
+    (600, 400, 12, 4, 3, 7, 3, 4, 33),          # 4-byte vectors, one tree level, ragged everything
+    (5000, 4000, 7, 3, 5, 11, 2, 1, 100),       # byte copies, critic values
+    (70_000, 60_000, 4096, 8, 4, 50, 5, 18, 512),  # the longest rows the fused calls take, three levels
+])
+def test_fused_calls_on_small_and_ragged_shapes(P, C, ob, ab, S, T, n, A, k):
+    """apex_pe_add_round / apex_pe_sample_update / apex_pe_evict_enqueue against the oracle's n-step priorities,
+    add, sample, update, evict on shapes that take every vector width, with heavy-tailed priorities (repeated
+    slots inside a batch) and evictions that need several rounds."""
+    from paper_1803_00933_amd import apex, synth
+    rng = np.random.default_rng(P + ob)
+    g = apex.PeReplay(C, P, ob, ab)
+    o = oracle.PrioritizedEvictionReplay(C, P, ob, ab)
+    w = synth.WORKLOADS["tiny"].scaled(streams=S, chunk=T, n=n, num_actions=A, act_bytes=ab)
+    fill = C - 2 * S * T
+    prio = (rng.pareto(0.5, fill) + 1e-3).astype(F32)
+    obs = rng.integers(0, 256, (fill, ob), dtype=np.uint8)
+    act = rng.integers(0, 256, (fill, ab), dtype=np.uint8)
+    ret, gacc = rng.standard_normal(fill).astype(F32), rng.random(fill).astype(F32)
+    assert o.add(prio, obs, act, ret, gacc)[0] == 0 and g.add(dev(prio), dev(obs), dev(act), dev(ret), dev(gacc)) == 0
+    rounds = 6
+    for step in range(12):
+        d = synth.actor_round(w, step, with_payload=False)
+        d["q_online"] *= F32(3.0)                      # larger TD errors: heavier tails
+        obs = rng.integers(0, 256, (S * T, ob), dtype=np.uint8)
+        act = rng.integers(0, 256, (S * T, ab), dtype=np.uint8)
+        ref = oracle.nstep_priorities(d["q_online"], d["q_target"], d["action"], d["reward"], d["discount"],
+                                      n, 0.6, 1e-6, 24, P)
+        rco = o.add(ref[0].reshape(-1), obs, act, ref[1].reshape(-1), ref[2].reshape(-1))[0]
+        rcg = g.add_round(dev(d["q_online"]), dev(d["q_target"]), dev(d["action"]), dev(d["reward"]),
+                          dev(d["discount"]), n, dev(obs), dev(act))
+        assert rcg == rco
+        rnd = rng.integers(0, U64, k, dtype=np.uint64)
+        newp = (rng.pareto(0.5, k) + 1e-3).astype(F32)
+        newp[rng.random(k) < 0.1] = 0.0
+        rco, oo = o.sample(1, k, 0.7, rnd)
+        assert rco == 0 and o.update_priorities(oo["key"], newp) == 0
+        out = g.alloc_sample_outputs(1, k)
+        assert g.sample_update(k, 0.7, dev(rnd), dev(newp), out) == 0
+        torch.cuda.synchronize()
+        assert_sample_equal(out, oo)
+        if step % 3 == 2:
+            e = max(0, o.size - C)
+            rnd_e = rng.integers(0, U64, (rounds, max(e, 1)), dtype=np.uint64)
+            rco, eo = o.evict(rounds, rnd_e)
+            assert g.evict_enqueue(rounds, dev(rnd_e)) == (rco, e)
+        check(g, o)
