@@ -524,8 +524,10 @@ int apex_pe_evict(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uin
  * the rounds the call copies the device's counters into host memory of the library's, and the next calls look at
  * that copy once it has arrived: if the rounds ran out before e distinct transitions were found, the host's
  * count is corrected then (and the next eviction asks for the rest).  An add that would only fit if the
- * unconfirmed eviction was complete waits for the copy first, so a slot is never handed out twice.  No device
- * memory is allocated.  Not for HIP graph capture (the copy and its event would be recorded once).
+ * unconfirmed eviction was complete waits for the copy first, so a slot is never handed out twice; so does the
+ * next apex_pe_evict_enqueue if the copy of the one before it has still not arrived (there is one such copy at a
+ * time).  No device memory is allocated.  Not for HIP graph capture (the copy and its event would be recorded
+ * once).
  */
 int apex_pe_evict_enqueue(apex_pe_replay_t *r, uint32_t rounds, const uint64_t *rnd, uint64_t *requested_out /*host*/,
                           void *hip_stream);

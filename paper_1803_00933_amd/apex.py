@@ -472,7 +472,7 @@ class PeReplay:
         return rc, int(e.value)
 
     def evict_enqueue(self, rounds, rnd, stream=None):
-        """apex_pe_evict_enqueue: returns (rc, number of evictions asked for); nothing is waited for."""
+        """apex_pe_evict_enqueue: returns (rc, number of evictions asked for) without waiting for the eviction."""
         e = _u64(0)
         rc = lib.apex_pe_evict_enqueue(self.h, rounds, _ptr(rnd), C.byref(e), _stream(stream))
         return rc, int(e.value)
