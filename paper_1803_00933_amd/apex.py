@@ -10,7 +10,8 @@ import os
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libapex_replay.so")
+# (APEX_REPLAY_LIB names another build of the same library, e.g. the one with sanitized host code)
+LIB_PATH = os.environ.get("APEX_REPLAY_LIB") or os.path.join(_HERE, "libapex_replay.so")
 
 OK, ERR_INVALID_ARG, ERR_FULL, ERR_NOT_READY, ERR_EMPTY, ERR_HIP, ERR_TOO_LARGE = 0, -1, -2, -3, -4, -5, -6
 STATUS_NAMES = {0: "APEX_OK", -1: "APEX_ERR_INVALID_ARG", -2: "APEX_ERR_FULL", -3: "APEX_ERR_NOT_READY",

@@ -18,14 +18,30 @@ FLAGS = [
 ]
 
 
-def build_library(verbose=False):
-    tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = [HIPCC] + FLAGS + ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"), "-o", tmp] + SOURCES
+LIB_HOSTSAN = os.path.join(HERE, "libapex_replay_hostsan.so")
+# host code only (the -Xarch_host prefix keeps the sanitizers away from the device pass), shared runtime
+HOSTSAN_FLAGS = ["-O1", "-g", "-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined",
+                 "-Xarch_host", "-fno-sanitize-recover=undefined", "-shared-libsan"]
+
+
+def build_library(verbose=False, sanitize_host=False):
+    """sanitize_host: a second library, same sources, whose HOST code runs under AddressSanitizer and
+    UndefinedBehaviorSanitizer (for the CPU-only argument-check tests; the process that loads it needs clang's
+    AddressSanitizer runtime preloaded, see asan_runtime())."""
+    out = LIB_HOSTSAN if sanitize_host else LIB
+    flags = [f for f in FLAGS if f != "-O3"] + HOSTSAN_FLAGS if sanitize_host else FLAGS
+    tmp = out + ".tmp.%d" % os.getpid()
+    cmd = [HIPCC] + flags + ["-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc"), "-o", tmp] + SOURCES
     if verbose:
         print(" ".join(cmd))
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, out)
+    return out
+
+
+def asan_runtime():
+    """Path of the AddressSanitizer runtime that belongs to hipcc's host compiler."""
+    return subprocess.check_output([HIPCC, "-print-file-name=libclang_rt.asan-x86_64.so"], text=True).strip()
 
 
 if __name__ == "__main__":

@@ -79,3 +79,23 @@ def test_rows_for_scattered_keys_are_the_rows_of_those_keys():
     for i, k in enumerate(keys):
         assert np.array_equal(got[i], synth.frame_rows(7, int(k), 1, 128)[0])
     assert np.array_equal(synth.frame_rows_torch(7, 40, 9, 256, "cpu").numpy(), synth.frame_rows(7, 40, 9, 256))
+
+
+def test_null_handles_are_refused_without_a_gpu():
+    from paper_1803_00933_amd import apex
+    lib, bad = apex.lib, apex.ERR_INVALID_ARG
+    assert lib.apex_replay_sample_noalloc(None, 1, 8, 0.4, *([None] * 9)) == bad
+    assert lib.apex_replay_sample(None, 1, 8, 0.4, *([None] * 9)) == bad
+    assert lib.apex_replay_update_priorities(None, 0, None, None, None) == bad
+    assert lib.apex_replay_evict(None, None, None) == bad
+    assert lib.apex_pipeline_steps(None, 1, 0.4, None, None, None) == bad
+    assert lib.apex_pe_evict_enqueue(None, 1, None, None, None) == bad
+    assert lib.apex_pe_add_round(None, 1, 1, 1, 1, *([None] * 8)) == bad
+    assert lib.apex_pe_sample_update(None, 8, 0.4, *([None] * 10)) == bad
+    assert lib.apex_pe_destroy(None) == bad and lib.apex_pipeline_destroy(None) == bad
+    pe = apex.PeConfig(10, 8, 16, 4, 0.6, -0.4, 1e-6, 24)              # max_slots < capacity
+    a = C.c_size_t(0)
+    assert lib.apex_pe_workspace_bytes(C.byref(pe), C.byref(a), None, None) == bad
+    pe = apex.PeConfig(1_000_000, 1 << 20, 256, 32, 0.6, -0.4, 1e-6, 24)
+    assert lib.apex_pe_workspace_bytes(C.byref(pe), C.byref(a), None, None) == apex.OK and a.value >= (1 << 20) * 256
+    assert int(lib.apex_codec_row_bytes(28224)) == 28736 and int(lib.apex_codec_row_bytes(100)) == 0
