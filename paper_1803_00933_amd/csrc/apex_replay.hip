@@ -260,13 +260,13 @@ void launch_step_codec(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t
 {
   const dim3 grid(wgs), block(threads);
   if (rider == kLeavesRide)
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1, kLeavesRide, true><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1, kLeavesRide, true><<<grid, block, lds, stream>>>(a);
   else if (n_top <= 8 * kWave)
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1, kNoRider, true><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 1, kNoRider, true><<<grid, block, lds, stream>>>(a);
   else if (n_top <= 16 * kWave)
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 2, kNoRider, true><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 2, kNoRider, true><<<grid, block, lds, stream>>>(a);
   else
-    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 4, kNoRider, true><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<u32x4, kStepThreads, kStepUnroll, 4, kNoRider, true><<<grid, block, lds, stream>>>(a);
 }
 
 template <typename Vec>
@@ -275,15 +275,15 @@ void launch_step_t(const StepArgs &a, uint32_t n_top, uint32_t wgs, uint32_t thr
 {
   const dim3 grid(wgs), block(threads);
   if (rider == kRoundRides)  // further workgroups carry part of an add round (such a launch draws nothing)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kRoundRides><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kRoundRides><<<grid, block, lds, stream>>>(a);
   else if (rider == kLeavesRide)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kLeavesRide><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kLeavesRide><<<grid, block, lds, stream>>>(a);
   else if (n_top <= 8 * kWave)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kNoRider><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 1, kNoRider><<<grid, block, lds, stream>>>(a);
   else if (n_top <= 16 * kWave)
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 2, kNoRider><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 2, kNoRider><<<grid, block, lds, stream>>>(a);
   else
-    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 4, kNoRider><<<grid, block, lds, stream>>>(a.slot, a.next_top, a);
+    learner_step_kernel<Vec, kStepThreads, kStepUnroll, 4, kNoRider><<<grid, block, lds, stream>>>(a);
 }
 
 // A small add round (observations of at most 1 KB per row) as one launch: n-step priorities, payload,

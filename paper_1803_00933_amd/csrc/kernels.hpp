@@ -1225,14 +1225,14 @@ __device__ __forceinline__ void fetch_now(T *p)
 //  - what does not depend on the walk (priority -> mass, head % P, the addresses of everything written at
 //    the end) is computed or fetched while the first row of children is on its way.
 template <int kTopChunk>
-__device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *pre, const uint64_t *top_arg)
+__device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t row, uint64_t *pre)
 {
   const TreeView &rd = a.next.tv;
   const uint32_t n_top = rd.n_top, lane = lane_id();
   const uint32_t n_top_pad = (n_top + kFanout - 1) & ~(kFanout - 1);  // the level is zero-padded to this in memory
   const bool second = a.next_prio && row + 1 < a.next.k;              // a next sample to compare slots with
   __builtin_amdgcn_s_setprio(2);
-  const uint64_t *top = top_arg;
+  const uint64_t *top = a.next_top;
   constexpr uint32_t kChunkNodes = kTopChunk * 8 * kWave;
 
   uint64_t v[kTopChunk][8];
@@ -1365,7 +1365,7 @@ __device__ __forceinline__ void draw_in_first_wave(const StepArgs &a, uint32_t r
 // kRider: what the workgroups beyond the first k carry (StepArgs::add or ::leaves).
 // kCodec: the rows are decoded on their way out (StepArgs::codec; Vec is 16 bytes wide).
 template <typename Vec, int kThreads, int kUnroll, int kTopChunk, int kRider, bool kCodec = false>
-__global__ __launch_bounds__(kThreads) void learner_step_kernel(const uint32_t *slot_arg, const uint64_t *top_arg, StepArgs a)
+__global__ __launch_bounds__(kThreads) void learner_step_kernel(StepArgs a)
 {
   extern __shared__ uint64_t lds[];
   const uint32_t row = blockIdx.x, tid = threadIdx.x, nthr = blockDim.x;
@@ -1385,12 +1385,12 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(const uint32_t *
   const uint32_t wave = tid / kWave, lane = lane_id();
   const bool write_back = a.dq != nullptr, draw = a.next.rnd != nullptr;
   if (!a.slot) {  // the first draw of a sequence (one wave per workgroup): no batch to gather yet
-    if (draw && wave == 0) draw_in_first_wave<kTopChunk>(a, row, lds, top_arg);
+    if (draw && wave == 0) draw_in_first_wave<kTopChunk>(a, row, lds);
     return;
   }
   const uint32_t first = (draw && a.vecs_per_row <= (nthr - kWave) * kUnroll) ? kWave : 0;
   if (draw && wave == 0) {
-    draw_in_first_wave<kTopChunk>(a, row, lds, top_arg);
+    draw_in_first_wave<kTopChunk>(a, row, lds);
     if (first) return;
   }
   // The compiler places its waits for memory by counting loads in flight; it can count them only along
@@ -1402,7 +1402,7 @@ __global__ __launch_bounds__(kThreads) void learner_step_kernel(const uint32_t *
   // no load below sits in a divergent branch (indices are clamped, unused lanes read an address of their
   // own workgroup that is always valid), the row is waited for once, and the side jobs' stores and
   // atomics follow the row's.
-  const uint32_t my_slot = slot_arg[row];
+  const uint32_t my_slot = a.slot[row];
   wait_for_all_loads();
 
   // ---- small loads, ahead of the row so that they return ahead of it
